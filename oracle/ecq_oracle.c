@@ -1,0 +1,300 @@
+/*
+ * ecq_oracle.c -- plain, slow, CPU-only statement of what the ECQ-SGD hot path computes.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the checker the HIP library is compared with.  It
+ * shares no code, header, table or constant generator with the HIP path and is never linked
+ * into or called from it; only tests/, the smoke check and the benchmark's cpu_baseline leg
+ * may load it.
+ *
+ * The method is a randomised encoding, so the oracle is the algorithm taken step by step in
+ * the paper's order and notation (Wu et al., ICML 2018):
+ *
+ *   compensate   v = g + alpha*h                                   Section 4, Eq. (7)
+ *   scale        ||v|| taken as the l_inf norm of each bucket      Section 4, text after Eq. (8)
+ *   round        xi(|v_i|; ||v||) in {0,1/s,...,1}, sign kept      Section 4, Eq. (8)-(9)
+ *   encode       r = ceil(log2(2s+1)) bits per element + 1 scale   Section 4, paragraph on cost
+ *   accumulate   h <- beta*h + (g - g~)                            Section 4, Eq. (6)
+ *   aggregate    g~ = (1/P) sum_p g~_p                             Section 3/4, Eq. (4); Alg. 1
+ *
+ * Arithmetic: IEEE-754 binary32, round-to-nearest-even, every operation rounded on its own
+ * (build with -ffp-contract=off -fno-fast-math; no FMA, denormals kept).  The paper fixes
+ * neither the precision nor the operation order; the order below is this repository's
+ * convention ("parity unpinned" by the paper for the exact rounding sequence -- it is pinned
+ * instead by an exact-rational re-derivation in the tests).
+ *
+ * Points the paper leaves open and the reading taken here:
+ *   - norm: l_inf (max-abs) per bucket; a bucket is a run of `bucket` consecutive elements of
+ *     the flat per-worker vector, the last one possibly short.
+ *   - ||v|| = 0: every level 0, scale 0.
+ *   - |v_i| = ||v|| (outside every half-open interval of Eq. (9)): l = s, never rounds up.
+ *   - sgn: level is negated iff v_i < 0; level 0 has no sign.
+ *   - s*|v_i|/||v|| is evaluated as (|v_i| / ||v||) * s.
+ *   - dequantised value is ||v|| * fl(|q|/s) with the sign of q.
+ *   - randomness: one 32-bit word per element from Philox4x32-10 (Salmon et al., SC'11), its
+ *     top 24 bits give u = k * 2^-24 in [0,1); the level rounds up iff u < frac.
+ *   - word for (seed, step, worker p, element i): lane (i & 3) of the block with counter
+ *     (low32(i >> 2), p, step_lo, step_hi) and key (seed_lo, seed_hi).
+ *   - code = level + s in r bits, fields laid LSB-first in one contiguous bit stream per
+ *     worker row (stream bit j is bit (j & 7) of byte (j >> 3)); pad bits are zero.
+ *   - Eq. (4): sum over p = 0..P-1 in that order in binary32, then one division by (float)P.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- Philox4x32-10 ---------- */
+/* Counter-based generator of Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as
+ * 1, 2, 3" (SC'11): ten rounds of two 32x32->64 multiplies and a word permutation, the key
+ * bumped by the Weyl constants between rounds. */
+void ecq_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t prod0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t prod1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+        uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The one random word element i of worker p consumes at iteration `step`. */
+uint32_t ecq_oracle_word(uint64_t seed, uint64_t step, uint32_t p, uint64_t i)
+{
+    uint32_t ctr[4], key[2], out[4];
+    ctr[0] = (uint32_t)(i >> 2);
+    ctr[1] = p;
+    ctr[2] = (uint32_t)step;
+    ctr[3] = (uint32_t)(step >> 32);
+    key[0] = (uint32_t)seed;
+    key[1] = (uint32_t)(seed >> 32);
+    ecq_oracle_philox4x32_10(ctr, key, out);
+    return out[i & 3];
+}
+
+void ecq_oracle_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count,
+                      uint32_t *words)
+{
+    for (int64_t j = 0; j < count; ++j)
+        words[j] = ecq_oracle_word(seed, step, p, i0 + (uint64_t)j);
+}
+
+/* ---------------------------------------------------------------- scalar steps ----------- */
+
+/* r = ceil(log2(2s+1)): smallest r with 2^r >= 2s+1 (cost paragraph of Section 4). */
+int ecq_oracle_code_bits(int s)
+{
+    if (s < 1) return -1;
+    int r = 0;
+    while ((1L << r) < 2L * s + 1L) ++r;
+    return r;
+}
+
+/* Eq. (7): v = g + alpha*h. */
+float ecq_oracle_compensate(float g, float alpha, float h)
+{
+    float ah = alpha * h;
+    return g + ah;
+}
+
+/* l_inf norm of one bucket. */
+float ecq_oracle_bucket_scale(const float *v, int64_t len)
+{
+    float m = 0.0f;
+    for (int64_t i = 0; i < len; ++i) {
+        float a = fabsf(v[i]);
+        if (a > m) m = a;
+    }
+    return m;
+}
+
+/* Eq. (8)-(9) for one element: signed level q in [-s, s] given the bucket's scale and the
+ * element's random word. */
+int ecq_oracle_round(float v, float scale, int s, uint32_t word)
+{
+    if (scale == 0.0f) return 0;
+    float a = fabsf(v) / scale;          /* |v_i| / ||v||  in [0,1]                        */
+    float x = a * (float)s;              /* position on the grid {0,1,...,s}               */
+    float l = floorf(x);                 /* lower grid point, exact                        */
+    float frac = x - l;                  /* = s|v_i|/||v|| - l: probability of rounding up */
+    float u = (float)(word >> 8) * 0x1p-24f;   /* uniform on {0,...,2^24-1} * 2^-24, exact */
+    int m = (int)l + ((u < frac) ? 1 : 0);
+    if (m > s) m = s;
+    return (v < 0.0f) ? -m : m;
+}
+
+/* Eq. (8): g~_i = ||v|| * sgn * xi with xi = |q|/s. */
+float ecq_oracle_dequant(int q, float scale, int s)
+{
+    int m = q < 0 ? -q : q;
+    float xi = (float)m / (float)s;
+    float gt = scale * xi;
+    return (q < 0) ? -gt : gt;
+}
+
+/* Eq. (6): h' = beta*h + (g - g~). */
+float ecq_oracle_error(float beta, float h, float g, float gt)
+{
+    float bh = beta * h;
+    float d = g - gt;
+    return bh + d;
+}
+
+/* Levels for many random words at a fixed (v, scale): lets a test enumerate every outcome. */
+void ecq_oracle_round_words(float v, float scale, int s, const uint32_t *words, int64_t count,
+                            int8_t *q)
+{
+    for (int64_t j = 0; j < count; ++j) q[j] = (int8_t)ecq_oracle_round(v, scale, s, words[j]);
+}
+
+/* ---------------------------------------------------------------- encoding --------------- */
+
+int64_t ecq_oracle_row_bytes(int64_t n, int s)
+{
+    int r = ecq_oracle_code_bits(s);
+    if (r < 0 || n < 0) return -1;
+    return (n * (int64_t)r + 7) / 8;
+}
+
+/* Fixed-length encoding: element i's code c = q + s occupies stream bits [i*r, (i+1)*r). */
+void ecq_oracle_pack(const int8_t *q, int64_t n, int s, uint8_t *bytes)
+{
+    int r = ecq_oracle_code_bits(s);
+    memset(bytes, 0, (size_t)ecq_oracle_row_bytes(n, s));
+    for (int64_t i = 0; i < n; ++i) {
+        unsigned c = (unsigned)((int)q[i] + s);
+        for (int b = 0; b < r; ++b) {
+            int64_t j = i * r + b;
+            if ((c >> b) & 1u) bytes[j >> 3] |= (uint8_t)(1u << (j & 7));
+        }
+    }
+}
+
+void ecq_oracle_unpack(const uint8_t *bytes, int64_t n, int s, int8_t *q)
+{
+    int r = ecq_oracle_code_bits(s);
+    for (int64_t i = 0; i < n; ++i) {
+        unsigned c = 0;
+        for (int b = 0; b < r; ++b) {
+            int64_t j = i * r + b;
+            c |= (unsigned)((bytes[j >> 3] >> (j & 7)) & 1u) << b;
+        }
+        q[i] = (int8_t)((int)c - s);
+    }
+}
+
+/* ---------------------------------------------------------------- one bucket ------------- */
+
+/* One bucket of worker p at iteration `step` (Alg. 1: quantise g + alpha*h with the current
+ * h, then move h to its next value with the same g and g~).  i0 is the index, in the worker's
+ * flat vector, of g[0]/h[0].  gt may be NULL.  If update_h is 0, h is left as it is. */
+void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, uint32_t p,
+                            int s, float alpha, float beta, uint64_t seed, uint64_t step,
+                            int update_h, int8_t *q, float *scale_out, float *gt)
+{
+    float scale = 0.0f;
+    for (int64_t i = 0; i < len; ++i) {
+        float a = fabsf(ecq_oracle_compensate(g[i], alpha, h[i]));
+        if (a > scale) scale = a;
+    }
+    *scale_out = scale;
+    for (int64_t i = 0; i < len; ++i) {
+        float v = ecq_oracle_compensate(g[i], alpha, h[i]);
+        uint32_t w = ecq_oracle_word(seed, step, p, i0 + (uint64_t)i);
+        int qi = ecq_oracle_round(v, scale, s, w);
+        float gti = ecq_oracle_dequant(qi, scale, s);
+        q[i] = (int8_t)qi;
+        if (gt) gt[i] = gti;
+        if (update_h) h[i] = ecq_oracle_error(beta, h[i], g[i], gti);
+    }
+}
+
+/* ---------------------------------------------------------------- whole batch ------------ */
+
+/* All P workers, all buckets, one iteration.  g, h: [P][gh_stride]; q: [P][n] signed levels;
+ * scales: [P][nb]; gt (optional): [P][n].  Buckets are independent, so the loop over them may
+ * be split over threads without changing any result. */
+void ecq_oracle_batch_step(const float *g, float *h, int64_t n, int64_t gh_stride, int P,
+                           int bucket, int s, float alpha, float beta, uint64_t seed,
+                           uint64_t step, int update_h, int8_t *q, float *scales, float *gt,
+                           int threads)
+{
+    int64_t nb = (n + bucket - 1) / bucket;
+    int64_t units = (int64_t)P * nb;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t unit = 0; unit < units; ++unit) {
+        int64_t p = unit / nb, k = unit % nb;
+        int64_t e0 = k * (int64_t)bucket;
+        int64_t len = (n - e0 < bucket) ? (n - e0) : bucket;
+        ecq_oracle_bucket_step(g + p * gh_stride + e0, h + p * gh_stride + e0, len,
+                               (uint64_t)e0, (uint32_t)p, s, alpha, beta, seed, step, update_h,
+                               q + p * n + e0, scales + p * nb + k,
+                               gt ? gt + p * n + e0 : NULL);
+    }
+    (void)threads;
+}
+
+int ecq_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Eq. (6) alone, from an encoded message: h <- beta*h + (g - decode(codes, scales)). */
+void ecq_oracle_error_update_row(const float *g, const uint8_t *codes, const float *scales,
+                                 int64_t n, int bucket, int s, float beta, float *h)
+{
+    int r = ecq_oracle_code_bits(s);
+    for (int64_t i = 0; i < n; ++i) {
+        unsigned c = 0;
+        for (int b = 0; b < r; ++b) {
+            int64_t j = i * r + b;
+            c |= (unsigned)((codes[j >> 3] >> (j & 7)) & 1u) << b;
+        }
+        float gt = ecq_oracle_dequant((int)c - s, scales[i / bucket], s);
+        h[i] = ecq_oracle_error(beta, h[i], g[i], gt);
+    }
+}
+
+/* Eq. (4) / Alg. 1 "compute global gradients": decode every worker's message and average.
+ * codes: [P] rows code_stride BYTES apart; scales: [P] rows scale_stride floats apart. */
+void ecq_oracle_aggregate(const uint8_t *codes, int64_t code_stride, const float *scales,
+                          int64_t scale_stride, int P, int64_t n, int bucket, int s, float *out)
+{
+    int r = ecq_oracle_code_bits(s);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t i = 0; i < n; ++i) {
+        float acc = 0.0f;
+        for (int p = 0; p < P; ++p) {
+            const uint8_t *row = codes + (int64_t)p * code_stride;
+            unsigned c = 0;
+            for (int b = 0; b < r; ++b) {
+                int64_t j = i * r + b;
+                c |= (unsigned)((row[j >> 3] >> (j & 7)) & 1u) << b;
+            }
+            float gt = ecq_oracle_dequant((int)c - s, scales[(int64_t)p * scale_stride + i / bucket], s);
+            acc = acc + gt;
+        }
+        out[i] = acc / (float)P;
+    }
+}

@@ -1,0 +1,463 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without the HIP path.
+
+Citations: Wu et al., "Error Compensated Quantized SGD ..." (ICML 2018).  Each test names the
+passage that fixes the property it checks.  A plausible slip in the oracle (a dropped term, a
+wrong sign or index, g and v swapped, a fused operation) fails at least one of these.
+"""
+import math
+import os
+import random
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from tests.conftest import read_table
+from tests import exact_ref as X
+
+F32 = np.float32
+
+
+def f32(x):
+    return float(F32(x))
+
+
+# ------------------------------------------------------------------ Philox -----------------
+
+def test_philox_known_answers(golden_dir):
+    """Published known answers of Philox4x32-10 (Salmon et al., SC'11)."""
+    rows = read_table(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
+    assert len(rows) == 3
+    for row in rows:
+        vals = [int(t, 16) for t in row if t != "->"]
+        ctr, key, want = vals[:4], vals[4:6], vals[6:]
+        assert list(oracle.philox4x32_10(ctr, key)) == want
+        assert X.philox4x32_10(ctr, key) == want
+
+
+def test_philox_two_implementations_agree():
+    rng = random.Random(5)
+    for _ in range(200):
+        ctr = [rng.getrandbits(32) for _ in range(4)]
+        key = [rng.getrandbits(32) for _ in range(2)]
+        assert list(oracle.philox4x32_10(ctr, key)) == X.philox4x32_10(ctr, key)
+
+
+def test_word_indexing():
+    """Element i uses lane i&3 of the block whose counter is (i>>2, p, step_lo, step_hi)."""
+    seed, step, p = 0x0123456789ABCDEF, (7 << 32) | 9, 5
+    for i in (0, 1, 2, 3, 4, 7, 1023, (1 << 33) + 6):
+        blk = oracle.philox4x32_10([(i >> 2) & 0xFFFFFFFF, p, 9, 7], [0x89ABCDEF, 0x01234567])
+        assert oracle.word(seed, step, p, i) == int(blk[i & 3]) == X.word(seed, step, p, i)
+    ws = oracle.words(seed, step, p, 40, 24)
+    assert [int(w) for w in ws] == [X.word(seed, step, p, 40 + j) for j in range(24)]
+    # distinct (p, step, i>>2) give distinct counters, hence (almost surely) distinct streams
+    a = oracle.words(1, 0, 0, 0, 64)
+    assert not np.array_equal(a, oracle.words(1, 1, 0, 0, 64))
+    assert not np.array_equal(a, oracle.words(1, 0, 1, 0, 64))
+    assert not np.array_equal(a, oracle.words(2, 0, 0, 0, 64))
+    assert np.array_equal(a[8:], oracle.words(1, 0, 0, 8, 56))
+
+
+def test_philox_uniformity():
+    """Top-24-bit uniforms: mean 1/2 and variance 1/12 within a few standard errors."""
+    w = oracle.words(3, 11, 2, 0, 1 << 18)
+    u = (w >> 8).astype(np.float64) * 2.0 ** -24
+    n = u.size
+    assert abs(u.mean() - 0.5) < 5 * math.sqrt(1 / 12 / n)
+    assert abs(u.var() - 1 / 12) < 5 * math.sqrt(1 / 180 / n)
+    # every bit of the word is balanced
+    for b in range(32):
+        frac = ((w >> b) & 1).mean()
+        assert abs(frac - 0.5) < 5 * 0.5 / math.sqrt(n)
+
+
+# ------------------------------------------------------------------ code width -------------
+
+def test_code_bits_and_message_size(golden_dir):
+    """r = ceil(log2(2s+1)); message = 32 + d*r bits (Section 4, cost paragraph)."""
+    for s, r, d, bits in read_table(os.path.join(golden_dir, "code_bits.txt")):
+        s, r, d, bits = int(s), int(r), int(d), int(bits)
+        assert oracle.code_bits(s) == r == X.code_bits(s)
+        assert oracle.row_bytes(d, s) * 8 - (-(d * r) % 8) + 32 == bits
+    for s in range(1, 128):
+        r = oracle.code_bits(s)
+        assert (1 << r) >= 2 * s + 1 > (1 << (r - 1))
+        assert r == math.ceil(math.log2(2 * s + 1))
+    assert oracle.code_bits(0) < 0
+
+
+# ------------------------------------------------------------------ rounding rule ----------
+
+@pytest.mark.parametrize("s,num,den", [(1, 321, 1024), (2, 777, 1024), (4, 5, 8), (4, 1023, 1024),
+                                       (3, 100, 1024), (7, 300, 1024), (1, 1, 1 << 20)])
+def test_round_exhaustive_unbiased(s, num, den):
+    """Eq. (9): the level rounds up with probability s|v|/||v|| - l.  Every one of the 2^24
+    outcomes of the uniform is enumerated; with scale 1 and v a dyadic rational the
+    probability is a multiple of 2^-24, so the count is exact and E[g~] = v (Lemma 1,
+    unbiasedness) holds exactly whenever |q|/s is exact in binary32."""
+    v = -num / den                      # negative: also pins the sign handling
+    scale = 1.0
+    k = np.arange(1 << 24, dtype=np.uint32)
+    low = np.random.default_rng(s).integers(0, 256, k.size, dtype=np.uint32)
+    q = oracle.round_words(v, scale, s, (k << 8) | low).astype(np.int64)
+    x = Fraction(num, den) * s
+    l = x.numerator // x.denominator
+    frac = x - l
+    ups = int((q == -(l + 1)).sum())
+    downs = int((q == -l).sum())
+    assert ups + downs == 1 << 24
+    assert Fraction(ups, 1 << 24) == frac
+    # the "up" outcomes are exactly the uniforms below frac
+    assert np.array_equal(q == -(l + 1), k < ups)
+    mean = Fraction(0)
+    for lev, cnt in ((l, downs), (l + 1, ups)):
+        mean += Fraction(cnt, 1 << 24) * Fraction(float(oracle.dequant(-lev, scale, s)))
+    if s in (1, 2, 4):
+        assert mean == Fraction(-num, den)
+    else:
+        assert abs(mean - Fraction(-num, den)) <= Fraction(num, den) * Fraction(1, 1 << 23)
+
+
+def test_round_up_count_is_ceil_when_inexact():
+    """When frac * 2^24 is not an integer the count of 'up' outcomes is its ceiling, so the
+    bias is below 2^-24 * scale / s."""
+    rng = np.random.default_rng(0)
+    k = np.arange(1 << 24, dtype=np.uint32) << 8
+    for s in (1, 3, 7):
+        scale = f32(rng.uniform(0.5, 3.0))
+        v = f32(rng.uniform(1e-4, 0.01) * scale)      # small: frac has bits below 2^-24
+        a = X.rn32(Fraction(v) / Fraction(scale))
+        x = X.rn32(a * s)
+        l = x.numerator // x.denominator
+        frac = x - l
+        q = oracle.round_words(v, scale, s, k).astype(np.int64)
+        ups = int((q == l + 1).sum())
+        assert ups == math.ceil(frac * (1 << 24))
+        assert (frac * (1 << 24)).denominator != 1
+
+
+def test_round_boundaries_and_signs():
+    """|v| = ||v|| sits outside every half-open interval of Eq. (9): it maps to level s for
+    every random word.  Level 0 carries no sign; -0.0 is level 0."""
+    for s in (1, 3, 4, 7, 127):
+        for w in (0, 0xFFFFFFFF, 0x80000000, 0x000000FF):
+            assert oracle.round_level(2.5, 2.5, s, w) == s
+            assert oracle.round_level(-2.5, 2.5, s, w) == -s
+            assert oracle.round_level(0.0, 2.5, s, w) == 0
+            assert oracle.round_level(-0.0, 2.5, s, w) == 0
+            assert oracle.round_level(1.0, 0.0, s, w) == 0
+    # exact grid points never move, whatever the word
+    for s in (2, 4):
+        for j in range(s + 1):
+            for w in (0, 0xFFFFFFFF):
+                assert oracle.round_level(j / s, 1.0, s, w) == j
+    # word 0 -> u = 0: rounds up whenever frac > 0; word 2^32-1 -> u = 1 - 2^-24: up only if
+    # frac > u, impossible for frac on the 2^-24 grid below 1
+    assert oracle.round_level(0.3, 1.0, 1, 0) == 1
+    assert oracle.round_level(0.3, 1.0, 1, 0xFFFFFFFF) == 0
+    # only the top 24 bits of the word matter
+    assert oracle.round_level(0.3, 1.0, 1, 0x4CCCCC00) == oracle.round_level(0.3, 1.0, 1, 0x4CCCCCFF)
+    # u < frac is strict: frac = 0.5 exactly, u = 0.5 exactly -> stays down
+    assert oracle.round_level(0.5, 1.0, 1, 0x80000000) == 0
+    assert oracle.round_level(0.5, 1.0, 1, 0x7FFFFF00) == 1
+
+
+def test_ratio_never_exceeds_one():
+    """Correctly rounded |v|/scale <= 1 and (|v|/scale)*s <= s whenever |v| <= scale."""
+    rng = np.random.default_rng(1)
+    bits = rng.integers(0x00000001, 0x7F000000, 4000, dtype=np.uint32)
+    vals = bits.view(np.float32)
+    for s in (1, 3, 7, 127):
+        for a, b in zip(vals[::2], vals[1::2]):
+            lo, hi = (a, b) if a <= b else (b, a)
+            for w in (0, 0xFFFFFFFF):
+                assert 0 <= oracle.round_level(float(lo), float(hi), s, w) <= s
+
+
+# ------------------------------------------------------------------ exact re-derivation ----
+
+def _random_bucket(rng, n, kind):
+    if kind == "normal":
+        g = rng.standard_normal(n)
+        h = 0.3 * rng.standard_normal(n)
+    elif kind == "tiny":            # denormal range: flush-to-zero would change the result
+        g = rng.standard_normal(n) * 1e-41
+        h = rng.standard_normal(n) * 1e-41
+    elif kind == "mixed":
+        g = rng.standard_normal(n) * 10.0 ** rng.integers(-30, 20, n)
+        h = rng.standard_normal(n) * 10.0 ** rng.integers(-30, 20, n)
+    else:                           # zeros, negative zeros, repeated maxima
+        g = rng.choice([0.0, -0.0, 1.5, -1.5, 0.75], n)
+        h = rng.choice([0.0, -0.0, 0.25], n)
+    return g.astype(np.float32), h.astype(np.float32)
+
+
+@pytest.mark.parametrize("kind", ["normal", "tiny", "mixed", "lattice"])
+@pytest.mark.parametrize("s", [1, 3, 4, 7, 100])
+def test_bucket_matches_exact_rational_model(kind, s):
+    """Operation order and one-rounding-per-operation of Eq. (7), (8)-(9), (6), against exact
+    rationals rounded once per binary32 operation."""
+    rng = np.random.default_rng([len(kind), ord(kind[0]), s])
+    alpha, beta = f32(0.7), f32(0.9)
+    for trial in range(6):
+        n = int(rng.integers(1, 40))
+        g, h = _random_bucket(rng, n, kind)
+        i0, p, seed, step = 8 * int(rng.integers(0, 1 << 20)), int(rng.integers(0, 64)), 0xABCDEF12345, trial
+        q, scale, gt, hn = oracle.bucket_step(g, h, i0, p, s, alpha, beta, seed, step)
+        eq, escale, egt, ehn = X.bucket_step([float(x) for x in g], [float(x) for x in h], i0, p, s,
+                                             alpha, beta, seed, step)
+        assert [int(x) for x in q] == eq
+        assert Fraction(float(scale)) == escale
+        assert [Fraction(float(x)) for x in gt] == egt
+        assert [Fraction(float(x)) for x in hn] == ehn
+
+
+def test_scalar_steps_are_the_equations():
+    """Eq. (7), (8), (6) one at a time against the rational model (catches g/v swaps, a
+    missing alpha or beta, a flipped subtraction)."""
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        g, h, a, b, sc = (f32(t) for t in rng.standard_normal(5))
+        sc = abs(sc)
+        assert Fraction(float(oracle.compensate(g, a, h))) == X.rn32(Fraction(g) + X.rn32(Fraction(a) * Fraction(h)))
+        gt = f32(rng.standard_normal())
+        assert Fraction(float(oracle.error(b, h, g, gt))) == X.rn32(
+            X.rn32(Fraction(b) * Fraction(h)) + X.rn32(Fraction(g) - Fraction(gt)))
+        s = int(rng.integers(1, 128))
+        q = int(rng.integers(-s, s + 1))
+        want = X.rn32(Fraction(sc) * X.rn32(Fraction(abs(q), s)))
+        assert Fraction(float(oracle.dequant(q, sc, s))) == (-want if q < 0 else want)
+
+
+# ------------------------------------------------------------------ invariants -------------
+
+def _run(P, n, bucket, s, alpha, beta, iters, seed=1, gscale=1.0, rng_seed=0, keep=False):
+    rng = np.random.default_rng(rng_seed)
+    h = np.zeros((P, n), np.float32)
+    log = []
+    for t in range(iters):
+        g = (gscale * rng.standard_normal((P, n))).astype(np.float32)
+        h_before = h.copy()
+        q, scales, gt = oracle.batch_step(g, h, bucket, s, alpha, beta, seed, t, want_gt=True)
+        log.append((g, h_before, q, scales, gt, h.copy()))
+    return log
+
+
+@pytest.mark.parametrize("s,bucket,n", [(1, 512, 4096), (3, 64, 1000), (7, 8, 250), (4, 4096, 5000)])
+def test_code_range_error_bound_and_max_element(s, bucket, n):
+    """Levels lie in [-s, s] (codebook of Eq. (8)); |v_i - g~_i| <= ||v||/s because the value
+    moves to an end of its interval of width ||v||/s (Eq. (9)); the element attaining the norm
+    is reproduced exactly (its rounding-up probability is 0)."""
+    alpha, beta = f32(1.0), f32(0.9)
+    for g, h0, q, scales, gt, h1 in _run(3, n, bucket, s, alpha, beta, 4):
+        assert q.min() >= -s and q.max() <= s
+        v = g + F32(alpha) * h0
+        nb = scales.shape[1]
+        for p in range(g.shape[0]):
+            for k in range(nb):
+                sl = slice(k * bucket, min(n, (k + 1) * bucket))
+                vv = v[p, sl]
+                assert scales[p, k] == np.abs(vv).max()
+                err = np.abs(vv.astype(np.float64) - gt[p, sl])
+                assert err.max() <= float(scales[p, k]) / s * (1 + 4 * 2.0 ** -24)
+                imax = int(np.abs(vv).argmax())
+                assert abs(int(q[p, sl][imax])) == s
+                assert gt[p, sl][imax] == vv[imax]
+                assert np.all(np.sign(gt[p, sl]) * np.sign(vv) >= 0)
+
+
+def test_last_bucket_is_short_and_buckets_are_independent():
+    """A bucket is a run of consecutive elements; the last may be short and takes its scale
+    from the elements that exist.  Changing one bucket leaves the others' levels alone."""
+    rng = np.random.default_rng(3)
+    P, n, bucket, s = 2, 1000, 64, 3
+    g = rng.standard_normal((P, n)).astype(np.float32)
+    h = np.zeros_like(g)
+    q, scales, _ = oracle.batch_step(g, h.copy(), bucket, s, 1.0, 1.0, 9, 0)
+    assert scales.shape == (P, 16)
+    assert scales[0, 15] == np.abs(g[0, 960:]).max()
+    g2 = g.copy()
+    g2[0, 70] = 100.0
+    q2, scales2, _ = oracle.batch_step(g2, h.copy(), bucket, s, 1.0, 1.0, 9, 0)
+    same = np.ones(n, bool)
+    same[64:128] = False
+    assert np.array_equal(q[0, same], q2[0, same]) and np.array_equal(q[1], q2[1])
+    assert scales2[0, 1] == 100.0
+    # a bucket computed on its own, with its offset, equals its slice of the batch
+    qb, sb, _, _ = oracle.bucket_step(g[1, 128:192], h[1, 128:192], 128, 1, s, 1.0, 1.0, 9, 0)
+    assert np.array_equal(qb, q[1, 128:192]) and sb == scales[1, 2]
+
+
+def test_deterministic_cases():
+    """Inputs on the quantisation grid are reproduced whatever the random words; with h = 0 and
+    alpha = beta = 1 the error stays 0.  An all-zero bucket gives scale 0, levels 0,
+    h' = beta*h + g.  A one-element bucket is its own norm."""
+    for s in (1, 2, 4):
+        M = 3.0
+        levels = np.arange(-s, s + 1)
+        g = np.tile((M * levels / s).astype(np.float32), 5)[None, :]
+        for seed in (1, 2, 3):
+            h = np.zeros_like(g)
+            q, scales, gt = oracle.batch_step(g, h, 8 * len(levels), s, 1.0, 1.0, seed, 0, want_gt=True)
+            assert np.array_equal(gt, g) and np.all(h == 0) and scales[0, 0] == M
+            assert np.array_equal(q[0], np.tile(levels, 5))
+    g = np.zeros((1, 16), np.float32)
+    h = np.full((1, 16), 0.0, np.float32)
+    q, scales, gt = oracle.batch_step(g, h, 8, 3, 1.0, 0.5, 1, 0, want_gt=True)
+    assert not q.any() and not scales.any() and not gt.any() and not h.any()
+    g = np.array([[0.25, -4.0, 7.5]], np.float32)
+    h = np.zeros_like(g)
+    q, scales, gt = oracle.batch_step(g, h, 1, 7, 1.0, 1.0, 5, 3, want_gt=True)
+    assert list(q[0]) == [7, -7, 7] and np.array_equal(gt, g) and np.array_equal(scales[0], np.abs(g[0]))
+
+
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.9), (0.2, 0.9), (0.01, 1.0), (1.0, 1.0)])
+def test_error_recursion_closed_forms(alpha, beta):
+    """Eq. (5): h(t) = sum_{t'<t} beta^(t-1-t') (g(t') - g~(t')), and the supplement's
+    re-organisation (proof of Lemma 2): h(t) = -sum_{t'<t} (beta-alpha)^(t-t'-1) eps(t') with
+    eps = g~ - (g + alpha h) (Eq. (10)); both recomputed in float64 from the logged g, g~."""
+    alpha, beta = f32(alpha), f32(beta)
+    log = _run(2, 600, 64, 3, alpha, beta, 8, gscale=0.5)
+    T = len(log)
+    a64, b64 = float(alpha), float(beta)
+    for t in range(1, T + 1):
+        h_t = log[t - 1][5].astype(np.float64)
+        closed = np.zeros_like(h_t)
+        eps_form = np.zeros_like(h_t)
+        for tp in range(t):
+            g, h0, q, scales, gt, h1 = log[tp]
+            closed += b64 ** (t - 1 - tp) * (g.astype(np.float64) - gt)
+            eps = gt.astype(np.float64) - (g.astype(np.float64) + a64 * h0.astype(np.float64))
+            eps_form -= (b64 - a64) ** (t - tp - 1) * eps
+        tol = 1e-6 * max(1.0, np.abs(h_t).max())
+        assert np.abs(h_t - closed).max() <= tol
+        assert np.abs(h_t - eps_form).max() <= tol
+    assert np.abs(log[-1][5]).max() > 1e-3      # the recursion is not vacuous
+
+
+def test_special_cases_qsgd_ternary_last_step():
+    """alpha = 0: the levels do not depend on h (QSGD, Section 5.2).  s = 1: ternary
+    {-||v||, 0, +||v||}.  beta = 0: h' = g - g~ (feedback from the last step only)."""
+    rng = np.random.default_rng(4)
+    P, n, bucket = 2, 512, 128
+    g = rng.standard_normal((P, n)).astype(np.float32)
+    h_rand = rng.standard_normal((P, n)).astype(np.float32)
+    q0, sc0, _ = oracle.batch_step(g, np.zeros_like(g), bucket, 4, 0.0, 1.0, 7, 2)
+    q1, sc1, _ = oracle.batch_step(g, h_rand.copy(), bucket, 4, 0.0, 1.0, 7, 2)
+    assert np.array_equal(q0, q1) and np.array_equal(sc0, sc1)
+    qa, _, _ = oracle.batch_step(g, h_rand.copy(), bucket, 4, 1.0, 1.0, 7, 2)
+    assert not np.array_equal(q0, qa)
+    q, sc, gt = oracle.batch_step(g, np.zeros_like(g), bucket, 1, 1.0, 1.0, 7, 2, want_gt=True)
+    big = np.repeat(sc, bucket, axis=1)
+    assert np.all((gt == 0) | (gt == big) | (gt == -big))
+    h = h_rand.copy()
+    q, sc, gt = oracle.batch_step(g, h, bucket, 4, 1.0, 0.0, 7, 2, want_gt=True)
+    assert np.array_equal(h, g - gt)
+    # update_h = 0 leaves h alone
+    h = h_rand.copy()
+    oracle.batch_step(g, h, bucket, 4, 1.0, 0.5, 7, 2, update_h=False)
+    assert np.array_equal(h, h_rand)
+
+
+def test_ternary_probability_statistical():
+    """s = 1 with the l_inf norm: P(|level| = 1) = |v|/||v|| (the ternary quantiser the paper
+    cites); checked over many iterations' independent words.  Also the per-element variance
+    (||v||/s)^2 f(1-f) summed over the bucket."""
+    n, iters = 256, 400
+    rng = np.random.default_rng(6)
+    g = rng.uniform(-1, 1, n).astype(np.float32)
+    g[0] = 1.0
+    hits = np.zeros(n)
+    sq = 0.0
+    for t in range(iters):
+        q, sc, gt, _ = oracle.bucket_step(g, np.zeros(n, np.float32), 0, 0, 1, 1.0, 1.0, 77, t)
+        hits += np.abs(q)
+        sq += ((gt.astype(np.float64) - g) ** 2).sum()
+    prob = np.abs(g.astype(np.float64))
+    se = np.sqrt(prob * (1 - prob) / iters) + 1e-9
+    assert np.all(np.abs(hits / iters - prob) < 5 * se + 1e-12)
+    var = (prob * (1 - prob)).sum()
+    assert abs(sq / iters - var) < 0.1 * var
+
+
+def test_resume_is_bit_identical():
+    """The random stream is a pure function of (seed, step, worker, element): running T steps
+    equals running k steps, saving h, and running the remaining T-k."""
+    rng = np.random.default_rng(8)
+    gs = [rng.standard_normal((2, 300)).astype(np.float32) for _ in range(6)]
+    h = np.zeros((2, 300), np.float32)
+    qs = [oracle.batch_step(g, h, 64, 3, 1.0, 0.9, 5, t)[0] for t, g in enumerate(gs)]
+    h2 = np.zeros((2, 300), np.float32)
+    for t in range(3):
+        oracle.batch_step(gs[t], h2, 64, 3, 1.0, 0.9, 5, t)
+    saved = h2.copy()
+    qs2 = [oracle.batch_step(gs[t], saved, 64, 3, 1.0, 0.9, 5, t)[0] for t in range(3, 6)]
+    assert all(np.array_equal(a, b) for a, b in zip(qs[3:], qs2))
+    assert np.array_equal(saved, h)
+
+
+# ------------------------------------------------------------------ encoding ---------------
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 7, 8, 20, 40, 100, 127])
+def test_pack_is_lsb_first_bitstream(s):
+    """r bits per element in one contiguous LSB-first stream: the packed row read as a
+    little-endian integer is sum_i (q_i + s) << (i r); pad bits are zero; unpack inverts."""
+    rng = np.random.default_rng(s)
+    r = oracle.code_bits(s)
+    for n in (1, 2, 3, 5, 7, 8, 9, 15, 16, 17, 63, 64, 65, 200):
+        q = rng.integers(-s, s + 1, n).astype(np.int8)
+        packed = oracle.pack(q, s)
+        assert packed.size == (n * r + 7) // 8 == oracle.row_bytes(n, s)
+        assert bytes(packed) == X.pack([int(x) for x in q], s)
+        assert int.from_bytes(bytes(packed), "little") >> (n * r) == 0
+        assert np.array_equal(oracle.unpack(packed, n, s), q)
+        assert X.unpack(bytes(packed), n, s) == [int(x) for x in q]
+    # explicit small case, r = 2: codes 0,1,2,1 -> bits 00 01 10 01 LSB-first = 0b01100100
+    assert list(oracle.pack(np.array([-1, 0, 1, 0], np.int8), 1)) == [0b01100100]
+    # r = 3, s = 3: codes 6,0,3 -> 110 | 000<<3 | 011<<6 = 0b0_1100_0110 -> bytes C6 00
+    assert list(oracle.pack(np.array([3, -3, 0], np.int8), 3)) == [0xC6, 0x00]
+
+
+# ------------------------------------------------------------------ aggregation ------------
+
+@pytest.mark.parametrize("P", [1, 3, 4, 8])
+def test_aggregate_is_the_mean(P):
+    """Eq. (4): g~ = (1/P) sum_p g~_p, against a float64 mean of the per-worker dequantised
+    vectors; P = 1 returns the single worker's g~ bit for bit."""
+    rng = np.random.default_rng(P)
+    n, bucket, s = 777, 64, 3
+    g = rng.standard_normal((P, n)).astype(np.float32)
+    h = np.zeros_like(g)
+    q, scales, gt = oracle.batch_step(g, h, bucket, s, 1.0, 1.0, 3, 0, want_gt=True)
+    codes = oracle.pack_rows(q, s)
+    out = oracle.aggregate(codes, scales, n, bucket, s)
+    mean = gt.astype(np.float64).mean(axis=0)
+    assert np.abs(out - mean).max() <= 1e-6 * np.abs(mean).max()
+    if P == 1:
+        assert np.array_equal(out, gt[0])
+    # exact model of the summation order: p = 0..P-1, then one division
+    acc = np.zeros(n, np.float32)
+    for p in range(P):
+        acc = acc + gt[p]
+    assert np.array_equal(out, acc / F32(P))
+    # strided rows
+    codes2 = np.zeros((P, codes.shape[1] + 5), np.uint8)
+    codes2[:, : codes.shape[1]] = codes
+    scales2 = np.zeros((P, scales.shape[1] + 3), np.float32)
+    scales2[:, : scales.shape[1]] = scales
+    assert np.array_equal(oracle.aggregate(codes2, scales2, n, bucket, s), out)
+
+
+def test_error_update_from_message_equals_fused_step():
+    """Eq. (6) applied to the decoded message reproduces the fused step's h."""
+    rng = np.random.default_rng(11)
+    n, bucket, s = 500, 40, 7
+    g = rng.standard_normal((1, n)).astype(np.float32)
+    h0 = rng.standard_normal((1, n)).astype(np.float32)
+    h = h0.copy()
+    q, scales, _ = oracle.batch_step(g, h, bucket, s, 0.5, 0.8, 3, 1)
+    h2 = h0[0].copy()
+    oracle.error_update_row(g[0], oracle.pack(q[0], s), scales[0], bucket, s, 0.8, h2)
+    assert np.array_equal(h2, h[0])
