@@ -1,0 +1,169 @@
+/*
+ * ecq.h -- C ABI of the ECQ-SGD hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, on one GPU and with the P data-parallel workers laid out as a
+ * resident batch, the per-iteration compression codec of Error Compensated Quantized SGD
+ * (Wu, Huang, Huang, Zhang, ICML 2018), Section 4:
+ *
+ *     v   = g + alpha*h                          compensate             Eq. (7)
+ *     g~  = ||v|| * sgn(v) * xi(|v|; ||v||)      stochastic quantiser   Eq. (8)-(9)
+ *     encode g~ as r = ceil(log2(2s+1)) bits per element + one fp32 scale per bucket
+ *     h  <- beta*h + (g - g~)                    error accumulator      Eq. (6)
+ *     g~_avg = (1/P) sum_p g~_p                  aggregation            Eq. (4), Alg. 1
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
+ *    nothing, frees nothing and keeps no state between calls: the state of the method is the
+ *    caller's `h` plus the (seed, step) pair; the caller passes step = t at iteration t.
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream) and returns without synchronising.
+ *  - Return value: ECQ_OK (0) or a negative ecq_status.  Argument errors are found on the
+ *    host before anything is launched and leave all outputs untouched.
+ *  - Non-finite inputs give undefined results (no error).
+ *
+ * Data layout (P = workers, N = n elements per worker, b = bucket, nb = ceil(N/b))
+ *  - g, h   : float32 [P][gh_stride], row p = worker p's flat gradient / accumulated error.
+ *  - scales : float32 [P][scale_stride]; scales[p][k] = l_inf norm of bucket k of worker p,
+ *             bucket k = elements [k*b, min((k+1)*b, N)).
+ *  - codes  : bytes [P][code_stride]; row p is one contiguous bit stream, element i's code
+ *             c = level + s (0..2s) in stream bits [i*r, (i+1)*r), stream bit j = bit (j & 7)
+ *             of byte (j >> 3).  The first ecq_row_bytes() bytes of every row are written in
+ *             full (pad bits zero); bytes from there to code_stride are never touched.
+ *
+ * Arithmetic: IEEE binary32, round to nearest even, one rounding per operation (no fused
+ * multiply-add), denormals kept.  Randomness: one word per element of Philox4x32-10
+ * (Salmon et al., SC'11): word (i & 3) of the block with counter
+ * (low32(i >> 2), p, step_lo, step_hi) and key (seed_lo, seed_hi); its top 24 bits form the
+ * uniform u in [0,1) that decides the rounding direction of Eq. (9).  Results therefore do
+ * not depend on launch geometry.
+ */
+#ifndef ECQ_H
+#define ECQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ECQ_OK = 0,
+    ECQ_ERR_NULL = -1,    /* a required pointer is NULL                                   */
+    ECQ_ERR_SHAPE = -2,   /* n <= 0, n > ECQ_MAX_N or workers <= 0 or workers > 65535      */
+    ECQ_ERR_LEVELS = -3,  /* s outside 1..127                                             */
+    ECQ_ERR_BUCKET = -4,  /* bucket not a positive multiple of 8                          */
+    ECQ_ERR_STRIDE = -5,  /* a row stride too small for its row or not suitably divisible */
+    ECQ_ERR_ALIGN = -6,   /* a base pointer is not aligned as documented                  */
+    ECQ_ERR_LAUNCH = -7,  /* the HIP runtime refused a launch                             */
+    ECQ_ERR_PARAM = -8    /* alpha or beta out of range, or an unknown tuning value        */
+} ecq_status;
+
+/* Largest n: element index i enters the Philox counter as low32(i >> 2). */
+#define ECQ_MAX_N (((int64_t)1) << 34)
+
+typedef struct {
+    int64_t n;            /* N: elements per worker, 1..ECQ_MAX_N                           */
+    int32_t workers;      /* P: 1..65535                                                   */
+    int32_t bucket;       /* b: positive multiple of 8 (every bucket starts on a byte)      */
+    int32_t s;            /* non-zero quantisation levels, 1..127 (r = 2..8 bits)          */
+    int32_t reserved;     /* must be 0                                                     */
+    int64_t gh_stride;    /* floats between worker rows of g and of h: >= n, multiple of 4 */
+    int64_t code_stride;  /* BYTES between worker rows of codes: >= row bytes, mult. of 4  */
+    int64_t scale_stride; /* floats between worker rows of scales: >= nb                   */
+} ecq_shape;
+
+/* Optional launch tuning; pass NULL for the defaults.  Results never depend on it. */
+typedef struct {
+    int32_t path;          /* 0 = choose; 1 = bucket-in-registers single pass;
+                              2 = two-pass (norm kernel, then quantise kernel)             */
+    int32_t waves_per_bucket; /* 0 = choose; else 1,2,4,8,16 (path 1, buckets >= 256)      */
+    int32_t block_threads; /* 0 = choose; else 64..1024, multiple of 64                    */
+    int32_t reserved;      /* must be 0                                                    */
+} ecq_tuning;
+
+/* r = ceil(log2(2s+1)) bits per encoded element (Section 4, cost paragraph);
+ * negative ecq_status for s outside 1..127. */
+int ecq_code_bits(int s);
+
+/* *bytes = ceil(n*r/8), the encoded length of one worker row without its scales. */
+int ecq_row_bytes(int64_t n, int s, int64_t *bytes);
+
+/* *nb = ceil(n / bucket). */
+int ecq_num_buckets(int64_t n, int bucket, int64_t *nb);
+
+/* Host-side check of a shape; what every entry point runs first. */
+int ecq_check_shape(const ecq_shape *shape);
+
+/*
+ * Eq. (7)-(9) and the fixed-length encoding: quantise v = g + alpha*h of every worker.
+ *   g, h   in   device, [P][gh_stride] float32, 16-byte aligned; neither is written.
+ *   alpha  in   compensation coefficient, finite, >= 0.
+ *   seed, step  select the random stream; use step = iteration number.
+ *   codes  out  device, [P][code_stride] bytes, 4-byte aligned.
+ *   scales out  device, [P][scale_stride] float32.
+ */
+int ecq_quantize(const ecq_shape *shape, const float *g, const float *h, float alpha,
+                 uint64_t seed, uint64_t step, uint8_t *codes, float *scales, void *stream);
+
+/*
+ * Eq. (6): h <- beta*h + (g - g~), with g~ decoded from (codes, scales) as
+ * scales[p][i/b] * fl(|q|/s) carrying the sign of q = code - s (Eq. (8)).
+ *   g      in      device, [P][gh_stride] float32, 16-byte aligned.
+ *   codes, scales  in, as written by ecq_quantize.
+ *   beta   in      time-decaying factor, 0 <= beta <= 1.
+ *   h      in/out  device, [P][gh_stride] float32, 16-byte aligned, updated in place.
+ */
+int ecq_error_update(const ecq_shape *shape, const float *g, const uint8_t *codes,
+                     const float *scales, float beta, float *h, void *stream);
+
+/*
+ * The per-worker part of one iteration of Alg. 1 in a single pass over g and h: quantise
+ * g + alpha*h with the current h (Eq. (7)-(9)), encode, and move h to its next value
+ * (Eq. (6)).  Bit-identical to ecq_quantize followed by ecq_error_update.  h is updated in
+ * place; g is not written.
+ */
+int ecq_quantize_update(const ecq_shape *shape, const float *g, float *h, float alpha,
+                        float beta, uint64_t seed, uint64_t step, uint8_t *codes, float *scales,
+                        void *stream);
+
+/* The same with explicit launch tuning (NULL = defaults); used to show that results do not
+ * depend on launch geometry and to sweep configurations. */
+int ecq_quantize_update_ex(const ecq_shape *shape, const float *g, float *h, float alpha,
+                           float beta, uint64_t seed, uint64_t step, uint8_t *codes,
+                           float *scales, const ecq_tuning *tuning, void *stream);
+
+/*
+ * Eq. (4) / Alg. 1 "compute global gradients": out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, the
+ * sum taken in the order p = 0, 1, ..., P-1 in binary32, followed by one division by
+ * (float)P.  gh_stride of the shape is not used.
+ *   codes, scales  in   all P workers' messages.
+ *   out            out  device, [n] float32, 16-byte aligned.
+ */
+int ecq_dequant_aggregate(const ecq_shape *shape, const uint8_t *codes, const float *scales,
+                          float *out, void *stream);
+
+/*
+ * The random words of Eq. (9)'s rounding decision, for inspection: words[j] is the word
+ * element i0 + j of worker p consumes at iteration `step`.  words: device, [count] uint32.
+ */
+int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count,
+                     uint32_t *words, void *stream);
+
+/*
+ * Bandwidth calibration, not part of the method: out[i] = a[i] + b[i] over n floats
+ * (two reads and one write of 4 bytes per element, the same traffic mix as the fused pass),
+ * and a plain copy out[i] = a[i].  All pointers device, 16-byte aligned.
+ */
+int ecq_calib_add(const float *a, const float *b, float *out, int64_t n, void *stream);
+int ecq_calib_copy(const float *a, float *out, int64_t n, void *stream);
+
+/* Static, human-readable text for a status value. */
+const char *ecq_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int ecq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECQ_H */

@@ -1,0 +1,158 @@
+"""ctypes binding of include/ecq.h: same names, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch is used for device memory and streams, nothing
+else); each wrapper passes raw device pointers and the current HIP stream to the library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG_DIR, "libecq.so")
+
+
+class EcqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Shape(C.Structure):
+    """Mirror of ecq_shape."""
+    _fields_ = [("n", C.c_int64), ("workers", C.c_int32), ("bucket", C.c_int32), ("s", C.c_int32),
+                ("reserved", C.c_int32), ("gh_stride", C.c_int64), ("code_stride", C.c_int64),
+                ("scale_stride", C.c_int64)]
+
+    @classmethod
+    def packed(cls, n: int, workers: int, bucket: int, s: int) -> "Shape":
+        """Tightest legal strides: gh rounded up to 4 floats, codes to 4 bytes."""
+        return cls(n=n, workers=workers, bucket=bucket, s=s, reserved=0,
+                   gh_stride=(n + 3) // 4 * 4, code_stride=(row_bytes(n, s) + 3) // 4 * 4,
+                   scale_stride=num_buckets(n, bucket))
+
+
+class Tuning(C.Structure):
+    """Mirror of ecq_tuning."""
+    _fields_ = [("path", C.c_int32), ("waves_per_bucket", C.c_int32), ("block_threads", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(_LIB_PATH)
+        vp, f, u64, i64 = C.c_void_p, C.c_float, C.c_uint64, C.c_int64
+        shp = C.POINTER(Shape)
+        L.ecq_code_bits.argtypes = [C.c_int]
+        L.ecq_row_bytes.argtypes = [i64, C.c_int, C.POINTER(i64)]
+        L.ecq_num_buckets.argtypes = [i64, C.c_int, C.POINTER(i64)]
+        L.ecq_check_shape.argtypes = [shp]
+        L.ecq_quantize.argtypes = [shp, vp, vp, f, u64, u64, vp, vp, vp]
+        L.ecq_error_update.argtypes = [shp, vp, vp, vp, f, vp, vp]
+        L.ecq_quantize_update.argtypes = [shp, vp, vp, f, f, u64, u64, vp, vp, vp]
+        L.ecq_quantize_update_ex.argtypes = [shp, vp, vp, f, f, u64, u64, vp, vp, C.POINTER(Tuning), vp]
+        L.ecq_dequant_aggregate.argtypes = [shp, vp, vp, vp, vp]
+        L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
+        L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
+        L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
+        L.ecq_status_string.argtypes = [C.c_int]
+        L.ecq_status_string.restype = C.c_char_p
+        L.ecq_version.argtypes = []
+        for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
+                     "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
+                     "ecq_dequant_aggregate", "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
+                     "ecq_version"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ecq_status_string(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise EcqError(status, where)
+
+
+def code_bits(s: int) -> int:
+    r = lib().ecq_code_bits(s)
+    if r < 0:
+        raise EcqError(r, "ecq_code_bits")
+    return r
+
+
+def row_bytes(n: int, s: int) -> int:
+    out = C.c_int64(0)
+    _check(lib().ecq_row_bytes(n, s, C.byref(out)), "ecq_row_bytes")
+    return out.value
+
+
+def num_buckets(n: int, bucket: int) -> int:
+    out = C.c_int64(0)
+    _check(lib().ecq_num_buckets(n, bucket, C.byref(out)), "ecq_num_buckets")
+    return out.value
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(stream)
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def ecq_quantize(shape: Shape, g, h, alpha: float, seed: int, step: int, codes, scales, stream=None) -> None:
+    _check(lib().ecq_quantize(C.byref(shape), _ptr(g), _ptr(h), alpha, seed, step, _ptr(codes), _ptr(scales),
+                              _stream(stream)), "ecq_quantize")
+
+
+def ecq_error_update(shape: Shape, g, codes, scales, beta: float, h, stream=None) -> None:
+    _check(lib().ecq_error_update(C.byref(shape), _ptr(g), _ptr(codes), _ptr(scales), beta, _ptr(h),
+                                  _stream(stream)), "ecq_error_update")
+
+
+def ecq_quantize_update(shape: Shape, g, h, alpha: float, beta: float, seed: int, step: int, codes, scales,
+                        stream=None) -> None:
+    _check(lib().ecq_quantize_update(C.byref(shape), _ptr(g), _ptr(h), alpha, beta, seed, step, _ptr(codes),
+                                     _ptr(scales), _stream(stream)), "ecq_quantize_update")
+
+
+def ecq_quantize_update_ex(shape: Shape, g, h, alpha: float, beta: float, seed: int, step: int, codes, scales,
+                           tuning: Tuning | None = None, stream=None) -> None:
+    _check(lib().ecq_quantize_update_ex(C.byref(shape), _ptr(g), _ptr(h), alpha, beta, seed, step, _ptr(codes),
+                                        _ptr(scales), C.byref(tuning) if tuning is not None else None,
+                                        _stream(stream)), "ecq_quantize_update_ex")
+
+
+def ecq_dequant_aggregate(shape: Shape, codes, scales, out, stream=None) -> None:
+    _check(lib().ecq_dequant_aggregate(C.byref(shape), _ptr(codes), _ptr(scales), _ptr(out), _stream(stream)),
+           "ecq_dequant_aggregate")
+
+
+def ecq_philox_words(seed: int, step: int, p: int, i0: int, count: int, words, stream=None) -> None:
+    _check(lib().ecq_philox_words(seed, step, p, i0, count, _ptr(words), _stream(stream)), "ecq_philox_words")
+
+
+def ecq_calib_add(a, b, out, n: int, stream=None) -> None:
+    _check(lib().ecq_calib_add(_ptr(a), _ptr(b), _ptr(out), n, _stream(stream)), "ecq_calib_add")
+
+
+def ecq_calib_copy(a, out, n: int, stream=None) -> None:
+    _check(lib().ecq_calib_copy(_ptr(a), _ptr(out), n, _stream(stream)), "ecq_calib_copy")

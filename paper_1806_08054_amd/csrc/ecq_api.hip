@@ -1,0 +1,254 @@
+// C ABI of the ECQ-SGD codec: argument checks on the host, then kernel launches.
+// Declarations and the contract of every entry point are in include/ecq.h.
+#include <cmath>
+#include <cstdint>
+
+#include "ecq_internal.hpp"
+
+namespace ecq {
+
+static int code_bits(int s)
+{
+    if (s < 1 || s > 127) return ECQ_ERR_LEVELS;
+    int r = 0;
+    while ((1 << r) < 2 * s + 1) ++r;                         // r = ceil(log2(2s+1))
+    return r;
+}
+
+static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static int check_shape(const ecq_shape *sh)
+{
+    if (!sh) return ECQ_ERR_NULL;
+    if (sh->n <= 0 || sh->n > ECQ_MAX_N || sh->workers <= 0 || sh->workers > 65535) return ECQ_ERR_SHAPE;
+    if (sh->s < 1 || sh->s > 127) return ECQ_ERR_LEVELS;
+    if (sh->bucket <= 0 || (sh->bucket & 7) != 0) return ECQ_ERR_BUCKET;
+    if (sh->reserved != 0) return ECQ_ERR_PARAM;
+    const int r = code_bits(sh->s);
+    const int64_t row_bytes = (sh->n * r + 7) / 8;
+    const int64_t nb = (sh->n + sh->bucket - 1) / sh->bucket;
+    if (sh->gh_stride < sh->n || (sh->gh_stride & 3) != 0) return ECQ_ERR_STRIDE;
+    if (sh->code_stride < row_bytes || (sh->code_stride & 3) != 0) return ECQ_ERR_STRIDE;
+    if (sh->scale_stride < nb) return ECQ_ERR_STRIDE;
+    return ECQ_OK;
+}
+
+static Args make_args(const ecq_shape &sh)
+{
+    Args a{};
+    a.n = sh.n;
+    a.nb = (sh.n + sh.bucket - 1) / sh.bucket;
+    a.gh_stride = sh.gh_stride;
+    a.code_stride = sh.code_stride;
+    a.scale_stride = sh.scale_stride;
+    a.r = code_bits(sh.s);
+    a.row_bytes = (sh.n * a.r + 7) / 8;
+    a.workers = sh.workers;
+    a.bucket = sh.bucket;
+    a.s = sh.s;
+    return a;
+}
+
+static void set_stream_key(Args &a, uint64_t seed, uint64_t step)
+{
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.step_lo = (uint32_t)step;
+    a.step_hi = (uint32_t)(step >> 32);
+}
+
+// Chooses how a bucket is mapped to lanes.  Single pass when the bucket is a power of two of
+// 8..128 elements (a group of lanes inside one wave) or when 256 <= bucket <= 32768 (a team of
+// up to 16 waves holding up to 8 float4 per lane); two passes otherwise.
+int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
+{
+    Plan pl{};
+    const int b = sh.bucket;
+    int path = 0, waves = 0, threads = 0;
+    if (tu) {
+        if (tu->reserved != 0) return ECQ_ERR_PARAM;
+        path = tu->path;
+        waves = tu->waves_per_bucket;
+        threads = tu->block_threads;
+        if (path < 0 || path > 2) return ECQ_ERR_PARAM;
+        if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8 && waves != 16) return ECQ_ERR_PARAM;
+        if (threads != 0 && (threads < 64 || threads > 1024 || (threads & 63) != 0)) return ECQ_ERR_PARAM;
+    }
+    const bool pow2 = (b & (b - 1)) == 0;
+    const bool small_ok = pow2 && b >= 8 && b <= 128;
+    const bool team_ok = b >= 256 && b <= 32768;
+    if (path == 0) path = (small_ok || team_ok) ? 1 : 2;
+    if (path == 1 && !(small_ok || team_ok)) return ECQ_ERR_PARAM;
+    pl.path = path;
+    pl.block_threads = 256;
+    if (path == 1 && small_ok) {
+        pl.lanes_per_bucket = b / 4;
+    } else if (path == 1) {
+        const int chunks = (b + 255) / 256;                    // float4-per-lane wave loads per bucket
+        if (waves == 0) {
+            waves = 1;
+            while (waves * 8 < chunks) waves *= 2;
+        }
+        int vec = 1;
+        while (vec * waves < chunks) vec *= 2;
+        if (vec > 8) return ECQ_ERR_PARAM;                     // the bucket would not fit the team's registers
+        if (threads == 0) threads = waves * 64 > 256 ? waves * 64 : 256;
+        if (threads % (waves * 64) != 0) return ECQ_ERR_PARAM;
+        pl.waves_per_bucket = waves;
+        pl.vec_per_lane = vec;
+        pl.block_threads = threads;
+    }
+    *plan = pl;
+    return ECQ_OK;
+}
+
+static int run_quantize(const ecq_shape *sh, const float *g, const float *h, float alpha, float beta,
+                        uint64_t seed, uint64_t step, uint8_t *codes, float *scales,
+                        const ecq_tuning *tuning, bool update_h, void *stream)
+{
+    const int st = check_shape(sh);
+    if (st != ECQ_OK) return st;
+    if (!g || !h || !codes || !scales) return ECQ_ERR_NULL;
+    if (!aligned(g, 16) || !aligned(h, 16) || !aligned(codes, 4) || !aligned(scales, 4)) return ECQ_ERR_ALIGN;
+    if (!std::isfinite(alpha) || alpha < 0.0f) return ECQ_ERR_PARAM;
+    if (update_h && !(beta >= 0.0f && beta <= 1.0f)) return ECQ_ERR_PARAM;
+    Plan plan;
+    const int ps = make_plan(*sh, tuning, &plan);
+    if (ps != ECQ_OK) return ps;
+    Args a = make_args(*sh);
+    a.g = g;
+    a.h = const_cast<float *>(h);
+    a.codes = codes;
+    a.scales = scales;
+    a.alpha = alpha;
+    a.beta = beta;
+    set_stream_key(a, seed, step);
+    return launch_quantize(a, plan, update_h, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
+}  // namespace ecq
+
+extern "C" {
+
+int ecq_code_bits(int s) { return ecq::code_bits(s); }
+
+int ecq_row_bytes(int64_t n, int s, int64_t *bytes)
+{
+    if (!bytes) return ECQ_ERR_NULL;
+    const int r = ecq::code_bits(s);
+    if (r < 0) return r;
+    if (n < 0 || n > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    *bytes = (n * r + 7) / 8;
+    return ECQ_OK;
+}
+
+int ecq_num_buckets(int64_t n, int bucket, int64_t *nb)
+{
+    if (!nb) return ECQ_ERR_NULL;
+    if (n < 0 || n > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    if (bucket <= 0 || (bucket & 7) != 0) return ECQ_ERR_BUCKET;
+    *nb = (n + bucket - 1) / bucket;
+    return ECQ_OK;
+}
+
+int ecq_check_shape(const ecq_shape *shape) { return ecq::check_shape(shape); }
+
+int ecq_quantize(const ecq_shape *shape, const float *g, const float *h, float alpha, uint64_t seed,
+                 uint64_t step, uint8_t *codes, float *scales, void *stream)
+{
+    return ecq::run_quantize(shape, g, h, alpha, 0.0f, seed, step, codes, scales, nullptr, false, stream);
+}
+
+int ecq_quantize_update(const ecq_shape *shape, const float *g, float *h, float alpha, float beta,
+                        uint64_t seed, uint64_t step, uint8_t *codes, float *scales, void *stream)
+{
+    return ecq::run_quantize(shape, g, h, alpha, beta, seed, step, codes, scales, nullptr, true, stream);
+}
+
+int ecq_quantize_update_ex(const ecq_shape *shape, const float *g, float *h, float alpha, float beta,
+                           uint64_t seed, uint64_t step, uint8_t *codes, float *scales,
+                           const ecq_tuning *tuning, void *stream)
+{
+    return ecq::run_quantize(shape, g, h, alpha, beta, seed, step, codes, scales, tuning, true, stream);
+}
+
+int ecq_error_update(const ecq_shape *shape, const float *g, const uint8_t *codes, const float *scales,
+                     float beta, float *h, void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!g || !h || !codes || !scales) return ECQ_ERR_NULL;
+    if (!ecq::aligned(g, 16) || !ecq::aligned(h, 16) || !ecq::aligned(codes, 4) || !ecq::aligned(scales, 4))
+        return ECQ_ERR_ALIGN;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return ECQ_ERR_PARAM;
+    ecq::Args a = ecq::make_args(*shape);
+    a.g = g;
+    a.h = h;
+    a.codes = const_cast<uint8_t *>(codes);
+    a.scales = const_cast<float *>(scales);
+    a.beta = beta;
+    return ecq::launch_error_update(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
+int ecq_dequant_aggregate(const ecq_shape *shape, const uint8_t *codes, const float *scales, float *out,
+                          void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!codes || !scales || !out) return ECQ_ERR_NULL;
+    if (!ecq::aligned(out, 16) || !ecq::aligned(codes, 4) || !ecq::aligned(scales, 4)) return ECQ_ERR_ALIGN;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    a.scales = const_cast<float *>(scales);
+    a.out = out;
+    return ecq::launch_dequant_aggregate(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
+int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
+                     void *stream)
+{
+    if (!words) return ECQ_ERR_NULL;
+    if (count <= 0 || count > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    if (!ecq::aligned(words, 4)) return ECQ_ERR_ALIGN;
+    return ecq::launch_philox_words((uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step,
+                                    (uint32_t)(step >> 32), p, i0, count, words,
+                                    static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_calib_add(const float *a, const float *b, float *out, int64_t n, void *stream)
+{
+    if (!a || !b || !out) return ECQ_ERR_NULL;
+    if (n <= 0) return ECQ_ERR_SHAPE;
+    if (!ecq::aligned(a, 16) || !ecq::aligned(b, 16) || !ecq::aligned(out, 16)) return ECQ_ERR_ALIGN;
+    return ecq::launch_calib_add(a, b, out, n, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
+int ecq_calib_copy(const float *a, float *out, int64_t n, void *stream)
+{
+    if (!a || !out) return ECQ_ERR_NULL;
+    if (n <= 0) return ECQ_ERR_SHAPE;
+    if (!ecq::aligned(a, 16) || !ecq::aligned(out, 16)) return ECQ_ERR_ALIGN;
+    return ecq::launch_calib_copy(a, out, n, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
+const char *ecq_status_string(int status)
+{
+    switch (status) {
+    case ECQ_OK: return "ok";
+    case ECQ_ERR_NULL: return "a required pointer is NULL";
+    case ECQ_ERR_SHAPE: return "n or workers out of range";
+    case ECQ_ERR_LEVELS: return "s must be in 1..127";
+    case ECQ_ERR_BUCKET: return "bucket must be a positive multiple of 8";
+    case ECQ_ERR_STRIDE: return "a row stride is too small or not suitably divisible";
+    case ECQ_ERR_ALIGN: return "a base pointer is not aligned as documented";
+    case ECQ_ERR_LAUNCH: return "the HIP runtime refused a launch";
+    case ECQ_ERR_PARAM: return "alpha, beta or a tuning value is out of range";
+    default: return "unknown status";
+    }
+}
+
+int ecq_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Host-side declarations shared by the C ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ecq.h"
+
+namespace ecq {
+
+// Everything a kernel needs, passed by value.
+struct Args {
+    const float *g;
+    float *h;              // read-only unless the kernel updates the accumulator
+    uint8_t *codes;
+    float *scales;
+    float *out;            // aggregation output
+    int64_t n;
+    int64_t nb;
+    int64_t gh_stride;
+    int64_t code_stride;
+    int64_t scale_stride;
+    int64_t row_bytes;
+    int32_t workers;
+    int32_t bucket;
+    int32_t s;
+    int32_t r;
+    float alpha;
+    float beta;
+    uint32_t key0, key1;   // seed
+    uint32_t step_lo, step_hi;
+};
+
+// Resolved launch plan for the quantise(+update) entry points.
+struct Plan {
+    int path;              // 1 = bucket in registers, 2 = two-pass
+    int lanes_per_bucket;  // path 1, bucket < 256: lanes sharing a bucket (power of two)
+    int waves_per_bucket;  // path 1, bucket >= 256
+    int vec_per_lane;      // path 1: float4 per lane (1, 2, 4, 8)
+    int block_threads;
+};
+
+int make_plan(const ecq_shape &shape, const ecq_tuning *tuning, Plan *plan);
+
+hipError_t launch_quantize(const Args &a, const Plan &plan, bool update_h, hipStream_t stream);
+hipError_t launch_error_update(const Args &a, hipStream_t stream);
+hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream);
+hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, uint32_t step_hi,
+                               uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
+                               hipStream_t stream);
+hipError_t launch_calib_add(const float *a, const float *b, float *out, int64_t n,
+                            hipStream_t stream);
+hipError_t launch_calib_copy(const float *a, float *out, int64_t n, hipStream_t stream);
+
+}  // namespace ecq

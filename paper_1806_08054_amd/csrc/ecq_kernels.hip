@@ -1,0 +1,512 @@
+// HIP kernels of the ECQ-SGD codec for gfx950 (MI355X), wave64.
+//
+// Single pass ("bucket in registers"): every bucket of b elements is owned by a team of
+// lanes that loads its share of g and h once, keeps it in VGPRs across the max-abs
+// reduction (DPP inside a wave, LDS across waves), then rounds, packs, stores the codes and
+// writes h back: 12 + r/8 + 4/b bytes of HBM traffic per element, the minimum for
+//   v = g + alpha*h (Eq. 7), Q_s(v) (Eq. 8-9), r-bit encoding, h <- beta*h + (g - g~) (Eq. 6)
+// of Wu et al., ICML 2018, Section 4.  Buckets that do not fit a team's registers, or whose
+// size is not a supported shape, take a two-pass route (norm kernel, then quantise kernel).
+//
+// A lane always owns 4 consecutive elements starting at a multiple of 4, which is exactly one
+// Philox4x32-10 block (counter low word = element index >> 2), so no random word is wasted.
+#include "ecq_device.hpp"
+#include "ecq_internal.hpp"
+
+namespace ecq {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// Per-lane work on 4 consecutive elements.
+// ---------------------------------------------------------------------------------------------
+
+// Loads elements [off, off+4) of a row segment of `len` elements; missing ones read as 0.
+__device__ __forceinline__ void load4(const float *__restrict__ row, int64_t off, int64_t len,
+                                      float (&x)[4])
+{
+    if (off + 4 <= len) {
+        const f4 t = *reinterpret_cast<const f4 *>(row + off);
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = (off + e < len) ? row[off + e] : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void store4(float *__restrict__ row, int64_t off, int64_t len,
+                                       const float (&x)[4])
+{
+    if (off + 4 <= len) {
+        f4 t;
+        t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
+        *reinterpret_cast<f4 *>(row + off) = t;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (off + e < len) row[off + e] = x[e];
+    }
+}
+
+// Bit pattern of max |g + alpha*h| over a lane's 4 elements (0 for missing elements).
+__device__ __forceinline__ uint32_t absmax4(const float (&g)[4], const float (&h)[4], float alpha)
+{
+    uint32_t m = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        m = umax(m, __float_as_uint(compensate(g[e], alpha, h[e])) & 0x7FFFFFFFu);
+    return m;
+}
+
+// Rounds, encodes and (optionally) accumulates the error for a lane's 4 elements.
+//   valid : how many of the 4 exist (0..4); codes of missing elements are zero bits.
+//   scale : the bucket's norm.  A zero norm means every v is zero: dividing by 1 instead
+//           then yields level 0 everywhere without a special case.
+// Returns the 4*R encoded bits, element e in bits [e*R, (e+1)*R).
+template <int R, bool UPDATE>
+__device__ __forceinline__ uint32_t quantize4(const float (&g)[4], float (&h)[4], int valid,
+                                              float scale, const Levels &lv, const float *xi_tab,
+                                              float alpha, float beta, const U4 &words)
+{
+    const float div = scale > 0.0f ? scale : 1.0f;
+    const uint32_t w[4] = {words.x, words.y, words.z, words.w};
+    uint32_t bits = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float v = compensate(g[e], alpha, h[e]);
+        const int m = round_level(v, div, lv, w[e]);
+        const float xi = (R == 2) ? (float)m : xi_tab[m];
+        const float gt = dequant_signed(scale, xi, m, v);
+        const bool neg = (m > 0) && (__float_as_uint(v) >> 31);
+        const uint32_t code = (uint32_t)(neg ? lv.s - m : lv.s + m);
+        bits |= (e < valid) ? (code << (R * e)) : 0u;
+        if (UPDATE) h[e] = error_update(beta, h[e], g[e], gt);
+    }
+    return bits;
+}
+
+// Stores a lane's 4*R code bits.  `elem` = index of the lane's first element in the row (a
+// multiple of 4; a multiple of 8 on even lanes).  For odd R two neighbouring lanes share
+// whole bytes, so the even lane stores both lanes' bits.  Must be called by all lanes.
+template <int R>
+__device__ __forceinline__ void store_codes(uint8_t *__restrict__ crow, int64_t row_bytes,
+                                            int64_t elem, int valid, uint32_t bits, int lane)
+{
+    if constexpr ((R & 1) == 0) {
+        constexpr int NB = R / 2;
+        const int64_t byte_off = (elem >> 2) * NB;
+        if (valid == 4) {
+            uint8_t *dst = crow + byte_off;
+            if constexpr (NB == 1) {
+                *dst = (uint8_t)bits;
+            } else if constexpr (NB == 2) {
+                *reinterpret_cast<uint16_t *>(dst) = (uint16_t)bits;
+            } else if constexpr (NB == 4) {
+                *reinterpret_cast<uint32_t *>(dst) = bits;
+            } else {
+                store_code_bytes(dst, bits, NB, NB);
+            }
+        } else if (valid > 0) {
+            store_code_bytes(crow + byte_off, bits, NB, row_bytes - byte_off);
+        }
+    } else {
+        const uint32_t next = dpp_u32<0xF5>(bits);            // quad_perm [1,1,3,3]
+        if ((lane & 1) == 0 && valid > 0) {
+            const uint64_t both = (uint64_t)bits | ((uint64_t)next << (4 * R));
+            const int64_t byte_off = (elem >> 3) * R;
+            store_code_bytes(crow + byte_off, both, R, row_bytes - byte_off);
+        }
+    }
+}
+
+__device__ __forceinline__ void fill_xi_table(float *xi_tab, int s)
+{
+    for (int t = threadIdx.x; t <= s; t += blockDim.x) xi_tab[t] = (float)t / (float)s;
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Single pass, buckets of 256 elements or more: a team of W waves per bucket, J float4 per lane.
+// ---------------------------------------------------------------------------------------------
+template <int R, int J, bool UPDATE>
+__global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_shift)
+{
+    __shared__ float xi_tab[128];
+    __shared__ uint32_t wave_norm[16];
+    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int W = 1 << w_shift;
+    const int team = wave >> w_shift;
+    const int wit = wave & (W - 1);
+    const int teams = blockDim.x >> (6 + w_shift);
+    const int64_t k = (int64_t)blockIdx.x * teams + team;
+    const uint32_t p = blockIdx.y;
+    const bool active = k < a.nb;
+    const int64_t e0 = active ? k * (int64_t)a.bucket : 0;
+    const int64_t rest = a.n - e0;
+    const int len = active ? (int)(rest < a.bucket ? rest : (int64_t)a.bucket) : 0;
+
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride + e0;
+    float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride + e0;
+
+    float g[J][4], h[J][4];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int off = ((wit * J + j) * 64 + lane) * 4;
+        load4(grow, off, len, g[j]);
+        load4(hrow, off, len, h[j]);
+    }
+    uint32_t mx = 0;
+#pragma unroll
+    for (int j = 0; j < J; ++j) mx = umax(mx, absmax4(g[j], h[j], a.alpha));
+
+    uint32_t norm = wave_max_uniform(mx);
+    if (W > 1) {
+        if (lane == 0) wave_norm[wave] = norm;
+        __syncthreads();
+        for (int t = 0; t < W; ++t) norm = umax(norm, wave_norm[(team << w_shift) + t]);
+    }
+    const float scale = __uint_as_float(norm);
+    const Levels lv{a.s, (float)a.s};
+
+    uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int chunk = (wit * J + j) * 256;
+        if (chunk >= len) continue;                            // wave-uniform
+        const int off = chunk + lane * 4;
+        const int64_t elem = e0 + off;
+        int valid = len - off;
+        valid = valid < 0 ? 0 : (valid > 4 ? 4 : valid);
+        const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
+        const uint32_t bits =
+            quantize4<R, UPDATE>(g[j], h[j], valid, scale, lv, xi_tab, a.alpha, a.beta, words);
+        store_codes<R>(crow, a.row_bytes, elem, valid, bits, lane);
+        if (UPDATE) store4(hrow, off, len, h[j]);
+    }
+    if (active && wit == 0 && lane == 0) a.scales[(int64_t)p * a.scale_stride + k] = scale;
+}
+
+// ---------------------------------------------------------------------------------------------
+// One float4 per lane, one 256-element chunk per wave.  Two uses:
+//   lanes_per_bucket > 0 : single pass for small power-of-two buckets (8..128 elements): the
+//                          norm is a max over aligned groups of lanes_per_bucket lanes;
+//   lanes_per_bucket == 0: second pass of the two-pass route: the norm is read from scales.
+// ---------------------------------------------------------------------------------------------
+template <int R, bool UPDATE>
+__global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lanes_per_bucket)
+{
+    __shared__ float xi_tab[128];
+    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t chunk = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
+    const int64_t elem = chunk * 256 + lane * 4;
+    const uint32_t p = blockIdx.y;
+    if (chunk * 256 >= a.n) return;                            // wave-uniform
+
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
+    float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
+    float g[4], h[4];
+    load4(grow, elem, a.n, g);
+    load4(hrow, elem, a.n, h);
+    int64_t rest = a.n - elem;
+    const int valid = rest < 0 ? 0 : (rest > 4 ? 4 : (int)rest);
+
+    float scale;
+    const int64_t k = elem / a.bucket;
+    if (lanes_per_bucket > 0) {
+        scale = __uint_as_float(group_max(absmax4(g, h, a.alpha), lanes_per_bucket));
+        if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
+            a.scales[(int64_t)p * a.scale_stride + k] = scale;
+    } else {
+        scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + k] : 0.0f;
+    }
+    const Levels lv{a.s, (float)a.s};
+    const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
+    const uint32_t bits = quantize4<R, UPDATE>(g, h, valid, scale, lv, xi_tab, a.alpha, a.beta, words);
+    store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem, valid, bits, lane);
+    if (UPDATE) store4(hrow, elem, a.n, h);
+}
+
+// First pass of the two-pass route: scales[p][k] = max |g + alpha*h| over bucket k, taken with
+// an unsigned atomic max on the bit patterns (order-preserving for non-negative floats).
+// scales must hold zeros on entry.
+__global__ void __launch_bounds__(256) k_bucket_norm(const Args a)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    const uint32_t p = blockIdx.y;
+    float g[4], h[4];
+    load4(a.g + (int64_t)p * a.gh_stride, elem, a.n, g);
+    load4(a.h + (int64_t)p * a.gh_stride, elem, a.n, h);
+    const uint32_t mx = absmax4(g, h, a.alpha);
+    const bool exists = elem < a.n;
+    const long long k = exists ? (long long)(elem / a.bucket) : -1;
+    // Element indices grow with the lane, so lane 0 holds the wave's lowest bucket, and if lane 0
+    // is past the end of the row the whole wave is.  Lanes past the end carry a zero norm.
+    const long long k_lead = __shfl(k, 0, 64);
+    if (k_lead < 0) return;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(a.scales + (int64_t)p * a.scale_stride);
+    if (__all(!exists || k == k_lead)) {
+        const uint32_t norm = wave_max_uniform(mx);
+        if (lane == 0) atomicMax(dst + k_lead, norm);
+    } else if (exists) {
+        atomicMax(dst + k, mx);
+    }
+}
+
+__global__ void __launch_bounds__(256) k_zero_scales(const Args a)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < a.nb) a.scales[(int64_t)blockIdx.y * a.scale_stride + k] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode side.
+// ---------------------------------------------------------------------------------------------
+
+// The R bytes that hold the codes of the 8 elements starting at `elem` (a multiple of 8).
+template <int R>
+__device__ __forceinline__ uint64_t load_code_group(const uint8_t *__restrict__ crow,
+                                                    int64_t row_bytes, int64_t elem)
+{
+    const int64_t byte_off = (elem >> 3) * R;
+    uint64_t bits = 0;
+#pragma unroll
+    for (int b = 0; b < R; ++b)
+        if (byte_off + b < row_bytes) bits |= (uint64_t)crow[byte_off + b] << (8 * b);
+    return bits;
+}
+
+// Eq. (8) from a code: scale * fl(|q|/s), negated iff q < 0.
+template <int R>
+__device__ __forceinline__ float decode_one(uint64_t bits, int e, int s, float scale,
+                                            const float *xi_tab)
+{
+    const int c = (int)((bits >> (R * e)) & ((1u << R) - 1u));
+    const int q = c - s;
+    const int m = q < 0 ? -q : q;
+    const float xi = (R == 2) ? (float)m : xi_tab[m];
+    const float gt = scale * xi;
+    return q < 0 ? -gt : gt;
+}
+
+// Eq. (6) from an encoded message; a lane owns 8 consecutive elements (R whole bytes).
+template <int R>
+__global__ void __launch_bounds__(256) k_error_update(const Args a)
+{
+    __shared__ float xi_tab[128];
+    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    const uint32_t p = blockIdx.y;
+    if (elem >= a.n) return;
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
+    float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
+    const uint64_t bits = load_code_group<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem);
+    const float scale = a.scales[(int64_t)p * a.scale_stride + elem / a.bucket];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        float g[4], h[4];
+        load4(grow, elem + 4 * half, a.n, g);
+        load4(hrow, elem + 4 * half, a.n, h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            h[e] = error_update(a.beta, h[e], g[e], decode_one<R>(bits, 4 * half + e, a.s, scale, xi_tab));
+        store4(hrow, elem + 4 * half, a.n, h);
+    }
+}
+
+// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
+template <int R>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a)
+{
+    __shared__ float xi_tab[128];
+    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (elem >= a.n) return;
+    const int64_t k = elem / a.bucket;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int p = 0; p < a.workers; ++p) {
+        const uint64_t bits = load_code_group<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem);
+        const float scale = a.scales[(int64_t)p * a.scale_stride + k];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] + decode_one<R>(bits, e, a.s, scale, xi_tab);
+    }
+    const float pf = (float)a.workers;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = acc[4 * half + e] / pf;
+        store4(a.out, elem + 4 * half, a.n, o);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inspection and calibration kernels.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo,
+                                                     uint32_t step_hi, uint32_t p, uint64_t i0,
+                                                     int64_t count, uint32_t *__restrict__ words)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= count) return;
+    const uint64_t i = i0 + (uint64_t)j;
+    const U4 blk = philox4x32_10((uint32_t)(i >> 2), p, step_lo, step_hi, key0, key1);
+    const uint32_t lane_word[4] = {blk.x, blk.y, blk.z, blk.w};
+    words[j] = lane_word[i & 3];
+}
+
+__global__ void __launch_bounds__(256) k_calib_add(const float *__restrict__ x, const float *__restrict__ y,
+                                                  float *__restrict__ out, int64_t n4, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const f4 u = reinterpret_cast<const f4 *>(x)[i];
+        const f4 v = reinterpret_cast<const f4 *>(y)[i];
+        reinterpret_cast<f4 *>(out)[i] = u + v;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const int64_t i = n4 * 4 + threadIdx.x;
+        out[i] = x[i] + y[i];
+    }
+}
+
+__global__ void __launch_bounds__(256) k_calib_copy(const float *__restrict__ x, float *__restrict__ out,
+                                                   int64_t n4, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        reinterpret_cast<f4 *>(out)[i] = reinterpret_cast<const f4 *>(x)[i];
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const int64_t i = n4 * 4 + threadIdx.x;
+        out[i] = x[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launchers.
+// ---------------------------------------------------------------------------------------------
+static inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
+
+template <int R, int J>
+static void launch_team_j(const Args &a, const Plan &plan, bool update, hipStream_t st)
+{
+    int w_shift = 0;
+    while ((1 << w_shift) < plan.waves_per_bucket) ++w_shift;
+    const int teams = plan.block_threads / (64 * plan.waves_per_bucket);
+    const dim3 grid(cdiv(a.nb, teams), (unsigned)a.workers);
+    if (update)
+        hipLaunchKernelGGL((k_fused_team<R, J, true>), grid, dim3(plan.block_threads), 0, st, a, w_shift);
+    else
+        hipLaunchKernelGGL((k_fused_team<R, J, false>), grid, dim3(plan.block_threads), 0, st, a, w_shift);
+}
+
+template <int R>
+static void launch_team(const Args &a, const Plan &plan, bool update, hipStream_t st)
+{
+    switch (plan.vec_per_lane) {
+    case 1: launch_team_j<R, 1>(a, plan, update, st); break;
+    case 2: launch_team_j<R, 2>(a, plan, update, st); break;
+    case 4: launch_team_j<R, 4>(a, plan, update, st); break;
+    default: launch_team_j<R, 8>(a, plan, update, st); break;
+    }
+}
+
+template <int R>
+static void launch_chunk(const Args &a, int lanes_per_bucket, int block_threads, bool update, hipStream_t st)
+{
+    const int waves = block_threads / 64;
+    const dim3 grid(cdiv(cdiv(a.n, 256), waves), (unsigned)a.workers);
+    if (update)
+        hipLaunchKernelGGL((k_quant_chunk<R, true>), grid, dim3(block_threads), 0, st, a, lanes_per_bucket);
+    else
+        hipLaunchKernelGGL((k_quant_chunk<R, false>), grid, dim3(block_threads), 0, st, a, lanes_per_bucket);
+}
+
+template <int R>
+static void launch_quantize_r(const Args &a, const Plan &plan, bool update, hipStream_t st)
+{
+    if (plan.path == 1 && plan.lanes_per_bucket == 0) {
+        launch_team<R>(a, plan, update, st);
+    } else if (plan.path == 1) {
+        launch_chunk<R>(a, plan.lanes_per_bucket, 256, update, st);
+    } else {
+        hipLaunchKernelGGL(k_zero_scales, dim3(cdiv(a.nb, 256), (unsigned)a.workers), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_bucket_norm, dim3(cdiv(cdiv(a.n, 4), 256), (unsigned)a.workers), dim3(256), 0, st, a);
+        launch_chunk<R>(a, 0, 256, update, st);
+    }
+}
+
+#define ECQ_DISPATCH_R(r, CALL)      \
+    switch (r) {                     \
+    case 2: CALL(2); break;          \
+    case 3: CALL(3); break;          \
+    case 4: CALL(4); break;          \
+    case 5: CALL(5); break;          \
+    case 6: CALL(6); break;          \
+    case 7: CALL(7); break;          \
+    default: CALL(8); break;         \
+    }
+
+hipError_t launch_quantize(const Args &a, const Plan &plan, bool update_h, hipStream_t stream)
+{
+#define CALL(RR) launch_quantize_r<RR>(a, plan, update_h, stream)
+    ECQ_DISPATCH_R(a.r, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_error_update(const Args &a, hipStream_t stream)
+{
+    const dim3 grid(cdiv(cdiv(a.n, 8), 256), (unsigned)a.workers);
+#define CALL(RR) hipLaunchKernelGGL((k_error_update<RR>), grid, dim3(256), 0, stream, a)
+    ECQ_DISPATCH_R(a.r, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
+{
+    const dim3 grid(cdiv(cdiv(a.n, 8), 256));
+#define CALL(RR) hipLaunchKernelGGL((k_dequant_aggregate<RR>), grid, dim3(256), 0, stream, a)
+    ECQ_DISPATCH_R(a.r, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, uint32_t step_hi,
+                               uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
+                               hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_philox_words, dim3(cdiv(count, 256)), dim3(256), 0, stream, key0, key1,
+                       step_lo, step_hi, p, i0, count, words);
+    return hipGetLastError();
+}
+
+static unsigned calib_grid(int64_t n4)
+{
+    const int64_t want = (n4 + 255) / 256;
+    const int64_t cap = 256 * 32;                              // 32 blocks per compute unit
+    return (unsigned)(want < 1 ? 1 : (want > cap ? cap : want));
+}
+
+hipError_t launch_calib_add(const float *x, const float *y, float *out, int64_t n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_calib_add, dim3(calib_grid(n / 4)), dim3(256), 0, stream, x, y, out, n / 4, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_calib_copy(const float *x, float *out, int64_t n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_calib_copy, dim3(calib_grid(n / 4)), dim3(256), 0, stream, x, out, n / 4, n);
+    return hipGetLastError();
+}
+
+}  // namespace ecq

@@ -1,0 +1,254 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bars: packed codes, scales and Philox words bit-exact; fp32 h and averaged update within 1e-6
+relative per bucket (and the number of non-bit-identical values is reported -- expected 0).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+SEED = 0x5EED0123456789AB
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_1806_08054_amd as E
+    return E
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+class GpuState:
+    """Device buffers of one workload, laid out as the C ABI documents."""
+
+    def __init__(self, E, P, N, bucket, s, pad=0):
+        self.E, self.P, self.N, self.bucket, self.s = E, P, N, bucket, s
+        sh = E.Shape.packed(N, P, bucket, s)
+        sh.gh_stride += 4 * pad
+        sh.code_stride += 4 * pad
+        sh.scale_stride += pad
+        self.sh = sh
+        self.rb = E.row_bytes(N, s)
+        self.nb = E.num_buckets(N, bucket)
+        self.g = torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda")
+        self.h = torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda")
+        self.codes = torch.full((P, sh.code_stride), 0xEE, dtype=torch.uint8, device="cuda")
+        self.scales = torch.full((P, sh.scale_stride), -7.0, dtype=torch.float32, device="cuda")
+        self.out = torch.full((N,), -7.0, dtype=torch.float32, device="cuda")
+
+    def poison(self):
+        self.codes.fill_(0xEE)
+        self.scales.fill_(-7.0)
+
+
+def _rel_ok(got, ref, bucket, tol=1e-6):
+    """max|d| <= tol * max|ref| per bucket (rows = workers or a single row)."""
+    got = np.atleast_2d(got).astype(np.float64)
+    ref = np.atleast_2d(ref).astype(np.float64)
+    n = ref.shape[1]
+    nb = (n + bucket - 1) // bucket
+    padn = nb * bucket - n
+    d = np.pad(np.abs(got - ref), ((0, 0), (0, padn))).reshape(ref.shape[0], nb, bucket).max(axis=2)
+    m = np.pad(np.abs(ref), ((0, 0), (0, padn))).reshape(ref.shape[0], nb, bucket).max(axis=2)
+    return bool(np.all(d <= tol * m))
+
+
+def _compare_step(st, g_np, h_ref, alpha, beta, step, tuning=None, fused=True):
+    """Runs one iteration on both sides from the same (g, h); returns oracle outputs.
+    h_ref is advanced in place by the oracle; st.h by the library."""
+    E = st.E
+    P, N = st.P, st.N
+    q, scales, _ = oracle.batch_step(g_np, h_ref, st.bucket, st.s, alpha, beta, SEED, step)
+    codes_ref = oracle.pack_rows(q, st.s)
+    st.poison()
+    if fused:
+        E.ecq_quantize_update_ex(st.sh, st.g, st.h, alpha, beta, SEED, step, st.codes, st.scales, tuning)
+    else:
+        E.ecq_quantize(st.sh, st.g, st.h, alpha, SEED, step, st.codes, st.scales)
+        E.ecq_error_update(st.sh, st.g, st.codes, st.scales, beta, st.h)
+    torch.cuda.synchronize()
+    codes = st.codes.cpu().numpy()
+    sc = st.scales.cpu().numpy()
+    hh = st.h.cpu().numpy()
+    assert np.array_equal(sc[:, : st.nb].view(np.uint32), scales.view(np.uint32)), "scales differ"
+    bad = np.nonzero(codes[:, : st.rb] != codes_ref)
+    assert bad[0].size == 0, f"{bad[0].size} code bytes differ, first at worker {bad[0][0]} byte {bad[1][0]}"
+    # bytes and floats outside the documented extents are never touched
+    assert np.all(codes[:, st.rb:] == 0xEE)
+    assert np.all(sc[:, st.nb:] == -7.0)
+    assert np.all(hh[:, N:] == 0)
+    assert _rel_ok(hh[:, :N], h_ref, st.bucket), "h outside 1e-6"
+    nbits = int((hh[:, :N].view(np.uint32) != h_ref.view(np.uint32)).sum())
+    assert nbits == 0, f"{nbits} h values not bit-identical"
+    return codes_ref, scales
+
+
+def _aggregate_check(st, codes_ref, scales_ref):
+    E = st.E
+    ref = oracle.aggregate(codes_ref, scales_ref, st.N, st.bucket, st.s)
+    st.out.fill_(-7.0)
+    E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+    torch.cuda.synchronize()
+    out = st.out.cpu().numpy()
+    assert _rel_ok(out, ref, st.bucket), "aggregate outside 1e-6"
+    nbits = int((out.view(np.uint32) != ref.view(np.uint32)).sum())
+    assert nbits == 0, f"{nbits} aggregate values not bit-identical"
+
+
+def _free_run(E, wl, iters, tuning=None, pad=0, fused=True, gens=None):
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, pad=pad)
+    h_ref = np.zeros((wl.P, wl.N), np.float32)
+    for t in range(iters):
+        g_np = gens(t) if gens else synth.gradients(wl, t).numpy()
+        st.g[:, : wl.N] = _dev(g_np)
+        codes_ref, scales_ref = _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, t, tuning, fused)
+        _aggregate_check(st, codes_ref, scales_ref)
+    return st
+
+
+# ------------------------------------------------------------------ RNG stream -------------
+
+def test_philox_words_bit_exact(E):
+    for seed, step, p, i0, count in [(SEED, 0, 0, 0, 4096), (1, (5 << 32) | 3, 31, 1 << 33, 1000),
+                                     (2**64 - 1, 2**64 - 1, 65534, 12345, 777)]:
+        w = torch.zeros(count, dtype=torch.int32, device="cuda")
+        E.ecq_philox_words(seed, step, p, i0, count, w)
+        torch.cuda.synchronize()
+        got = w.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, oracle.words(seed, step, p, i0, count))
+
+
+# ------------------------------------------------------------------ the five workloads -----
+
+def test_tiny_free_running(E):
+    """Workload 1 in full: 10 free-running iterations, every element compared."""
+    wl = synth.WORKLOADS["tiny"]
+    _free_run(E, wl, wl.iters)
+
+
+@pytest.mark.parametrize("name,N,iters", [("linear", 40_000, 6), ("resnet50", 161 * 700 + 40, 6),
+                                          ("alexnet", 100_000 + 808, 4), ("vgg16", 8192 * 5 + 2856, 4)])
+def test_workload_shapes_reduced(E, name, N, iters):
+    """Workloads 2-5 with their bucket, s, alpha, beta and value distribution at a length the
+    oracle covers in full (several buckets plus the same ragged tail), free-running."""
+    wl = synth.scaled(synth.WORKLOADS[name], N=N, P=min(synth.WORKLOADS[name].P, 4))
+    _free_run(E, wl, iters)
+
+
+# ------------------------------------------------------------------ shapes and edges -------
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 7, 8, 15, 16, 31, 33, 64, 127])
+@pytest.mark.parametrize("bucket", [8, 64, 512, 1000])
+def test_levels_and_buckets(E, s, bucket):
+    """Every code width r = 2..8 against every kernel route (lane groups, wave teams, two-pass),
+    N not a multiple of 4, 8 or the bucket, padded strides."""
+    wl = synth.Workload("edge", P=3, N=2 * 1024 + 8 * 37 + 3, bucket=bucket, s=s, alpha=0.5, beta=0.75,
+                        iters=2, kind="normal", data_seed=s * 131 + bucket)
+    _free_run(E, wl, 2, pad=3)
+
+
+@pytest.mark.parametrize("bucket", [16, 24, 32, 128, 256, 264, 2048, 4096, 8192, 16384, 32768, 40000])
+def test_bucket_routes(E, bucket):
+    wl = synth.Workload("edge", P=2, N=3 * bucket + bucket // 2 + 5, bucket=bucket, s=3, alpha=1.0, beta=0.9,
+                        iters=2, kind="normal", data_seed=bucket)
+    _free_run(E, wl, 2)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8, 9, 255, 256, 257, 511, 513])
+@pytest.mark.parametrize("s", [1, 3, 7])
+def test_tiny_lengths(E, N, s):
+    wl = synth.Workload("edge", P=2, N=N, bucket=512, s=s, alpha=1.0, beta=1.0, iters=2, kind="normal",
+                        data_seed=N)
+    _free_run(E, wl, 2)
+    wl = synth.scaled(wl, bucket=8)
+    _free_run(E, wl, 2)
+
+
+def test_launch_geometry_invariance(E):
+    """Same bits for every mapping of buckets to lanes."""
+    wl = synth.Workload("edge", P=2, N=5 * 2048 + 1000, bucket=2048, s=3, alpha=1.0, beta=0.9, iters=2,
+                        kind="normal", data_seed=99)
+    for path, waves, threads in [(1, 1, 64), (1, 1, 256), (1, 2, 256), (1, 4, 256), (1, 8, 512),
+                                 (1, 8, 1024), (1, 16, 1024), (2, 0, 0)]:
+        _free_run(E, wl, 2, tuning=E.Tuning(path, waves, threads, 0))
+
+
+def test_unfused_equals_fused(E):
+    wl = synth.Workload("edge", P=3, N=7000, bucket=512, s=7, alpha=0.3, beta=0.9, iters=3, kind="normal",
+                        data_seed=5)
+    _free_run(E, wl, 3, fused=False)
+
+
+def test_degenerate_values(E):
+    """All-zero buckets, a zero row, negative zeros, denormals, repeated maxima, huge range."""
+    P, N, bucket = 4, 4096, 512
+    rng = np.random.default_rng(0)
+
+    def gens(t):
+        g = rng.standard_normal((P, N)).astype(np.float32)
+        g[0] = 0.0
+        g[1, 512:1024] = 0.0
+        g[1, 1024:1536] = -0.0
+        g[2] *= 1e-41                                   # denormal inputs and denormal norms
+        g[3, :100] = np.float32(3.0) * np.sign(g[3, :100])   # many elements attain the norm
+        g[3, 2048:2560] *= (10.0 ** rng.integers(-30, 30, 512)).astype(np.float32)
+        return g
+
+    for s in (1, 3, 127):
+        wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=3,
+                            kind="normal")
+        _free_run(E, wl, 3, gens=gens)
+
+
+def test_teacher_forced_and_alpha_zero(E):
+    """The oracle's h is fed to the library every iteration; alpha = 0 (QSGD) ignores h."""
+    wl = synth.Workload("edge", P=2, N=6000, bucket=1024, s=4, alpha=0.0, beta=1.0, iters=3, kind="normal",
+                        data_seed=3)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s)
+    h_ref = np.random.default_rng(1).standard_normal((wl.P, wl.N)).astype(np.float32)
+    for t in range(3):
+        g_np = synth.gradients(wl, t).numpy()
+        st.g[:, : wl.N] = _dev(g_np)
+        st.h[:, : wl.N] = _dev(h_ref)
+        _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, t)
+
+
+# ------------------------------------------------------------------ boundary errors --------
+
+def test_argument_errors_leave_outputs_untouched(E):
+    st = GpuState(E, 2, 1024, 512, 1)
+    lib = E.lib()
+    import ctypes as C
+
+    def call(sh, g=st.g, h=st.h, codes=st.codes, scales=st.scales, alpha=1.0, beta=1.0):
+        ptr = lambda t: None if t is None else C.c_void_p(t.data_ptr() if hasattr(t, "data_ptr") else t)
+        return lib.ecq_quantize_update(C.byref(sh), ptr(g), ptr(h), alpha, beta, 1, 0, ptr(codes), ptr(scales), None)
+
+    def shape(**kw):
+        sh = E.Shape.packed(1024, 2, 512, 1)
+        for k, v in kw.items():
+            setattr(sh, k, v)
+        return sh
+
+    assert call(shape(), g=None) == -1
+    assert call(shape(n=0)) == -2 and call(shape(workers=0)) == -2 and call(shape(workers=70000)) == -2
+    assert call(shape(s=0)) == -3 and call(shape(s=128)) == -3
+    assert call(shape(bucket=0)) == -4 and call(shape(bucket=12)) == -4
+    assert call(shape(gh_stride=1000)) == -5 and call(shape(gh_stride=1026)) == -5
+    assert call(shape(code_stride=100)) == -5 and call(shape(scale_stride=1)) == -5
+    assert call(shape(), g=st.g.data_ptr() + 4) == -6
+    assert call(shape(), alpha=-1.0) == -8 and call(shape(), beta=1.5) == -8
+    assert call(shape(), alpha=float("nan")) == -8 and call(shape(reserved=1)) == -8
+    torch.cuda.synchronize()
+    assert bool((st.codes == 0xEE).all()) and bool((st.scales == -7.0).all()) and not bool(st.h.any())
+    assert call(shape()) == 0
+    torch.cuda.synchronize()
