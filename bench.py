@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the ECQ-SGD hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic gradients that already
+sit in HBM: the fused compensate / norm / stochastic-round / encode / error-update kernel
+over all P workers (Section 4, Eq. (6)-(9) of Wu et al., ICML 2018), then the
+dequantise-and-average kernel over the P encoded messages (Eq. (4)).
+
+Prints ONE JSON line.  `value` is the algorithmic bytes of a whole step divided by the step
+time; the `roofline` object is the fused kernel alone (the kernel the headline metric is
+about), timed with HIP events inside the timed region; `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(P, N, bucket, s, E):
+    """(fused, dequant) bytes one step must move: read g, read h, write h, write codes and
+    scales; then read codes and scales of all workers, write the fp32 average."""
+    rb, nb = E.row_bytes(N, s), E.num_buckets(N, bucket)
+    fused = P * (12 * N + rb + 4 * nb)
+    dequant = P * (rb + 4 * nb) + 4 * N
+    return fused, dequant
+
+
+def cpu_baseline(wl, sample_n, g_sample):
+    """The oracle as it stands on a prefix of every worker's gradient (whole buckets)."""
+    import numpy as np
+    import oracle
+    P = wl.P
+    g = np.ascontiguousarray(g_sample, np.float32)
+    h = np.zeros_like(g)
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    q, scales, _ = oracle.batch_step(g, h, wl.bucket, wl.s, wl.alpha, wl.beta, 1, 0, threads=threads)
+    codes = oracle.pack_rows(q, wl.s)
+    oracle.aggregate(codes, scales, sample_n, wl.bucket, wl.s)
+    dt = time.perf_counter() - t0
+    rb = oracle.row_bytes(sample_n, wl.s)
+    nb = (sample_n + wl.bucket - 1) // wl.bucket
+    nbytes = P * (12 * sample_n + rb + 4 * nb) + P * (rb + 4 * nb) + 4 * sample_n
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample_n} elements of each of the {P} workers, 1 step "
+                      f"(quantise+update, pack, aggregate), {dt:.2f} s wall",
+            "gelem_per_s": round(P * sample_n / dt / 1e9, 5)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50", choices=["tiny", "linear", "resnet50", "alexnet", "vgg16"])
+    ap.add_argument("--pool", type=int, default=2, help="distinct gradient batches cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=32 * 1024 * 1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; the P workers are a resident batch on it "
+                 "(--gpus must be 1)")
+
+    import torch
+    import paper_1806_08054_amd as E
+    import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    P, N = wl.P, wl.N
+    sh = E.Shape.packed(N, P, wl.bucket, wl.s)
+    pool = [synth.gradients(wl, t, device="cuda",
+                            out=torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda"))
+            for t in range(max(1, args.pool))]
+    h = torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda")
+    codes = torch.zeros(P, sh.code_stride, dtype=torch.uint8, device="cuda")
+    scales = torch.zeros(P, sh.scale_stride, dtype=torch.float32, device="cuda")
+    out = torch.zeros(N, dtype=torch.float32, device="cuda")
+    fused_b, deq_b = algorithmic_bytes(P, N, wl.bucket, wl.s, E)
+    seed = 1
+
+    def step(t, ev=None):
+        g = pool[t % len(pool)]
+        if ev:
+            ev[0].record()
+        E.ecq_quantize_update(sh, g, h, wl.alpha, wl.beta, seed, t, codes, scales)
+        if ev:
+            ev[1].record()
+        E.ecq_dequant_aggregate(sh, codes, scales, out)
+        if ev:
+            ev[2].record()
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    K = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = evs[0][0].elapsed_time(evs[-1][2])
+    ms_per_step = max(wall * 1e3, gpu_ms) / K
+    fused_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / K
+    deq_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K
+
+    value = (fused_b + deq_b) / (ms_per_step * 1e-3) / 1e9
+    fused_gbps = fused_b / (fused_ms * 1e-3) / 1e9
+    result = {
+        "metric": "ECQ quantize+error-update GB/s (% HBM peak), 25M-elem grad, P=8",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: P={P} workers x N={N} fp32, bucket {wl.bucket}, s={wl.s} "
+                               f"({E.code_bits(wl.s)}-bit codes), alpha={wl.alpha}, beta={wl.beta}; "
+                               "step = fused quantise+error-update over all workers, then dequantise+average",
+                   "workers": P, "n": N, "bucket": wl.bucket, "s": wl.s},
+        "step_bytes": fused_b + deq_b,
+        "gelem_per_s": round(P * N / (ms_per_step * 1e-3) / 1e9, 2),
+        "fused": {"ms": round(fused_ms, 4), "GBps": round(fused_gbps, 1),
+                  "pct_hbm_peak": round(100 * fused_gbps / HBM_PEAK_GBPS, 2),
+                  "gelem_per_s": round(P * N / (fused_ms * 1e-3) / 1e9, 2), "bytes": fused_b},
+        "dequant_aggregate": {"ms": round(deq_ms, 4), "GBps": round(deq_b / (deq_ms * 1e-3) / 1e9, 1),
+                              "bytes": deq_b},
+        "roofline": {"bound": "hbm", "kernel": "ecq_quantize_update (fused single pass)",
+                     "achieved": round(fused_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(fused_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "fused_traffic.json")
+    if os.path.exists(traffic_file) and args.workload == "resnet50":
+        with open(traffic_file) as fh:
+            result["roofline"]["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
+    if not args.no_cpu_baseline:
+        n_s = min(N, max(wl.bucket, args.cpu_sample // wl.bucket * wl.bucket))
+        result["cpu_baseline"] = cpu_baseline(wl, n_s, pool[0][:, :n_s].cpu().numpy())
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
