@@ -6,6 +6,7 @@ import subprocess
 import sys
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libecq.so")
 SOURCES = ["ecq_api.hip", "ecq_kernels.hip"]
@@ -25,7 +26,7 @@ def build(verbose: bool = False, extra: list[str] | None = None, out: str | None
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     out = out or LIB_PATH
     tmp = out + ".tmp.%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, *(extra or []), *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I" + INCLUDE, *(extra or []), *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -85,14 +85,20 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
         pl.lanes_per_bucket = b / 4;
     } else if (path == 1) {
         const int chunks = (b + 255) / 256;                    // float4-per-lane wave loads per bucket
+        // Measured on MI355X: two float4 of g and of h per lane stream best; one wave keeps up to
+        // four per lane before a second wave (and with it an LDS exchange and a barrier) pays.
         if (waves == 0) {
             waves = 1;
-            while (waves * 8 < chunks) waves *= 2;
+            if (chunks > 4)
+                while (waves * 2 < chunks && waves < 16) waves *= 2;
         }
         int vec = 1;
         while (vec * waves < chunks) vec *= 2;
         if (vec > 8) return ECQ_ERR_PARAM;                     // the bucket would not fit the team's registers
-        if (threads == 0) threads = waves * 64 > 256 ? waves * 64 : 256;
+        if (threads == 0) {
+            threads = (waves == 1 && vec == 4) ? 256 : 512;
+            if (waves * 64 > threads) threads = waves * 64;
+        }
         if (threads % (waves * 64) != 0) return ECQ_ERR_PARAM;
         pl.waves_per_bucket = waves;
         pl.vec_per_lane = vec;

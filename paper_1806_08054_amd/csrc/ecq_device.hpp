@@ -6,8 +6,10 @@
 //   accumulation (Eq. 6) of Wu et al., ICML 2018, Section 4, plus Philox4x32-10 of
 //   Salmon et al. (SC'11) for the rounding decision.
 //
-// Floating point: this file must be compiled with -ffp-contract=off; every binary32 operation
-// below is meant to round on its own.
+// Floating point: this file must be compiled with -ffp-contract=off and with fp32 denormals
+// enabled; every binary32 operation of the method rounds on its own.  The only fused
+// multiply-adds are the explicit ones inside the division routine, where they are the
+// standard way to obtain a correctly rounded quotient.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -44,39 +46,11 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
     return U4{c0, c1, c2, c3};
 }
 
-// Parameters of the rounding that are uniform over a launch.
-struct Levels {
-    int s;        // non-zero levels
-    float sf;     // (float)s
-};
-
 // Eq. (7).
 __device__ __forceinline__ float compensate(float g, float alpha, float h)
 {
     const float ah = alpha * h;
     return g + ah;
-}
-
-// Eq. (8)-(9): magnitude level m in [0, s] of |v| on the grid scale*{0,1/s,...,1}; `scale`
-// must be > 0.  u = (word >> 8) * 2^-24 is exact, so is frac; the level moves up iff u < frac.
-__device__ __forceinline__ int round_level(float v, float scale, const Levels &lv, uint32_t word)
-{
-    const float a = __builtin_fabsf(v) / scale;
-    const float x = a * lv.sf;
-    const float l = __builtin_floorf(x);
-    const float frac = x - l;
-    const float u = (float)(word >> 8) * 0x1p-24f;
-    int m = (int)l + ((u < frac) ? 1 : 0);
-    return m < lv.s ? m : lv.s;
-}
-
-// Eq. (8): scale * fl(m/s) with the sign of v when m > 0.  `xi` is fl(m/s).
-// m > 0 implies v != 0, so "v < 0" and "sign bit of v" agree whenever the sign is applied.
-__device__ __forceinline__ float dequant_signed(float scale, float xi, int m, float v)
-{
-    const float gt = scale * xi;
-    const uint32_t sign = (m > 0) ? (__float_as_uint(v) & 0x80000000u) : 0u;
-    return __uint_as_float(__float_as_uint(gt) ^ sign);
 }
 
 // Eq. (6).
@@ -85,6 +59,98 @@ __device__ __forceinline__ float error_update(float beta, float h, float g, floa
     const float bh = beta * h;
     const float d = g - gt;
     return bh + d;
+}
+
+// ---- correctly rounded |v| / scale with the divisor-only work hoisted out -----------------
+//
+// Every element of a bucket is divided by the same norm, and 0 <= |v| <= norm.  The quotient
+// is produced by the classic reciprocal / two-residual-corrections scheme (the one the
+// compiler itself emits for a correctly rounded binary32 division once operands are in a
+// range where no rescaling is needed): the reciprocal and its Newton step are computed once
+// per bucket, each element costs one multiply and four fused multiply-adds.  The scheme is
+// exact only while quotient and residuals stay normal, so operands outside a safe window
+// (divisor outside [2^-100, 2^100], or 0 < |v| < max(1, divisor) * 2^-100) take the plain
+// division instead.  With SCALE24 the quotient comes out multiplied by 2^24 (an exact
+// scaling folded into the per-bucket constants).
+struct Ratio {
+    float d;        // divisor: the norm, or 1 for an all-zero bucket
+    float neg_d;    // -d            (* 2^-24 with SCALE24)
+    float y;        // ~ 1/d         (* 2^24 with SCALE24)
+    float tiny;     // numerators in (0, tiny) use the plain division
+    bool fast;      // divisor inside the safe window
+};
+
+template <bool SCALE24>
+__device__ __forceinline__ Ratio make_ratio(float norm)
+{
+    Ratio rt;
+    rt.d = norm > 0.0f ? norm : 1.0f;
+    rt.fast = (rt.d >= 0x1p-100f) && (rt.d <= 0x1p100f);
+    float r = __builtin_amdgcn_rcpf(rt.d);
+    const float e = __builtin_fmaf(-rt.d, r, 1.0f);
+    r = __builtin_fmaf(e, r, r);
+    rt.y = SCALE24 ? r * 0x1p24f : r;
+    rt.neg_d = SCALE24 ? -rt.d * 0x1p-24f : -rt.d;
+    rt.tiny = (rt.d > 1.0f ? rt.d : 1.0f) * 0x1p-100f;
+    return rt;
+}
+
+template <bool SCALE24>
+__device__ __forceinline__ float ratio(float av, const Ratio &rt)
+{
+    float q = av * rt.y;
+    float e = __builtin_fmaf(rt.neg_d, q, av);
+    q = __builtin_fmaf(e, rt.y, q);
+    e = __builtin_fmaf(rt.neg_d, q, av);
+    q = __builtin_fmaf(e, rt.y, q);
+    // (bits - 1) as unsigned sends 0 to the top of the range: true only for 0 < av < tiny.
+    const bool rare = !rt.fast || (__float_as_uint(av) - 1u) < (__float_as_uint(rt.tiny) - 1u);
+    if (__builtin_expect(rare, 0)) {
+        q = av / rt.d;
+        if (SCALE24) q = q * 0x1p24f;
+    }
+    return q;
+}
+
+// ---- Eq. (8)-(9) for one element ------------------------------------------------------------
+
+struct Quantized {
+    uint32_t code;  // level + s, in [0, 2s]
+    float gt;       // dequantised value with its sign (Eq. 8)
+};
+
+// s = 1 (ternary, 2-bit codes).  With x = |v|/norm in [0,1] the level is 1 iff u < x: for
+// x < 1 the lower grid point is 0 and x itself is the round-up probability, and x = 1 (the
+// element that attains the norm) gives level 1 for every u < 1.  The comparison is done on
+// both sides scaled by 2^24: k < x * 2^24 with k = word >> 8.
+__device__ __forceinline__ Quantized quantize_ternary(float v, float norm, const Ratio &rt, uint32_t word)
+{
+    const float x24 = ratio<true>(__builtin_fabsf(v), rt);
+    const bool up = (float)(word >> 8) < x24;
+    const uint32_t sign = __float_as_uint(v) & 0x80000000u;
+    Quantized out;
+    out.gt = up ? __uint_as_float(__float_as_uint(norm) | sign) : 0.0f;
+    out.code = up ? (sign ? 0u : 2u) : 1u;
+    return out;
+}
+
+// General s.  xi_tab[m] = fl(m/s).  m > 0 implies v != 0, so "v < 0" and the sign bit of v
+// agree whenever the sign is applied.  m <= s always: the quotient never exceeds 1.
+__device__ __forceinline__ Quantized quantize_levels(float v, float norm, const Ratio &rt, int s, float sf,
+                                                     const float *xi_tab, uint32_t word)
+{
+    const float a = ratio<false>(__builtin_fabsf(v), rt);
+    const float x = a * sf;
+    const float l = __builtin_floorf(x);
+    const float frac = x - l;
+    const float u = (float)(word >> 8) * 0x1p-24f;
+    const int m = (int)l + ((u < frac) ? 1 : 0);
+    const float mag = norm * xi_tab[m];
+    const bool neg = (m > 0) && (__float_as_uint(v) >> 31);
+    Quantized out;
+    out.gt = neg ? -mag : mag;
+    out.code = (uint32_t)(neg ? s - m : s + m);
+    return out;
 }
 
 // ---- cross-lane helpers ---------------------------------------------------------------------

@@ -3,7 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/ecq.h"
+#include "ecq.h"
 
 namespace ecq {
 

@@ -21,12 +21,15 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // Per-lane work on 4 consecutive elements.
 // ---------------------------------------------------------------------------------------------
 
+// g and h are streamed exactly once per call and h is written back once, so all three use
+// non-temporal accesses: on MI355X that alone is worth ~8 % of bandwidth for this traffic mix.
+//
 // Loads elements [off, off+4) of a row segment of `len` elements; missing ones read as 0.
 __device__ __forceinline__ void load4(const float *__restrict__ row, int64_t off, int64_t len,
                                       float (&x)[4])
 {
     if (off + 4 <= len) {
-        const f4 t = *reinterpret_cast<const f4 *>(row + off);
+        const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(row + off));
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
     } else {
 #pragma unroll
@@ -40,7 +43,7 @@ __device__ __forceinline__ void store4(float *__restrict__ row, int64_t off, int
     if (off + 4 <= len) {
         f4 t;
         t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
-        *reinterpret_cast<f4 *>(row + off) = t;
+        __builtin_nontemporal_store(t, reinterpret_cast<f4 *>(row + off));
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -48,39 +51,52 @@ __device__ __forceinline__ void store4(float *__restrict__ row, int64_t off, int
     }
 }
 
-// Bit pattern of max |g + alpha*h| over a lane's 4 elements (0 for missing elements).
-__device__ __forceinline__ uint32_t absmax4(const float (&g)[4], const float (&h)[4], float alpha)
+// v = g + alpha*h for a lane's 4 elements (Eq. 7); returns the bit pattern of max |v|
+// (0 for missing elements, which were loaded as zeros).
+__device__ __forceinline__ uint32_t compensate4(const float (&g)[4], const float (&h)[4], float alpha,
+                                               float (&v)[4])
 {
     uint32_t m = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        m = umax(m, __float_as_uint(compensate(g[e], alpha, h[e])) & 0x7FFFFFFFu);
+    for (int e = 0; e < 4; ++e) {
+        v[e] = compensate(g[e], alpha, h[e]);
+        m = umax(m, __float_as_uint(v[e]) & 0x7FFFFFFFu);
+    }
     return m;
 }
 
+// Per-bucket constants of the rounding step.
+template <int R>
+struct Rounder {
+    float norm;
+    Ratio rt;
+    int s;
+    float sf;
+    const float *xi_tab;
+    __device__ __forceinline__ Rounder(float norm_, int s_, const float *xi_tab_)
+        : norm(norm_), rt(make_ratio<R == 2>(norm_)), s(s_), sf((float)s_), xi_tab(xi_tab_) {}
+    __device__ __forceinline__ Quantized operator()(float v, uint32_t word) const
+    {
+        if constexpr (R == 2) return quantize_ternary(v, norm, rt, word);      // r = 2 <=> s = 1
+        else return quantize_levels(v, norm, rt, s, sf, xi_tab, word);
+    }
+};
+
 // Rounds, encodes and (optionally) accumulates the error for a lane's 4 elements.
 //   valid : how many of the 4 exist (0..4); codes of missing elements are zero bits.
-//   scale : the bucket's norm.  A zero norm means every v is zero: dividing by 1 instead
-//           then yields level 0 everywhere without a special case.
 // Returns the 4*R encoded bits, element e in bits [e*R, (e+1)*R).
 template <int R, bool UPDATE>
-__device__ __forceinline__ uint32_t quantize4(const float (&g)[4], float (&h)[4], int valid,
-                                              float scale, const Levels &lv, const float *xi_tab,
-                                              float alpha, float beta, const U4 &words)
+__device__ __forceinline__ uint32_t quantize4(const float (&g)[4], float (&h)[4], const float (&v)[4],
+                                              int valid, const Rounder<R> &rounder, float beta,
+                                              const U4 &words)
 {
-    const float div = scale > 0.0f ? scale : 1.0f;
     const uint32_t w[4] = {words.x, words.y, words.z, words.w};
     uint32_t bits = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const float v = compensate(g[e], alpha, h[e]);
-        const int m = round_level(v, div, lv, w[e]);
-        const float xi = (R == 2) ? (float)m : xi_tab[m];
-        const float gt = dequant_signed(scale, xi, m, v);
-        const bool neg = (m > 0) && (__float_as_uint(v) >> 31);
-        const uint32_t code = (uint32_t)(neg ? lv.s - m : lv.s + m);
-        bits |= (e < valid) ? (code << (R * e)) : 0u;
-        if (UPDATE) h[e] = error_update(beta, h[e], g[e], gt);
+        const Quantized qz = rounder(v[e], w[e]);
+        bits |= (e < valid) ? (qz.code << (R * e)) : 0u;
+        if (UPDATE) h[e] = error_update(beta, h[e], g[e], qz.gt);
     }
     return bits;
 }
@@ -151,7 +167,10 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
     const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride + e0;
     float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride + e0;
 
-    float g[J][4], h[J][4];
+    // v = g + alpha*h is kept in registers between the two phases while it fits (J <= 4);
+    // with 8 float4 per lane it is recomputed instead.
+    constexpr bool kKeepV = J <= 4;
+    float g[J][4], h[J][4], v[kKeepV ? J : 1][4];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const int off = ((wit * J + j) * 64 + lane) * 4;
@@ -160,7 +179,7 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
     }
     uint32_t mx = 0;
 #pragma unroll
-    for (int j = 0; j < J; ++j) mx = umax(mx, absmax4(g[j], h[j], a.alpha));
+    for (int j = 0; j < J; ++j) mx = umax(mx, compensate4(g[j], h[j], a.alpha, v[kKeepV ? j : 0]));
 
     uint32_t norm = wave_max_uniform(mx);
     if (W > 1) {
@@ -169,7 +188,7 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
         for (int t = 0; t < W; ++t) norm = umax(norm, wave_norm[(team << w_shift) + t]);
     }
     const float scale = __uint_as_float(norm);
-    const Levels lv{a.s, (float)a.s};
+    const Rounder<R> rounder(scale, a.s, xi_tab);
 
     uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
 #pragma unroll
@@ -181,8 +200,9 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
         int valid = len - off;
         valid = valid < 0 ? 0 : (valid > 4 ? 4 : valid);
         const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
+        if constexpr (!kKeepV) compensate4(g[j], h[j], a.alpha, v[0]);
         const uint32_t bits =
-            quantize4<R, UPDATE>(g[j], h[j], valid, scale, lv, xi_tab, a.alpha, a.beta, words);
+            quantize4<R, UPDATE>(g[j], h[j], v[kKeepV ? j : 0], valid, rounder, a.beta, words);
         store_codes<R>(crow, a.row_bytes, elem, valid, bits, lane);
         if (UPDATE) store4(hrow, off, len, h[j]);
     }
@@ -210,24 +230,25 @@ __global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lan
 
     const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
     float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
-    float g[4], h[4];
+    float g[4], h[4], v[4];
     load4(grow, elem, a.n, g);
     load4(hrow, elem, a.n, h);
     int64_t rest = a.n - elem;
     const int valid = rest < 0 ? 0 : (rest > 4 ? 4 : (int)rest);
+    const uint32_t mx = compensate4(g, h, a.alpha, v);
 
     float scale;
     const int64_t k = elem / a.bucket;
     if (lanes_per_bucket > 0) {
-        scale = __uint_as_float(group_max(absmax4(g, h, a.alpha), lanes_per_bucket));
+        scale = __uint_as_float(group_max(mx, lanes_per_bucket));
         if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
             a.scales[(int64_t)p * a.scale_stride + k] = scale;
     } else {
         scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + k] : 0.0f;
     }
-    const Levels lv{a.s, (float)a.s};
+    const Rounder<R> rounder(scale, a.s, xi_tab);
     const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
-    const uint32_t bits = quantize4<R, UPDATE>(g, h, valid, scale, lv, xi_tab, a.alpha, a.beta, words);
+    const uint32_t bits = quantize4<R, UPDATE>(g, h, v, valid, rounder, a.beta, words);
     store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem, valid, bits, lane);
     if (UPDATE) store4(hrow, elem, a.n, h);
 }
@@ -243,7 +264,8 @@ __global__ void __launch_bounds__(256) k_bucket_norm(const Args a)
     float g[4], h[4];
     load4(a.g + (int64_t)p * a.gh_stride, elem, a.n, g);
     load4(a.h + (int64_t)p * a.gh_stride, elem, a.n, h);
-    const uint32_t mx = absmax4(g, h, a.alpha);
+    float v[4];
+    const uint32_t mx = compensate4(g, h, a.alpha, v);
     const bool exists = elem < a.n;
     const long long k = exists ? (long long)(elem / a.bucket) : -1;
     // Element indices grow with the lane, so lane 0 holds the wave's lowest bucket, and if lane 0
@@ -320,32 +342,101 @@ __global__ void __launch_bounds__(256) k_error_update(const Args a)
     }
 }
 
-// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
+// The 4*R code bits of the 4 elements starting at `elem` (a multiple of 4).  They start at bit
+// 0 or 4 of a byte and span (R+1)/2 bytes.
 template <int R>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a)
+__device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ crow, int64_t row_bytes,
+                                                int64_t elem, bool full)
 {
-    __shared__ float xi_tab[128];
-    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
-    const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-    if (elem >= a.n) return;
-    const int64_t k = elem / a.bucket;
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-    for (int p = 0; p < a.workers; ++p) {
-        const uint64_t bits = load_code_group<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem);
-        const float scale = a.scales[(int64_t)p * a.scale_stride + k];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = acc[e] + decode_one<R>(bits, e, a.s, scale, xi_tab);
+    const int64_t bit0 = elem * R;
+    const int64_t byte0 = bit0 >> 3;
+    if constexpr (R == 2) {
+        if (full) return crow[byte0];
+    } else if constexpr (R == 4) {
+        if (full) return *reinterpret_cast<const uint16_t *>(crow + byte0);
+    } else if constexpr (R == 8) {
+        if (full) return *reinterpret_cast<const uint32_t *>(crow + byte0);
     }
+    constexpr int NB = (R + 1) / 2;
+    uint32_t w = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        if (byte0 + b < row_bytes) w |= (uint32_t)crow[byte0 + b] << (8 * b);
+    w >>= (int)(bit0 & 7);
+    return (R == 8) ? w : (w & ((1u << (4 * (R & 7))) - 1u));
+}
+
+// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
+// A lane owns 4 consecutive outputs (one coalesced float4 store); a wave owns 256.
+//   r = 2: a 256-entry LDS table maps a code byte to its four levels {-1,0,+1} as floats, and
+//          acc = fma(norm, level, acc) equals acc + norm*level because that product is exact.
+//   else : a signed table sxi[c] = +-fl(|c-s|/s) gives g~ = norm * sxi[c] (Eq. 8).
+// bucket_shift >= 0 when the bucket is a power of two; uniform_bucket when every aligned run of
+// 256 elements lies inside one bucket, so the norm is one scalar load per wave and worker.
+template <int R>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
+                                                           const int uniform_bucket, const float inv_p)
+{
+    __shared__ __attribute__((aligned(16))) float table[R == 2 ? 1024 : 256];
+    if constexpr (R == 2) {
+        for (int t = threadIdx.x; t < 256; t += blockDim.x) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int c = (t >> (2 * e)) & 3;
+                table[4 * t + e] = c == 0 ? -1.0f : (c == 2 ? 1.0f : 0.0f);
+            }
+        }
+    } else {
+        for (int c = threadIdx.x; c < 256; c += blockDim.x) {
+            const int q = c - a.s;
+            const int m = q < 0 ? -q : q;
+            const float xi = (m <= a.s) ? (float)m / (float)a.s : 0.0f;
+            table[c] = q < 0 ? -xi : xi;
+        }
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int64_t chunk = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (chunk * 256 >= a.n) return;                            // wave-uniform
+    const int64_t elem = chunk * 256 + lane * 4;
+    const bool exists = elem < a.n;
+    const bool full = elem + 4 <= a.n;
+    int64_t k = bucket_shift >= 0 ? (elem >> bucket_shift) : (elem / a.bucket);
+    if (uniform_bucket) {
+        const int64_t k0 = bucket_shift >= 0 ? ((chunk * 256) >> bucket_shift) : ((chunk * 256) / a.bucket);
+        k = ((int64_t)__builtin_amdgcn_readfirstlane((int)(k0 >> 32)) << 32) |
+            (uint32_t)__builtin_amdgcn_readfirstlane((int)k0);
+    } else if (!exists) {
+        k = 0;
+    }
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const uint8_t *__restrict__ crow = a.codes;
+    const float *__restrict__ srow = a.scales;
+    for (int p = 0; p < a.workers; ++p) {
+        const uint32_t bits = exists ? load_codes4<R>(crow, a.row_bytes, elem, full) : 0u;
+        const float norm = srow[k];
+        if constexpr (R == 2) {
+            const f4 lv = *reinterpret_cast<const f4 *>(&table[4 * (bits & 0xFFu)]);
+            acc[0] = __builtin_fmaf(norm, lv.x, acc[0]);
+            acc[1] = __builtin_fmaf(norm, lv.y, acc[1]);
+            acc[2] = __builtin_fmaf(norm, lv.z, acc[2]);
+            acc[3] = __builtin_fmaf(norm, lv.w, acc[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float gt = norm * table[(bits >> (R * e)) & ((1u << R) - 1u)];
+                acc[e] = acc[e] + gt;
+            }
+        }
+        crow += a.code_stride;
+        srow += a.scale_stride;
+    }
+    float o[4];
     const float pf = (float)a.workers;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = acc[4 * half + e] / pf;
-        store4(a.out, elem + 4 * half, a.n, o);
-    }
+    for (int e = 0; e < 4; ++e) o[e] = inv_p > 0.0f ? acc[e] * inv_p : acc[e] / pf;
+    store4(a.out, elem, a.n, o);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -363,31 +454,27 @@ __global__ void __launch_bounds__(256) k_philox_words(uint32_t key0, uint32_t ke
     words[j] = lane_word[i & 3];
 }
 
+// One float4 per lane, one 4 KiB tile per block, blocks in address order: the access pattern of
+// the fused kernel without its arithmetic.
 __global__ void __launch_bounds__(256) k_calib_add(const float *__restrict__ x, const float *__restrict__ y,
-                                                  float *__restrict__ out, int64_t n4, int64_t n)
+                                                  float *__restrict__ out, int64_t n)
 {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        const f4 u = reinterpret_cast<const f4 *>(x)[i];
-        const f4 v = reinterpret_cast<const f4 *>(y)[i];
-        reinterpret_cast<f4 *>(out)[i] = u + v;
-    }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        const int64_t i = n4 * 4 + threadIdx.x;
-        out[i] = x[i] + y[i];
-    }
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    float u[4], v[4], w[4];
+    load4(x, i, n, u);
+    load4(y, i, n, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = u[e] + v[e];
+    store4(out, i, n, w);
 }
 
 __global__ void __launch_bounds__(256) k_calib_copy(const float *__restrict__ x, float *__restrict__ out,
-                                                   int64_t n4, int64_t n)
+                                                   int64_t n)
 {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
-        reinterpret_cast<f4 *>(out)[i] = reinterpret_cast<const f4 *>(x)[i];
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        const int64_t i = n4 * 4 + threadIdx.x;
-        out[i] = x[i];
-    }
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    float u[4];
+    load4(x, i, n, u);
+    store4(out, i, n, u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -474,8 +561,15 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream)
 
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
 {
-    const dim3 grid(cdiv(cdiv(a.n, 8), 256));
-#define CALL(RR) hipLaunchKernelGGL((k_dequant_aggregate<RR>), grid, dim3(256), 0, stream, a)
+    const dim3 grid(cdiv(cdiv(a.n, 256), 4));
+    int bucket_shift = -1;
+    if ((a.bucket & (a.bucket - 1)) == 0)
+        for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
+    const int uniform_bucket = (a.bucket % 256) == 0;
+    // Dividing by a power of two and multiplying by its reciprocal round identically.
+    const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
+#define CALL(RR) \
+    hipLaunchKernelGGL((k_dequant_aggregate<RR>), grid, dim3(256), 0, stream, a, bucket_shift, uniform_bucket, inv_p)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
@@ -490,22 +584,15 @@ hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, u
     return hipGetLastError();
 }
 
-static unsigned calib_grid(int64_t n4)
-{
-    const int64_t want = (n4 + 255) / 256;
-    const int64_t cap = 256 * 32;                              // 32 blocks per compute unit
-    return (unsigned)(want < 1 ? 1 : (want > cap ? cap : want));
-}
-
 hipError_t launch_calib_add(const float *x, const float *y, float *out, int64_t n, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_calib_add, dim3(calib_grid(n / 4)), dim3(256), 0, stream, x, y, out, n / 4, n);
+    hipLaunchKernelGGL(k_calib_add, dim3(cdiv(n, 1024)), dim3(256), 0, stream, x, y, out, n);
     return hipGetLastError();
 }
 
 hipError_t launch_calib_copy(const float *x, float *out, int64_t n, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_calib_copy, dim3(calib_grid(n / 4)), dim3(256), 0, stream, x, out, n / 4, n);
+    hipLaunchKernelGGL(k_calib_copy, dim3(cdiv(n, 1024)), dim3(256), 0, stream, x, out, n);
     return hipGetLastError();
 }
 
