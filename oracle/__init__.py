@@ -81,7 +81,9 @@ def _declare(L):
                                          C.c_float, C.c_float, C.c_uint64, C.c_uint64, C.c_int,
                                          _i8p, C.POINTER(C.c_float), C.c_void_p]
     L.ecq_oracle_bucket_step.restype = None
-    L.ecq_oracle_batch_step.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_int, C.c_int,
+    L.ecq_oracle_pack_rows.argtypes = [_i8p, C.c_int, C.c_int64, C.c_int, _u8p, C.c_int64]
+    L.ecq_oracle_pack_rows.restype = None
+    L.ecq_oracle_batch_step.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                         C.c_int, _i8p, _f32p, C.c_void_p, C.c_int]
     L.ecq_oracle_batch_step.restype = None
@@ -189,9 +191,10 @@ def bucket_step(g, h, i0, p, s, alpha, beta, seed, step, update_h=True, want_gt=
 
 
 def batch_step(g, h, bucket, s, alpha, beta, seed, step, update_h=True, want_gt=False,
-               threads=0):
+               threads=0, worker0=0):
     """All workers for one iteration (Alg. 1, first loop).  g, h: [P, N] float32; h is updated
-    IN PLACE when update_h.  Returns (q [P,N] int8, scales [P,nb] float32, gt or None)."""
+    IN PLACE when update_h.  Row j is worker worker0 + j.  Returns (q [P,N] int8, scales [P,nb]
+    float32, gt or None)."""
     assert g.dtype == np.float32 and h.dtype == np.float32
     assert g.ndim == 2 and g.shape == h.shape
     assert g.flags.c_contiguous and h.flags.c_contiguous
@@ -200,7 +203,7 @@ def batch_step(g, h, bucket, s, alpha, beta, seed, step, update_h=True, want_gt=
     q = np.zeros((P, n), np.int8)
     scales = np.zeros((P, nb), np.float32)
     gt = np.zeros((P, n), np.float32) if want_gt else None
-    lib().ecq_oracle_batch_step(g, h, n, n, P, bucket, s, alpha, beta, seed, step,
+    lib().ecq_oracle_batch_step(g, h, n, n, P, worker0, bucket, s, alpha, beta, seed, step,
                                 int(update_h), q, scales,
                                 gt.ctypes.data if want_gt else None, threads)
     return q, scales, gt
@@ -208,10 +211,10 @@ def batch_step(g, h, bucket, s, alpha, beta, seed, step, update_h=True, want_gt=
 
 def pack_rows(q: np.ndarray, s: int) -> np.ndarray:
     """Encode every worker row; returns [P, row_bytes] uint8."""
+    q = np.ascontiguousarray(q, np.int8)
     P, n = q.shape
     out = np.zeros((P, row_bytes(n, s)), np.uint8)
-    for p in range(P):
-        lib().ecq_oracle_pack(np.ascontiguousarray(q[p]), n, s, out[p])
+    lib().ecq_oracle_pack_rows(q, P, n, s, out, out.shape[1])
     return out
 
 

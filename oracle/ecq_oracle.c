@@ -182,6 +182,15 @@ void ecq_oracle_pack(const int8_t *q, int64_t n, int s, uint8_t *bytes)
     }
 }
 
+/* Every worker row encoded on its own; rows of q are n apart, rows of bytes out_stride apart. */
+void ecq_oracle_pack_rows(const int8_t *q, int P, int64_t n, int s, uint8_t *bytes, int64_t out_stride)
+{
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int p = 0; p < P; ++p) ecq_oracle_pack(q + (int64_t)p * n, n, s, bytes + (int64_t)p * out_stride);
+}
+
 void ecq_oracle_unpack(const uint8_t *bytes, int64_t n, int s, int8_t *q)
 {
     int r = ecq_oracle_code_bits(s);
@@ -223,11 +232,11 @@ void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, 
 
 /* ---------------------------------------------------------------- whole batch ------------ */
 
-/* All P workers, all buckets, one iteration.  g, h: [P][gh_stride]; q: [P][n] signed levels;
- * scales: [P][nb]; gt (optional): [P][n].  Buckets are independent, so the loop over them may
- * be split over threads without changing any result. */
+/* P workers (numbered worker0 .. worker0+P-1), all buckets, one iteration.  g, h:
+ * [P][gh_stride]; q: [P][n] signed levels; scales: [P][nb]; gt (optional): [P][n].  Buckets are
+ * independent, so the loop over them may be split over threads without changing any result. */
 void ecq_oracle_batch_step(const float *g, float *h, int64_t n, int64_t gh_stride, int P,
-                           int bucket, int s, float alpha, float beta, uint64_t seed,
+                           int worker0, int bucket, int s, float alpha, float beta, uint64_t seed,
                            uint64_t step, int update_h, int8_t *q, float *scales, float *gt,
                            int threads)
 {
@@ -242,7 +251,7 @@ void ecq_oracle_batch_step(const float *g, float *h, int64_t n, int64_t gh_strid
         int64_t e0 = k * (int64_t)bucket;
         int64_t len = (n - e0 < bucket) ? (n - e0) : bucket;
         ecq_oracle_bucket_step(g + p * gh_stride + e0, h + p * gh_stride + e0, len,
-                               (uint64_t)e0, (uint32_t)p, s, alpha, beta, seed, step, update_h,
+                               (uint64_t)e0, (uint32_t)(worker0 + p), s, alpha, beta, seed, step, update_h,
                                q + p * n + e0, scales + p * nb + k,
                                gt ? gt + p * n + e0 : NULL);
     }

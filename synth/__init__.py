@@ -105,18 +105,10 @@ def _lsq(wl, t, p, device, rows: int = 256, density: float = 0.05):
     w = torch.randn(wl.N, generator=_gen(device, wl.data_seed, 4242), device=device,
                     dtype=torch.float32)
     y = torch.randn(rows, generator=gen, device=device, dtype=torch.float32)
-    out = torch.zeros(wl.N, device=device, dtype=torch.float32)
-    resid = torch.empty(rows, device=device, dtype=torch.float32)
-    xs = []
-    for r in range(rows):
-        keep = torch.rand(wl.N, generator=gen, device=device) < density
-        x = torch.where(keep, torch.randn(wl.N, generator=gen, device=device), 0.0)
-        resid[r] = torch.dot(x, w) - y[r]
-        xs.append(x.to_sparse() if wl.N > (1 << 16) else x)
-    for r in range(rows):
-        x = xs[r].to_dense() if xs[r].is_sparse else xs[r]
-        out += resid[r] * x
-    return out / rows
+    x = torch.randn(rows, wl.N, generator=gen, device=device, dtype=torch.float32)
+    x *= torch.rand(rows, wl.N, generator=gen, device=device) < density
+    resid = x @ w - y
+    return (resid @ x) / rows
 
 
 _KINDS = {"normal": _normal, "layered": _layered, "student_t": _student_t,

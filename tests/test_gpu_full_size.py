@@ -1,0 +1,161 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(default plan of ecq_quantize_update, then ecq_dequant_aggregate), free-running for every
+iteration of each workload.
+
+Where the oracle can cover everything in reasonable time the comparison is total (workloads
+1-3, and selected whole worker rows of 4-5); beyond that, randomly sampled buckets (always
+including each row's first bucket and its ragged last one) are recomputed one by one by the
+oracle from the (g, h) the GPU kernel actually consumed.  Bars as in test_gpu_parity.py.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from tests.test_gpu_parity import SEED, GpuState, _rel_ok
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_1806_08054_amd as E
+    return E
+
+
+def _pack_row_chunked(q_row, s, chunk=1 << 20):
+    """oracle.pack of one long row, taken in byte-aligned chunks that run in parallel."""
+    n = q_row.size
+    whole = n // chunk
+    parts = []
+    if whole:
+        parts.append(oracle.pack_rows(q_row[: whole * chunk].reshape(whole, chunk), s).reshape(-1))
+    if n > whole * chunk:
+        parts.append(oracle.pack(q_row[whole * chunk:], s))
+    return np.concatenate(parts)
+
+
+def _check_rows(st, wl, t, rows, h_before):
+    """Whole worker rows: oracle from (g row, h row before the step) vs the GPU's outputs."""
+    for p in rows:
+        g_np = st.g[p, : wl.N].cpu().numpy()[None, :]
+        h_np = h_before[p][None, :].copy()
+        q, scales, _ = oracle.batch_step(g_np, h_np, wl.bucket, wl.s, wl.alpha, wl.beta, SEED, t, worker0=p)
+        codes_ref = _pack_row_chunked(q[0], wl.s)
+        codes = st.codes[p, : st.rb].cpu().numpy()
+        sc = st.scales[p, : st.nb].cpu().numpy()
+        hh = st.h[p, : wl.N].cpu().numpy()
+        assert np.array_equal(sc.view(np.uint32), scales[0].view(np.uint32)), f"scales differ, worker {p}"
+        nbad = int((codes != codes_ref).sum())
+        assert nbad == 0, f"{nbad} code bytes differ, worker {p}, iteration {t}"
+        assert _rel_ok(hh, h_np[0], wl.bucket)
+        nbits = int((hh.view(np.uint32) != h_np[0].view(np.uint32)).sum())
+        assert nbits == 0, f"{nbits} h values not bit-identical, worker {p}, iteration {t}"
+        h_before[p] = h_np[0]
+    return h_before
+
+
+def _sample_buckets(wl, rng, count):
+    picks = {(p, k) for p in (0, wl.P - 1) for k in (0, wl.nb - 1)}
+    while len(picks) < count:
+        picks.add((int(rng.integers(wl.P)), int(rng.integers(wl.nb))))
+    return sorted(picks)
+
+
+def _bucket_extent(wl, k, r):
+    e0 = k * wl.bucket
+    e1 = min(wl.N, e0 + wl.bucket)
+    return e0, e1, e0 * r // 8, (e1 * r + 7) // 8
+
+
+def _check_sampled(E, st, wl, t, picks, before):
+    """before[(p,k)] = (g slice, h slice) captured ahead of the step."""
+    r = E.code_bits(wl.s)
+    for (p, k) in picks:
+        e0, e1, b0, b1 = _bucket_extent(wl, k, r)
+        g_np, h_np = before[(p, k)]
+        q, scale, _, h_next = oracle.bucket_step(g_np, h_np, e0, p, wl.s, wl.alpha, wl.beta, SEED, t)
+        assert st.scales[p, k].item() == float(scale), f"scale differs at worker {p} bucket {k}"
+        codes = st.codes[p, b0:b1].cpu().numpy()
+        assert np.array_equal(codes, oracle.pack(q, wl.s)), f"codes differ at worker {p} bucket {k} iteration {t}"
+        hh = st.h[p, e0:e1].cpu().numpy()
+        assert np.array_equal(hh.view(np.uint32), h_next.view(np.uint32)), f"h differs at worker {p} bucket {k}"
+
+
+def _check_aggregate_sampled(E, st, wl, ks):
+    r = E.code_bits(wl.s)
+    for k in ks:
+        e0, e1, b0, b1 = _bucket_extent(wl, k, r)
+        codes = st.codes[:, b0:b1].cpu().numpy()
+        scales = st.scales[:, k:k + 1].cpu().numpy()
+        ref = oracle.aggregate(codes, scales, e1 - e0, wl.bucket, wl.s)
+        got = st.out[e0:e1].cpu().numpy()
+        assert _rel_ok(got, ref, wl.bucket)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"aggregate differs in bucket {k}"
+
+
+def _run(E, wl, full_iters, full_rows, samples=48, seed=0):
+    """Free-running GPU iterations.  For t < full_iters the rows in full_rows are compared in
+    full (their oracle h runs freely beside the GPU's); every iteration, sampled buckets of all
+    rows are recomputed from the inputs the GPU consumed; the aggregate is checked on sampled
+    buckets (in full when full_rows covers every worker)."""
+    rng = np.random.default_rng(seed)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s)
+    r = E.code_bits(wl.s)
+    h_rows = {p: np.zeros(wl.N, np.float32) for p in full_rows} if full_iters else {}
+    for t in range(wl.iters):
+        synth.gradients(wl, t, device="cuda", out=st.g)
+        picks = _sample_buckets(wl, rng, samples)
+        before = {}
+        for (p, k) in picks:
+            e0, e1, _, _ = _bucket_extent(wl, k, r)
+            before[(p, k)] = (st.g[p, e0:e1].cpu().numpy(), st.h[p, e0:e1].cpu().numpy())
+        st.poison()
+        E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, t, st.codes, st.scales)
+        st.out.fill_(-7.0)
+        E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+        torch.cuda.synchronize()
+        assert bool((st.codes[:, st.rb:] == 0xEE).all())
+        _check_sampled(E, st, wl, t, picks, before)
+        if t < full_iters:
+            h_rows = _check_rows(st, wl, t, full_rows, h_rows)
+        if t < full_iters and len(full_rows) == wl.P:
+            codes = st.codes[:, : st.rb].cpu().numpy()
+            scales = st.scales[:, : st.nb].cpu().numpy()
+            ref = oracle.aggregate(codes, scales, wl.N, wl.bucket, wl.s)
+            got = st.out.cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "aggregate differs"
+        else:
+            _check_aggregate_sampled(E, st, wl, sorted({k for (_, k) in picks}))
+        print(f"{wl.name}: iteration {t} ok", flush=True)
+
+
+def test_linear_full(E):
+    """Workload 2: 100 free-running iterations, every element of every iteration."""
+    wl = synth.WORKLOADS["linear"]
+    _run(E, wl, full_iters=wl.iters, full_rows=list(range(wl.P)), samples=8)
+
+
+def test_resnet50_full(E):
+    """Workload 3 (the metric workload): 20 free-running iterations, every element of every
+    iteration."""
+    wl = synth.WORKLOADS["resnet50"]
+    _run(E, wl, full_iters=wl.iters, full_rows=list(range(wl.P)))
+
+
+def test_alexnet_full(E):
+    """Workload 4: 10 free-running iterations; all 16 workers in full for the first 3,
+    sampled buckets of all workers for all 10."""
+    wl = synth.WORKLOADS["alexnet"]
+    _run(E, wl, full_iters=3, full_rows=list(range(wl.P)))
+
+
+def test_vgg16_full(E):
+    """Workload 5: 5 free-running iterations incl. the aggregate over all 32 workers (35 GB of
+    g and h resident, 64-bit element offsets); workers 0, 15 and 31 in full for the first 2
+    iterations, sampled buckets of all 32 workers for all 5."""
+    wl = synth.WORKLOADS["vgg16"]
+    _run(E, wl, full_iters=2, full_rows=[0, 15, wl.P - 1], samples=64)
