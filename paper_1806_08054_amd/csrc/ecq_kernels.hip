@@ -366,18 +366,13 @@ __device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ crow
     return (R == 8) ? w : (w & ((1u << (4 * (R & 7))) - 1u));
 }
 
-// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
-// A lane owns 4 consecutive outputs (one coalesced float4 store); a wave owns 256.
-//   r = 2: a 256-entry LDS table maps a code byte to its four levels {-1,0,+1} as floats, and
+// Decode tables of the aggregation kernel, in LDS.
+//   r = 2: a 256-entry table maps a code byte to its four levels {-1,0,+1} as floats;
 //          acc = fma(norm, level, acc) equals acc + norm*level because that product is exact.
 //   else : a signed table sxi[c] = +-fl(|c-s|/s) gives g~ = norm * sxi[c] (Eq. 8).
-// bucket_shift >= 0 when the bucket is a power of two; uniform_bucket when every aligned run of
-// 256 elements lies inside one bucket, so the norm is one scalar load per wave and worker.
 template <int R>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
-                                                           const int uniform_bucket, const float inv_p)
+__device__ __forceinline__ void fill_agg_table(float *table, int s)
 {
-    __shared__ __attribute__((aligned(16))) float table[R == 2 ? 1024 : 256];
     if constexpr (R == 2) {
         for (int t = threadIdx.x; t < 256; t += blockDim.x) {
 #pragma unroll
@@ -388,55 +383,165 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         }
     } else {
         for (int c = threadIdx.x; c < 256; c += blockDim.x) {
-            const int q = c - a.s;
+            const int q = c - s;
             const int m = q < 0 ? -q : q;
-            const float xi = (m <= a.s) ? (float)m / (float)a.s : 0.0f;
+            const float xi = (m <= s) ? (float)m / (float)s : 0.0f;
             table[c] = q < 0 ? -xi : xi;
         }
     }
     __syncthreads();
+}
 
-    const int lane = threadIdx.x & 63;
-    const int64_t chunk = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (chunk * 256 >= a.n) return;                            // wave-uniform
-    const int64_t elem = chunk * 256 + lane * 4;
+// sum += one worker's dequantised values for a lane's 4 elements.
+template <int R>
+__device__ __forceinline__ void agg_add(const float *table, uint32_t bits, float norm, float (&sum)[4])
+{
+    if constexpr (R == 2) {
+        const f4 lv = *reinterpret_cast<const f4 *>(&table[4 * (bits & 0xFFu)]);
+        sum[0] = __builtin_fmaf(norm, lv.x, sum[0]);
+        sum[1] = __builtin_fmaf(norm, lv.y, sum[1]);
+        sum[2] = __builtin_fmaf(norm, lv.z, sum[2]);
+        sum[3] = __builtin_fmaf(norm, lv.w, sum[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float gt = norm * table[(bits >> (R * e)) & ((1u << R) - 1u)];
+            sum[e] = sum[e] + gt;
+        }
+    }
+}
+
+// One run of 256 outputs starting at `run`, any bucket size, ragged end allowed: the slow,
+// fully guarded route (per-lane bucket index, one worker at a time).
+template <int R>
+__device__ __forceinline__ void agg_run_guarded(const Args &a, const float *table, int64_t run, int lane,
+                                             int bucket_shift, float inv_p)
+{
+    const int64_t elem = run + lane * 4;
     const bool exists = elem < a.n;
     const bool full = elem + 4 <= a.n;
-    int64_t k = bucket_shift >= 0 ? (elem >> bucket_shift) : (elem / a.bucket);
-    if (uniform_bucket) {
-        const int64_t k0 = bucket_shift >= 0 ? ((chunk * 256) >> bucket_shift) : ((chunk * 256) / a.bucket);
-        k = ((int64_t)__builtin_amdgcn_readfirstlane((int)(k0 >> 32)) << 32) |
-            (uint32_t)__builtin_amdgcn_readfirstlane((int)k0);
-    } else if (!exists) {
-        k = 0;
-    }
+    const int64_t k = !exists ? 0 : (bucket_shift >= 0 ? (elem >> bucket_shift) : (elem / a.bucket));
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     const uint8_t *__restrict__ crow = a.codes;
     const float *__restrict__ srow = a.scales;
     for (int p = 0; p < a.workers; ++p) {
         const uint32_t bits = exists ? load_codes4<R>(crow, a.row_bytes, elem, full) : 0u;
-        const float norm = srow[k];
-        if constexpr (R == 2) {
-            const f4 lv = *reinterpret_cast<const f4 *>(&table[4 * (bits & 0xFFu)]);
-            acc[0] = __builtin_fmaf(norm, lv.x, acc[0]);
-            acc[1] = __builtin_fmaf(norm, lv.y, acc[1]);
-            acc[2] = __builtin_fmaf(norm, lv.z, acc[2]);
-            acc[3] = __builtin_fmaf(norm, lv.w, acc[3]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float gt = norm * table[(bits >> (R * e)) & ((1u << R) - 1u)];
-                acc[e] = acc[e] + gt;
-            }
-        }
+        agg_add<R>(table, bits, srow[k], acc);
         crow += a.code_stride;
         srow += a.scale_stride;
     }
-    float o[4];
     const float pf = (float)a.workers;
+    float o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = inv_p > 0.0f ? acc[e] * inv_p : acc[e] / pf;
     store4(a.out, elem, a.n, o);
+}
+
+// The 4*R code bits at bit offset `bitoff` (a multiple of 4) from `tile`, no bounds checks.
+template <int R>
+__device__ __forceinline__ uint32_t load_codes4_inner(const uint8_t *__restrict__ tile, uint32_t bitoff)
+{
+    const uint32_t byte0 = bitoff >> 3;
+    if constexpr (R == 2) {
+        return tile[byte0];
+    } else if constexpr (R == 4) {
+        return *reinterpret_cast<const uint16_t *>(tile + byte0);
+    } else if constexpr (R == 8) {
+        return *reinterpret_cast<const uint32_t *>(tile + byte0);
+    } else {
+        constexpr int NB = (R + 1) / 2;
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) w |= (uint32_t)tile[byte0 + b] << (8 * b);
+        return (w >> (bitoff & 7u)) & ((1u << (4 * R)) - 1u);
+    }
+}
+
+// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
+// A wave owns J runs of 256 consecutive outputs, a lane 4 consecutive outputs of each
+// (coalesced float4 stores).  When every run lies inside one bucket (bucket a multiple of 256)
+// and the tile is complete, the norms are scalar loads and four workers' codes and norms are
+// in flight together; anything else goes through agg_run_guarded.
+// bucket_shift >= 0 when the bucket is a power of two.
+template <int R, int J>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
+                                                           const int uniform_bucket, const float inv_p)
+{
+    __shared__ __attribute__((aligned(16))) float table[R == 2 ? 1024 : 256];
+    fill_agg_table<R>(table, a.s);
+
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    int64_t base = tile * (256 * J);
+    base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+    if (base >= a.n) return;                                   // wave-uniform
+    if (!uniform_bucket || base + 256 * J > a.n) {
+#pragma unroll 1
+        for (int j = 0; j < J; ++j)
+            if (base + j * 256 < a.n) agg_run_guarded<R>(a, table, base + j * 256, lane, bucket_shift, inv_p);
+        return;
+    }
+
+    // Bucket of each run (wave-uniform): that of the tile's first element, advanced by the
+    // remainder arithmetic in 32 bits.
+    const int64_t k0 = bucket_shift >= 0 ? (base >> bucket_shift) : (base / a.bucket);
+    const uint32_t rem = (uint32_t)(base - k0 * a.bucket);
+    int64_t k[J];
+    uint32_t bitoff[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t r = rem + 256u * j;
+        k[j] = k0 + (bucket_shift >= 0 ? (r >> bucket_shift) : (r / (uint32_t)a.bucket));
+        bitoff[j] = (uint32_t)(j * 256 + lane * 4) * R;
+    }
+
+    float acc[J][4];
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] = 0.0f;
+
+    const uint8_t *__restrict__ ctile = a.codes + ((base * R) >> 3);
+    const float *__restrict__ srow = a.scales;
+    int p = 0;
+    for (; p + U <= a.workers; p += U) {
+        uint32_t bits[U][J];
+        float norm[U][J];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                bits[u][j] = load_codes4_inner<R>(ctile + u * a.code_stride, bitoff[j]);
+                norm[u][j] = srow[u * a.scale_stride + k[j]];
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)                           // workers in index order
+#pragma unroll
+            for (int j = 0; j < J; ++j) agg_add<R>(table, bits[u][j], norm[u][j], acc[j]);
+        ctile += U * a.code_stride;
+        srow += U * a.scale_stride;
+    }
+    for (; p < a.workers; ++p) {
+#pragma unroll
+        for (int j = 0; j < J; ++j) agg_add<R>(table, load_codes4_inner<R>(ctile, bitoff[j]), srow[k[j]], acc[j]);
+        ctile += a.code_stride;
+        srow += a.scale_stride;
+    }
+
+    const float pf = (float)a.workers;
+    float *__restrict__ otile = a.out + base;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        f4 o;
+        if (inv_p > 0.0f) {
+            o.x = acc[j][0] * inv_p; o.y = acc[j][1] * inv_p; o.z = acc[j][2] * inv_p; o.w = acc[j][3] * inv_p;
+        } else {
+            o.x = acc[j][0] / pf; o.y = acc[j][1] / pf; o.z = acc[j][2] / pf; o.w = acc[j][3] / pf;
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(otile + j * 256 + lane * 4));
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -561,15 +666,22 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream)
 
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
 {
-    const dim3 grid(cdiv(cdiv(a.n, 256), 4));
+    // Four runs per wave once there are enough outputs to fill the chip with such waves.
+    const int vec = a.n >= ((int64_t)1 << 22) ? 4 : 1;
+    const dim3 grid(cdiv(cdiv(a.n, 256 * vec), 4));
     int bucket_shift = -1;
     if ((a.bucket & (a.bucket - 1)) == 0)
         for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
     const int uniform_bucket = (a.bucket % 256) == 0;
     // Dividing by a power of two and multiplying by its reciprocal round identically.
     const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
-#define CALL(RR) \
-    hipLaunchKernelGGL((k_dequant_aggregate<RR>), grid, dim3(256), 0, stream, a, bucket_shift, uniform_bucket, inv_p)
+#define CALL(RR)                                                                                              \
+    if (vec == 4)                                                                                             \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, 4>), grid, dim3(256), 0, stream, a, bucket_shift,         \
+                           uniform_bucket, inv_p);                                                            \
+    else                                                                                                      \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, 1>), grid, dim3(256), 0, stream, a, bucket_shift,         \
+                           uniform_bucket, inv_p)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
