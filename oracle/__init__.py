@@ -63,6 +63,8 @@ def _declare(L):
     L.ecq_oracle_compensate.restype = C.c_float
     L.ecq_oracle_bucket_scale.argtypes = [_f32p, C.c_int64]
     L.ecq_oracle_bucket_scale.restype = C.c_float
+    L.ecq_oracle_bucket_scale_l2.argtypes = [_f32p, C.c_int64]
+    L.ecq_oracle_bucket_scale_l2.restype = C.c_float
     L.ecq_oracle_round.argtypes = [C.c_float, C.c_float, C.c_int, C.c_uint32]
     L.ecq_oracle_round.restype = C.c_int
     L.ecq_oracle_dequant.argtypes = [C.c_int, C.c_float, C.c_int]
@@ -79,13 +81,13 @@ def _declare(L):
     L.ecq_oracle_unpack.restype = None
     L.ecq_oracle_bucket_step.argtypes = [_f32p, _f32p, C.c_int64, C.c_uint64, C.c_uint32, C.c_int,
                                          C.c_float, C.c_float, C.c_uint64, C.c_uint64, C.c_int,
-                                         _i8p, C.POINTER(C.c_float), C.c_void_p]
+                                         _i8p, C.POINTER(C.c_float), C.c_void_p, C.c_int]
     L.ecq_oracle_bucket_step.restype = None
     L.ecq_oracle_pack_rows.argtypes = [_i8p, C.c_int, C.c_int64, C.c_int, _u8p, C.c_int64]
     L.ecq_oracle_pack_rows.restype = None
     L.ecq_oracle_batch_step.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
-                                        C.c_int, _i8p, _f32p, C.c_void_p, C.c_int]
+                                        C.c_int, _i8p, _f32p, C.c_void_p, C.c_int, C.c_int]
     L.ecq_oracle_batch_step.restype = None
     L.ecq_oracle_max_threads.argtypes = []
     L.ecq_oracle_max_threads.restype = C.c_int
@@ -136,6 +138,12 @@ def bucket_scale(v: np.ndarray) -> np.float32:
     return np.float32(lib().ecq_oracle_bucket_scale(v, v.size))
 
 
+def bucket_scale_l2(v: np.ndarray) -> np.float32:
+    """l_2 norm of a bucket: tree sum of fl(v_i^2) by index, then sqrt."""
+    v = np.ascontiguousarray(v, np.float32)
+    return np.float32(lib().ecq_oracle_bucket_scale_l2(v, v.size))
+
+
 def round_level(v: float, scale: float, s: int, w: int) -> int:
     """Eq. (8)-(9): signed level for one element."""
     return int(lib().ecq_oracle_round(v, scale, s, w))
@@ -177,7 +185,11 @@ def unpack(codes: np.ndarray, n: int, s: int) -> np.ndarray:
 
 # ------------------------------------------------------------------ buckets and batches -----
 
-def bucket_step(g, h, i0, p, s, alpha, beta, seed, step, update_h=True, want_gt=True):
+def _norm_flag(norm) -> int:
+    return {"linf": 0, "l2": 1, 0: 0, 1: 1}[norm]
+
+
+def bucket_step(g, h, i0, p, s, alpha, beta, seed, step, update_h=True, want_gt=True, norm="linf"):
     """One bucket of one worker for one iteration.  Returns (q, scale, gt, h_next)."""
     g = np.ascontiguousarray(g, np.float32)
     h = np.array(h, np.float32, copy=True)
@@ -186,12 +198,12 @@ def bucket_step(g, h, i0, p, s, alpha, beta, seed, step, update_h=True, want_gt=
     gt = np.zeros(n, np.float32) if want_gt else None
     sc = C.c_float(0.0)
     lib().ecq_oracle_bucket_step(g, h, n, i0, p, s, alpha, beta, seed, step, int(update_h), q,
-                                 C.byref(sc), gt.ctypes.data if want_gt else None)
+                                 C.byref(sc), gt.ctypes.data if want_gt else None, _norm_flag(norm))
     return q, np.float32(sc.value), gt, h
 
 
 def batch_step(g, h, bucket, s, alpha, beta, seed, step, update_h=True, want_gt=False,
-               threads=0, worker0=0):
+               threads=0, worker0=0, norm="linf"):
     """All workers for one iteration (Alg. 1, first loop).  g, h: [P, N] float32; h is updated
     IN PLACE when update_h.  Row j is worker worker0 + j.  Returns (q [P,N] int8, scales [P,nb]
     float32, gt or None)."""
@@ -205,7 +217,7 @@ def batch_step(g, h, bucket, s, alpha, beta, seed, step, update_h=True, want_gt=
     gt = np.zeros((P, n), np.float32) if want_gt else None
     lib().ecq_oracle_batch_step(g, h, n, n, P, worker0, bucket, s, alpha, beta, seed, step,
                                 int(update_h), q, scales,
-                                gt.ctypes.data if want_gt else None, threads)
+                                gt.ctypes.data if want_gt else None, threads, _norm_flag(norm))
     return q, scales, gt
 
 

@@ -23,8 +23,12 @@
  * instead by an exact-rational re-derivation in the tests).
  *
  * Points the paper leaves open and the reading taken here:
- *   - norm: l_inf (max-abs) per bucket; a bucket is a run of `bucket` consecutive elements of
- *     the flat per-worker vector, the last one possibly short.
+ *   - norm: l_inf (max-abs) per bucket by default; a bucket is a run of `bucket` consecutive
+ *     elements of the flat per-worker vector, the last one possibly short.  The l_2 norm (the
+ *     other choice the paper names, and the one its Lemma 1 covers) is sqrt of the sum of the
+ *     squares fl(v_i*v_i), the sum taken over a balanced binary tree by element index (the
+ *     bucket padded with zeros to a power of two), then one correctly rounded square root.
+ *     (The computed l_2 norm is never below max|v_i|, so the ratio stays <= 1 here too.)
  *   - ||v|| = 0: every level 0, scale 0.
  *   - |v_i| = ||v|| (outside every half-open interval of Eq. (9)): l = s, never rounds up.
  *   - sgn: level is negated iff v_i < 0; level 0 has no sign.
@@ -41,6 +45,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -118,6 +123,25 @@ float ecq_oracle_bucket_scale(const float *v, int64_t len)
         if (a > m) m = a;
     }
     return m;
+}
+
+/* Sum of fl(v_i^2) over indices [lo, lo+width) of a bucket of `len` elements, width a power of
+ * two: the two halves are summed on their own and then added; indices >= len count as 0. */
+static float sum_squares_tree(const float *v, int64_t lo, int64_t width, int64_t len)
+{
+    if (lo >= len) return 0.0f;
+    if (width == 1) return v[lo] * v[lo];
+    float left = sum_squares_tree(v, lo, width / 2, len);
+    float right = sum_squares_tree(v, lo + width / 2, width / 2, len);
+    return left + right;
+}
+
+/* l_2 norm of one bucket, with the summation order stated in the header. */
+float ecq_oracle_bucket_scale_l2(const float *v, int64_t len)
+{
+    int64_t width = 1;
+    while (width < len) width *= 2;
+    return sqrtf(sum_squares_tree(v, 0, width, len));
 }
 
 /* Eq. (8)-(9) for one element: signed level q in [-s, s] given the bucket's scale and the
@@ -211,12 +235,19 @@ void ecq_oracle_unpack(const uint8_t *bytes, int64_t n, int s, int8_t *q)
  * flat vector, of g[0]/h[0].  gt may be NULL.  If update_h is 0, h is left as it is. */
 void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, uint32_t p,
                             int s, float alpha, float beta, uint64_t seed, uint64_t step,
-                            int update_h, int8_t *q, float *scale_out, float *gt)
+                            int update_h, int8_t *q, float *scale_out, float *gt, int norm_l2)
 {
     float scale = 0.0f;
-    for (int64_t i = 0; i < len; ++i) {
-        float a = fabsf(ecq_oracle_compensate(g[i], alpha, h[i]));
-        if (a > scale) scale = a;
+    if (norm_l2) {
+        float *v = (float *)malloc(sizeof(float) * (size_t)(len > 0 ? len : 1));
+        for (int64_t i = 0; i < len; ++i) v[i] = ecq_oracle_compensate(g[i], alpha, h[i]);
+        scale = ecq_oracle_bucket_scale_l2(v, len);
+        free(v);
+    } else {
+        for (int64_t i = 0; i < len; ++i) {
+            float a = fabsf(ecq_oracle_compensate(g[i], alpha, h[i]));
+            if (a > scale) scale = a;
+        }
     }
     *scale_out = scale;
     for (int64_t i = 0; i < len; ++i) {
@@ -238,7 +269,7 @@ void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, 
 void ecq_oracle_batch_step(const float *g, float *h, int64_t n, int64_t gh_stride, int P,
                            int worker0, int bucket, int s, float alpha, float beta, uint64_t seed,
                            uint64_t step, int update_h, int8_t *q, float *scales, float *gt,
-                           int threads)
+                           int threads, int norm_l2)
 {
     int64_t nb = (n + bucket - 1) / bucket;
     int64_t units = (int64_t)P * nb;
@@ -253,7 +284,7 @@ void ecq_oracle_batch_step(const float *g, float *h, int64_t n, int64_t gh_strid
         ecq_oracle_bucket_step(g + p * gh_stride + e0, h + p * gh_stride + e0, len,
                                (uint64_t)e0, (uint32_t)(worker0 + p), s, alpha, beta, seed, step, update_h,
                                q + p * n + e0, scales + p * nb + k,
-                               gt ? gt + p * n + e0 : NULL);
+                               gt ? gt + p * n + e0 : NULL, norm_l2);
     }
     (void)threads;
 }

@@ -10,6 +10,7 @@ Citations are to Wu et al., "Error Compensated Quantized SGD ..." (ICML 2018), S
 """
 from __future__ import annotations
 
+import math
 import struct
 from fractions import Fraction
 
@@ -91,7 +92,51 @@ def code_bits(s: int) -> int:
     return r
 
 
-def bucket_step(g, h, i0, p, s, alpha, beta, seed, step):
+def rn32_sqrt(q: Fraction) -> Fraction:
+    """Correctly rounded binary32 square root of an exact non-negative rational."""
+    if q == 0:
+        return Fraction(0)
+    # scale by 4^k so that the integer square root carries well over 24 bits
+    k = 0
+    while q * Fraction(4) ** k < (1 << 60):
+        k += 1
+    while q * Fraction(4) ** k >= (1 << 64):
+        k -= 1
+    scaled = q * Fraction(4) ** k                  # sqrt(q) = sqrt(scaled) / 2^k
+    n = scaled.numerator // scaled.denominator
+    r = math.isqrt(n)                              # floor(sqrt(floor(scaled))) = floor(sqrt(scaled))
+    # candidates on the binary32 grid around r / 2^k: round r to 24 significant bits both ways
+    shift = r.bit_length() - _P
+    lo = (r >> shift) << shift
+    hi = lo + (1 << shift)
+    mid = lo + (1 << (shift - 1))
+    # compare sqrt(scaled) with mid exactly: scaled vs mid^2
+    if scaled > mid * mid or (scaled == mid * mid and ((lo >> shift) & 1)):
+        pick = hi
+    else:
+        pick = lo
+    out = Fraction(pick) / Fraction(2) ** k
+    assert rn32(out) == out, "result must be a binary32 value (no denormal results modelled)"
+    return out
+
+
+def tree_sum_squares(v, lo, width):
+    """Balanced binary tree by index; one rounding per square and per addition."""
+    if lo >= len(v):
+        return Fraction(0)
+    if width == 1:
+        return rn32(v[lo] * v[lo])
+    return rn32(tree_sum_squares(v, lo, width // 2) + tree_sum_squares(v, lo + width // 2, width // 2))
+
+
+def norm_l2(v):
+    width = 1
+    while width < len(v):
+        width *= 2
+    return rn32_sqrt(tree_sum_squares(v, 0, width))
+
+
+def bucket_step(g, h, i0, p, s, alpha, beta, seed, step, norm="linf"):
     """One bucket, exact rationals with one rounding per binary32 operation.
 
     g, h: lists of Python floats holding binary32 values; alpha, beta binary32 values.
@@ -104,7 +149,7 @@ def bucket_step(g, h, i0, p, s, alpha, beta, seed, step):
     neg = []
     for gi, hi, vi in zip(g, h, v):
         neg.append(vi < 0)
-    scale = max((abs(x) for x in v), default=Fraction(0))
+    scale = max((abs(x) for x in v), default=Fraction(0)) if norm == "linf" else norm_l2(v)
     q, gt, hn = [], [], []
     for j, (gi, hi, vi) in enumerate(zip(G, H, v)):
         if scale == 0:

@@ -461,3 +461,117 @@ def test_error_update_from_message_equals_fused_step():
     h2 = h0[0].copy()
     oracle.error_update_row(g[0], oracle.pack(q[0], s), scales[0], bucket, s, 0.8, h2)
     assert np.array_equal(h2, h[0])
+
+
+# ------------------------------------------------------------------ l_2 scaling ------------
+
+@pytest.mark.parametrize("kind", ["normal", "mixed", "lattice"])
+@pytest.mark.parametrize("s", [1, 4, 7])
+def test_l2_bucket_matches_exact_rational_model(kind, s):
+    """The l_2 route against exact rationals: squares, the balanced tree by index, one
+    correctly rounded square root, then Eq. (7)-(9), (6) as before."""
+    rng = np.random.default_rng([7, len(kind), s])
+    alpha, beta = f32(0.2), f32(0.9)
+    for trial in range(6):
+        n = int(rng.integers(1, 40))
+        g, h = _random_bucket(rng, n, kind)
+        if kind == "mixed":                       # keep squares inside the binary32 range
+            g = (rng.standard_normal(n) * 10.0 ** rng.integers(-12, 12, n)).astype(np.float32)
+            h = (rng.standard_normal(n) * 10.0 ** rng.integers(-12, 12, n)).astype(np.float32)
+        q, scale, gt, hn = oracle.bucket_step(g, h, 64, 3, s, alpha, beta, 99, trial, norm="l2")
+        eq, escale, egt, ehn = X.bucket_step([float(x) for x in g], [float(x) for x in h], 64, 3, s,
+                                             alpha, beta, 99, trial, norm="l2")
+        assert Fraction(float(scale)) == escale
+        assert [int(x) for x in q] == eq
+        assert [Fraction(float(x)) for x in gt] == egt
+        assert [Fraction(float(x)) for x in hn] == ehn
+
+
+def test_l2_norm_value_and_order():
+    """Close to the float64 norm; independent of zero padding; the summation order is the
+    balanced tree (a left-to-right sum gives a different binary32 value on this input)."""
+    rng = np.random.default_rng(12)
+    for n in (1, 2, 3, 5, 8, 100, 512, 1000, 4096):
+        v = rng.standard_normal(n).astype(np.float32)
+        got = float(oracle.bucket_scale_l2(v))
+        ref = float(np.linalg.norm(v.astype(np.float64)))
+        assert abs(got - ref) <= ref * (math.log2(max(n, 2)) + 2) * 2.0 ** -24
+        padded = np.concatenate([v, np.zeros(3, np.float32)])
+        assert float(oracle.bucket_scale_l2(padded)) == got
+    differ = 0
+    for trial in range(200):
+        v = rng.standard_normal(16).astype(np.float32)
+        sq = v * v
+        level = sq.copy()
+        while level.size > 1:
+            level = level[0::2] + level[1::2]
+        tree = np.sqrt(level[0])
+        seq = np.float32(0)
+        for x in sq:
+            seq = np.float32(seq + x)
+        seq = np.sqrt(seq)
+        got = oracle.bucket_scale_l2(v)
+        assert float(got) == float(tree)
+        assert Fraction(float(got)) == X.norm_l2([Fraction(float(x)) for x in v])
+        differ += float(tree) != float(seq)
+    assert differ > 10          # the order is observable, and it is the tree's
+
+
+def test_l2_norm_dominates_every_element():
+    """fl(sqrt(fl(x^2))) = |x| in binary32 and sums of non-negative terms are monotone under
+    rounding, so the computed l_2 norm is never below max|v_i|: the ratio stays <= 1 and the
+    element of a one-element bucket is reproduced exactly, as with l_inf."""
+    rng = np.random.default_rng(13)
+    for x in rng.uniform(1.0, 2.0, 2000).astype(np.float32):
+        assert float(oracle.bucket_scale_l2(np.array([x], np.float32))) == float(x)
+    for n in (2, 3, 17, 64):
+        for _ in range(200):
+            v = (rng.standard_normal(n) * 10.0 ** rng.integers(-6, 6)).astype(np.float32)
+            assert float(oracle.bucket_scale_l2(v)) >= float(np.abs(v).max())
+    q, sc, gt, _ = oracle.bucket_step(np.array([-1.7], np.float32), np.zeros(1, np.float32), 0, 0, 3, 1.0, 1.0,
+                                      1, 0, norm="l2")
+    assert int(q[0]) == -3 and float(gt[0]) == float(np.float32(-1.7))
+
+
+def test_l2_lemma1_unbiased_and_variance_bound():
+    """Lemma 1 (borrowed from QSGD for l_2 scaling): E[eps] = 0 and
+    E||eps||^2 <= min(d/s^2, sqrt(d)/s) ||v||^2, over many independent iterations' words."""
+    d, iters = 64, 3000
+    rng = np.random.default_rng(14)
+    v = rng.standard_normal(d).astype(np.float32)
+    for s in (1, 4):
+        acc = np.zeros(d)
+        sq = 0.0
+        for t in range(iters):
+            q, sc, gt, _ = oracle.bucket_step(v, np.zeros(d, np.float32), 0, 0, s, 1.0, 1.0, 5, t, norm="l2")
+            eps = gt.astype(np.float64) - v
+            acc += eps
+            sq += float((eps ** 2).sum())
+        norm2 = float((v.astype(np.float64) ** 2).sum())
+        bound = min(d / s ** 2, math.sqrt(d) / s) * norm2
+        assert sq / iters <= bound
+        assert sq / iters > 0.05 * bound            # the bound is not vacuous here
+        per_elem_sd = float(sc) / s * 0.5 / math.sqrt(iters)
+        assert np.abs(acc / iters).max() < 6 * per_elem_sd
+    # sparse output: with l_2 scaling most levels are 0 (expected non-zeros <= s(s + sqrt(d)))
+    q, _, _, _ = oracle.bucket_step(v, np.zeros(d, np.float32), 0, 0, 1, 1.0, 1.0, 5, 0, norm="l2")
+    assert (q != 0).sum() < d / 2
+
+
+def test_l2_batch_uses_tree_per_bucket_and_recursion_holds():
+    """Batch route with l_2: per-bucket norms equal the single-bucket routine; Eq. (5) closed
+    form still holds (it does not depend on the norm)."""
+    rng = np.random.default_rng(15)
+    P, n, bucket, s = 2, 300, 64, 4
+    alpha, beta = f32(0.2), f32(0.9)
+    h = np.zeros((P, n), np.float32)
+    closed = np.zeros((P, n))
+    for t in range(5):
+        g = rng.standard_normal((P, n)).astype(np.float32)
+        v = g + F32(alpha) * h
+        q, scales, gt = oracle.batch_step(g, h, bucket, s, alpha, beta, 3, t, want_gt=True, norm="l2")
+        for p in range(P):
+            for k in range(scales.shape[1]):
+                assert scales[p, k] == oracle.bucket_scale_l2(v[p, k * bucket:(k + 1) * bucket])
+        closed = float(beta) * closed + (g.astype(np.float64) - gt)
+        assert np.abs(h - closed).max() <= 1e-6 * max(1.0, np.abs(closed).max())
