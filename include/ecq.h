@@ -23,7 +23,7 @@
  *
  * Data layout (P = workers, N = n elements per worker, b = bucket, nb = ceil(N/b))
  *  - g, h   : float32 [P][gh_stride], row p = worker p's flat gradient / accumulated error.
- *  - scales : float32 [P][scale_stride]; scales[p][k] = l_inf norm of bucket k of worker p,
+ *  - scales : float32 [P][scale_stride]; scales[p][k] = norm ||v|| of bucket k of worker p,
  *             bucket k = elements [k*b, min((k+1)*b, N)).
  *  - codes  : bytes [P][code_stride]; row p is one contiguous bit stream, element i's code
  *             c = level + s (0..2s) in stream bits [i*r, (i+1)*r), stream bit j = bit (j & 7)
@@ -51,22 +51,32 @@ typedef enum {
     ECQ_ERR_NULL = -1,    /* a required pointer is NULL                                   */
     ECQ_ERR_SHAPE = -2,   /* n <= 0, n > ECQ_MAX_N or workers <= 0 or workers > 65535      */
     ECQ_ERR_LEVELS = -3,  /* s outside 1..127                                             */
-    ECQ_ERR_BUCKET = -4,  /* bucket not a positive multiple of 8                          */
+    ECQ_ERR_BUCKET = -4,  /* bucket not a positive multiple of 8, or unsupported with l2  */
     ECQ_ERR_STRIDE = -5,  /* a row stride too small for its row or not suitably divisible */
     ECQ_ERR_ALIGN = -6,   /* a base pointer is not aligned as documented                  */
     ECQ_ERR_LAUNCH = -7,  /* the HIP runtime refused a launch                             */
-    ECQ_ERR_PARAM = -8    /* alpha or beta out of range, or an unknown tuning value        */
+    ECQ_ERR_PARAM = -8    /* alpha, beta or norm out of range, or an unknown tuning value  */
 } ecq_status;
 
 /* Largest n: element index i enters the Philox counter as low32(i >> 2). */
 #define ECQ_MAX_N (((int64_t)1) << 34)
+
+/* The scaling factor ||v|| of Eq. (8); the paper names both choices (text after Eq. (8)).
+ *   ECQ_NORM_LINF  max |v_i| over the bucket (order-free).
+ *   ECQ_NORM_L2    sqrt of the sum of fl(v_i^2), the sum taken over a balanced binary tree by
+ *                  element index (the bucket padded with zeros to a power of two), then one
+ *                  correctly rounded square root.  Needs a bucket that is a power of two in
+ *                  8..128 or any multiple of 8 in 256..32768; other buckets give
+ *                  ECQ_ERR_BUCKET.  Squares must stay inside the binary32 range. */
+#define ECQ_NORM_LINF 0
+#define ECQ_NORM_L2 1
 
 typedef struct {
     int64_t n;            /* N: elements per worker, 1..ECQ_MAX_N                           */
     int32_t workers;      /* P: 1..65535                                                   */
     int32_t bucket;       /* b: positive multiple of 8 (every bucket starts on a byte)      */
     int32_t s;            /* non-zero quantisation levels, 1..127 (r = 2..8 bits)          */
-    int32_t reserved;     /* must be 0                                                     */
+    int32_t norm;         /* scaling factor ||v||: ECQ_NORM_LINF (0) or ECQ_NORM_L2 (1)     */
     int64_t gh_stride;    /* floats between worker rows of g and of h: >= n, multiple of 4 */
     int64_t code_stride;  /* BYTES between worker rows of codes: >= row bytes, mult. of 4  */
     int64_t scale_stride; /* floats between worker rows of scales: >= nb                   */

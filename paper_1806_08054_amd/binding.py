@@ -21,13 +21,14 @@ class EcqError(RuntimeError):
 class Shape(C.Structure):
     """Mirror of ecq_shape."""
     _fields_ = [("n", C.c_int64), ("workers", C.c_int32), ("bucket", C.c_int32), ("s", C.c_int32),
-                ("reserved", C.c_int32), ("gh_stride", C.c_int64), ("code_stride", C.c_int64),
+                ("norm", C.c_int32), ("gh_stride", C.c_int64), ("code_stride", C.c_int64),
                 ("scale_stride", C.c_int64)]
 
     @classmethod
-    def packed(cls, n: int, workers: int, bucket: int, s: int) -> "Shape":
-        """Tightest legal strides: gh rounded up to 4 floats, codes to 4 bytes."""
-        return cls(n=n, workers=workers, bucket=bucket, s=s, reserved=0,
+    def packed(cls, n: int, workers: int, bucket: int, s: int, norm: int = 0) -> "Shape":
+        """Tightest legal strides: gh rounded up to 4 floats, codes to 4 bytes.
+        norm: 0 = l_inf (ECQ_NORM_LINF), 1 = l_2 (ECQ_NORM_L2)."""
+        return cls(n=n, workers=workers, bucket=bucket, s=s, norm=norm,
                    gh_stride=(n + 3) // 4 * 4, code_stride=(row_bytes(n, s) + 3) // 4 * 4,
                    scale_stride=num_buckets(n, bucket))
 

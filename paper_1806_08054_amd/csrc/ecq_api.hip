@@ -23,7 +23,7 @@ static int check_shape(const ecq_shape *sh)
     if (sh->n <= 0 || sh->n > ECQ_MAX_N || sh->workers <= 0 || sh->workers > 65535) return ECQ_ERR_SHAPE;
     if (sh->s < 1 || sh->s > 127) return ECQ_ERR_LEVELS;
     if (sh->bucket <= 0 || (sh->bucket & 7) != 0) return ECQ_ERR_BUCKET;
-    if (sh->reserved != 0) return ECQ_ERR_PARAM;
+    if (sh->norm != ECQ_NORM_LINF && sh->norm != ECQ_NORM_L2) return ECQ_ERR_PARAM;
     const int r = code_bits(sh->s);
     const int64_t row_bytes = (sh->n * r + 7) / 8;
     const int64_t nb = (sh->n + sh->bucket - 1) / sh->bucket;
@@ -46,6 +46,7 @@ static Args make_args(const ecq_shape &sh)
     a.workers = sh.workers;
     a.bucket = sh.bucket;
     a.s = sh.s;
+    a.norm_l2 = sh.norm == ECQ_NORM_L2;
     return a;
 }
 
@@ -77,6 +78,9 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
     const bool pow2 = (b & (b - 1)) == 0;
     const bool small_ok = pow2 && b >= 8 && b <= 128;
     const bool team_ok = b >= 256 && b <= 32768;
+    // The l2 sum has a fixed tree order that only the single-pass mappings reproduce.
+    if (sh.norm == ECQ_NORM_L2 && !(small_ok || team_ok)) return ECQ_ERR_BUCKET;
+    if (sh.norm == ECQ_NORM_L2 && path == 2) return ECQ_ERR_PARAM;
     if (path == 0) path = (small_ok || team_ok) ? 1 : 2;
     if (path == 1 && !(small_ok || team_ok)) return ECQ_ERR_PARAM;
     pl.path = path;
@@ -246,11 +250,11 @@ const char *ecq_status_string(int status)
     case ECQ_ERR_NULL: return "a required pointer is NULL";
     case ECQ_ERR_SHAPE: return "n or workers out of range";
     case ECQ_ERR_LEVELS: return "s must be in 1..127";
-    case ECQ_ERR_BUCKET: return "bucket must be a positive multiple of 8";
+    case ECQ_ERR_BUCKET: return "bucket must be a positive multiple of 8 (with l2: a power of two in 8..128 or 256..32768)";
     case ECQ_ERR_STRIDE: return "a row stride is too small or not suitably divisible";
     case ECQ_ERR_ALIGN: return "a base pointer is not aligned as documented";
     case ECQ_ERR_LAUNCH: return "the HIP runtime refused a launch";
-    case ECQ_ERR_PARAM: return "alpha, beta or a tuning value is out of range";
+    case ECQ_ERR_PARAM: return "alpha, beta, norm or a tuning value is out of range";
     default: return "unknown status";
     }
 }

@@ -197,6 +197,39 @@ __device__ __forceinline__ uint32_t group_max(uint32_t x, int lanes)
     return x;
 }
 
+// ---- l2 norm: sum of squares over a balanced binary tree by element index --------------------
+//
+// a + b == b + a in IEEE arithmetic, so a butterfly in which both partners add leaves the same
+// value in both lanes, and the exchange order (distance 1, 2, 4, ... lanes) is exactly the
+// index tree because a lane owns 4 consecutive elements and lanes own consecutive groups.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x)
+{
+    return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(x)));
+}
+
+// Tree sum of the squares of a lane's 4 consecutive elements.
+__device__ __forceinline__ float sum_squares4(const float (&v)[4])
+{
+    const float s0 = v[0] * v[0], s1 = v[1] * v[1], s2 = v[2] * v[2], s3 = v[3] * v[3];
+    const float lo = s0 + s1;
+    const float hi = s2 + s3;
+    return lo + hi;
+}
+
+// Tree sum over aligned groups of `lanes` lanes (a power of two, 1..64), result in every lane.
+__device__ __forceinline__ float group_sum_tree(float x, int lanes)
+{
+    if (lanes >= 2) x = x + dpp_f32<0xB1>(x);
+    if (lanes >= 4) x = x + dpp_f32<0x4E>(x);
+    if (lanes >= 8) x = x + dpp_f32<0x141>(x);
+    if (lanes >= 16) x = x + dpp_f32<0x140>(x);
+    if (lanes >= 32) x = x + __shfl_xor(x, 16, 64);
+    if (lanes >= 64) x = x + __shfl_xor(x, 32, 64);
+    return x;
+}
+
 // ---- code packing -----------------------------------------------------------------------
 
 // Store the low `nbytes` bytes of `bits` at dst, skipping bytes at or beyond `limit` bytes

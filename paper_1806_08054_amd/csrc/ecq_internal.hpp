@@ -24,6 +24,7 @@ struct Args {
     int32_t bucket;
     int32_t s;
     int32_t r;
+    int32_t norm_l2;       // 1: l2 scaling, 0: l_inf
     float alpha;
     float beta;
     uint32_t key0, key1;   // seed

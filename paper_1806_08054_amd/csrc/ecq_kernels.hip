@@ -181,13 +181,42 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 #pragma unroll
     for (int j = 0; j < J; ++j) mx = umax(mx, compensate4(g[j], h[j], a.alpha, v[kKeepV ? j : 0]));
 
-    uint32_t norm = wave_max_uniform(mx);
-    if (W > 1) {
-        if (lane == 0) wave_norm[wave] = norm;
-        __syncthreads();
-        for (int t = 0; t < W; ++t) norm = umax(norm, wave_norm[(team << w_shift) + t]);
+    float scale;
+    if (!a.norm_l2) {
+        uint32_t norm = wave_max_uniform(mx);
+        if (W > 1) {
+            if (lane == 0) wave_norm[wave] = norm;
+            __syncthreads();
+            for (int t = 0; t < W; ++t) norm = umax(norm, wave_norm[(team << w_shift) + t]);
+        }
+        scale = __uint_as_float(norm);
+    } else {
+        // Tree by index: lanes of a 256-element run, then the wave's J runs, then the team's waves.
+        float part[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            if constexpr (!kKeepV) compensate4(g[j], h[j], a.alpha, v[0]);
+            part[j] = group_sum_tree(sum_squares4(v[kKeepV ? j : 0]), 64);
+        }
+#pragma unroll
+        for (int w = 1; w < J; w *= 2)
+#pragma unroll
+            for (int j = 0; j + w < J; j += 2 * w) part[j] = part[j] + part[j + w];
+        float total = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(part[0])));
+        if (W > 1) {
+            if (lane == 0) wave_norm[wave] = __float_as_uint(total);
+            __syncthreads();
+            float t[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = i < W ? __uint_as_float(wave_norm[(team << w_shift) + i]) : 0.0f;
+#pragma unroll
+            for (int w = 1; w < 16; w *= 2)
+#pragma unroll
+                for (int i = 0; i + w < 16; i += 2 * w) t[i] = t[i] + t[i + w];
+            total = t[0];
+        }
+        scale = __builtin_sqrtf(total);
     }
-    const float scale = __uint_as_float(norm);
     const Rounder<R> rounder(scale, a.s, xi_tab);
 
     uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
@@ -240,7 +269,8 @@ __global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lan
     float scale;
     const int64_t k = elem / a.bucket;
     if (lanes_per_bucket > 0) {
-        scale = __uint_as_float(group_max(mx, lanes_per_bucket));
+        scale = a.norm_l2 ? __builtin_sqrtf(group_sum_tree(sum_squares4(v), lanes_per_bucket))
+                          : __uint_as_float(group_max(mx, lanes_per_bucket));
         if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
             a.scales[(int64_t)p * a.scale_stride + k] = scale;
     } else {

@@ -30,6 +30,7 @@ class Workload:
     iters: int
     kind: str         # which generator
     data_seed: int = 0
+    norm: str = "linf"   # scaling factor of the quantiser: "linf" or "l2"
 
     @property
     def nb(self) -> int:

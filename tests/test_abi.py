@@ -67,7 +67,7 @@ def test_check_shape_status_codes(E):
     assert st(gh_stride=4095) == -5 and st(gh_stride=4098) == -5
     assert st(code_stride=1020) == -5 and st(code_stride=1026) == -5
     assert st(scale_stride=7) == -5
-    assert st(reserved=3) == -8
+    assert st(norm=1) == 0 and st(norm=3) == -8 and st(norm=-1) == -8
     for code in range(0, -9, -1):
         assert E.status_string(code) != "unknown status"
     assert E.status_string(-99) == "unknown status"
@@ -87,6 +87,10 @@ def test_entry_points_reject_bad_arguments_before_any_launch(E):
     assert lib.ecq_quantize_update(C.byref(sh), fake, fake, -1.0, 1.0, 1, 0, fake, fake, None) == -8
     assert lib.ecq_quantize_update(C.byref(sh), fake, fake, 1.0, 2.0, 1, 0, fake, fake, None) == -8
     assert lib.ecq_quantize_update(C.byref(sh), C.c_void_p(0x1004), fake, 1.0, 1.0, 1, 0, fake, fake, None) == -6
+    l2_odd = E.Shape.packed(4096, 4, 24, 1, norm=1)        # l2 needs a single-pass bucket shape
+    assert lib.ecq_quantize_update(C.byref(l2_odd), fake, fake, 1.0, 1.0, 1, 0, fake, fake, None) == -4
+    l2_big = E.Shape.packed(1 << 20, 1, 65536, 1, norm=1)
+    assert lib.ecq_quantize_update(C.byref(l2_big), fake, fake, 1.0, 1.0, 1, 0, fake, fake, None) == -4
     tu = E.Tuning(1, 3, 0, 0)
     assert lib.ecq_quantize_update_ex(C.byref(sh), fake, fake, 1.0, 1.0, 1, 0, fake, fake, C.byref(tu), None) == -8
 

@@ -30,9 +30,9 @@ def _dev(x):
 class GpuState:
     """Device buffers of one workload, laid out as the C ABI documents."""
 
-    def __init__(self, E, P, N, bucket, s, pad=0):
-        self.E, self.P, self.N, self.bucket, self.s = E, P, N, bucket, s
-        sh = E.Shape.packed(N, P, bucket, s)
+    def __init__(self, E, P, N, bucket, s, pad=0, norm="linf"):
+        self.E, self.P, self.N, self.bucket, self.s, self.norm = E, P, N, bucket, s, norm
+        sh = E.Shape.packed(N, P, bucket, s, norm={"linf": 0, "l2": 1}[norm])
         sh.gh_stride += 4 * pad
         sh.code_stride += 4 * pad
         sh.scale_stride += pad
@@ -67,7 +67,7 @@ def _compare_step(st, g_np, h_ref, alpha, beta, step, tuning=None, fused=True):
     h_ref is advanced in place by the oracle; st.h by the library."""
     E = st.E
     P, N = st.P, st.N
-    q, scales, _ = oracle.batch_step(g_np, h_ref, st.bucket, st.s, alpha, beta, SEED, step)
+    q, scales, _ = oracle.batch_step(g_np, h_ref, st.bucket, st.s, alpha, beta, SEED, step, norm=st.norm)
     codes_ref = oracle.pack_rows(q, st.s)
     st.poison()
     if fused:
@@ -105,7 +105,7 @@ def _aggregate_check(st, codes_ref, scales_ref):
 
 
 def _free_run(E, wl, iters, tuning=None, pad=0, fused=True, gens=None):
-    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, pad=pad)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, pad=pad, norm=wl.norm)
     h_ref = np.zeros((wl.P, wl.N), np.float32)
     for t in range(iters):
         g_np = gens(t) if gens else synth.gradients(wl, t).numpy()
@@ -171,6 +171,45 @@ def test_tiny_lengths(E, N, s):
     _free_run(E, wl, 2)
     wl = synth.scaled(wl, bucket=8)
     _free_run(E, wl, 2)
+
+
+# ------------------------------------------------------------------ l_2 scaling ------------
+
+@pytest.mark.parametrize("s", [1, 4, 7])
+@pytest.mark.parametrize("bucket", [8, 32, 128, 256, 512, 1000, 1024, 4096, 8192, 16384, 32768])
+def test_l2_norm_buckets(E, s, bucket):
+    """l_2 scaling (tree sum of squares by index, one square root) on every single-pass route,
+    ragged tails included; the paper's own setting is l_2 with s = 4 (Section 6)."""
+    wl = synth.Workload("edge", P=2, N=2 * bucket + bucket // 2 + 3 + 1024, bucket=bucket, s=s, alpha=0.2,
+                        beta=0.9, iters=3, kind="normal", data_seed=bucket + s, norm="l2")
+    _free_run(E, wl, 3)
+
+
+def test_l2_geometry_invariance_and_unfused(E):
+    wl = synth.Workload("edge", P=2, N=5 * 2048 + 1000, bucket=2048, s=4, alpha=0.2, beta=0.9, iters=2,
+                        kind="normal", data_seed=77, norm="l2")
+    for path, waves, threads in [(1, 1, 64), (1, 1, 256), (1, 2, 256), (1, 4, 256), (1, 8, 512), (1, 16, 1024)]:
+        _free_run(E, wl, 2, tuning=E.Tuning(path, waves, threads, 0))
+    _free_run(E, wl, 2, fused=False)
+
+
+def test_l2_degenerate(E):
+    """Zero buckets, sparse buckets (one non-zero), equal magnitudes."""
+    P, N, bucket = 3, 4096, 512
+    rng = np.random.default_rng(2)
+
+    def gens(t):
+        g = rng.standard_normal((P, N)).astype(np.float32)
+        g[0] = 0.0
+        g[1, :] = 0.0
+        g[1, ::512] = 2.5
+        g[2, :1024] = np.float32(0.125) * np.sign(g[2, :1024])
+        return g
+
+    for s in (1, 4):
+        wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=3,
+                            kind="normal", norm="l2")
+        _free_run(E, wl, 3, gens=gens)
 
 
 def test_launch_geometry_invariance(E):
@@ -247,7 +286,7 @@ def test_argument_errors_leave_outputs_untouched(E):
     assert call(shape(code_stride=100)) == -5 and call(shape(scale_stride=1)) == -5
     assert call(shape(), g=st.g.data_ptr() + 4) == -6
     assert call(shape(), alpha=-1.0) == -8 and call(shape(), beta=1.5) == -8
-    assert call(shape(), alpha=float("nan")) == -8 and call(shape(reserved=1)) == -8
+    assert call(shape(), alpha=float("nan")) == -8 and call(shape(norm=7)) == -8
     torch.cuda.synchronize()
     assert bool((st.codes == 0xEE).all()) and bool((st.scales == -7.0).all()) and not bool(st.h.any())
     assert call(shape()) == 0
