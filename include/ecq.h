@@ -153,6 +153,17 @@ int ecq_dequant_aggregate(const ecq_shape *shape, const uint8_t *codes, const fl
                           float *out, void *stream);
 
 /*
+ * Eq. (4) in full, i.e. Alg. 1 "compute global gradients" followed by "update model
+ * parameters": g~avg as in ecq_dequant_aggregate, then w[i] <- w[i] - fl(eta * g~avg[i]),
+ * fused so the averaged gradient need not travel through memory.
+ *   eta  in      learning rate, finite.
+ *   w    in/out  device, [n] float32, 16-byte aligned: the model replica, updated in place.
+ *   out  out     device, [n] float32, 16-byte aligned, or NULL: g~avg is also stored there.
+ */
+int ecq_dequant_aggregate_sgd(const ecq_shape *shape, const uint8_t *codes, const float *scales,
+                              float eta, float *w, float *out, void *stream);
+
+/*
  * The random words of Eq. (9)'s rounding decision, for inspection: words[j] is the word
  * element i0 + j of worker p consumes at iteration `step`.  words: device, [count] uint32.
  */

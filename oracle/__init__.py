@@ -97,6 +97,8 @@ def _declare(L):
     L.ecq_oracle_aggregate.argtypes = [_u8p, C.c_int64, _f32p, C.c_int64, C.c_int, C.c_int64,
                                        C.c_int, C.c_int, _f32p]
     L.ecq_oracle_aggregate.restype = None
+    L.ecq_oracle_sgd_step.argtypes = [_f32p, _f32p, C.c_float, C.c_int64]
+    L.ecq_oracle_sgd_step.restype = None
 
 
 # ------------------------------------------------------------------ scalar steps ------------
@@ -249,6 +251,13 @@ def aggregate(codes: np.ndarray, scales: np.ndarray, n: int, bucket: int, s: int
     out = np.zeros(n, np.float32)
     lib().ecq_oracle_aggregate(codes, codes.shape[1], scales, scales.shape[1], P, n, bucket, s, out)
     return out
+
+
+def sgd_step(w: np.ndarray, gavg: np.ndarray, eta: float) -> np.ndarray:
+    """Alg. 1, model update: w <- w - eta * g~ (w float32, updated in place)."""
+    assert w.dtype == np.float32 and w.flags.c_contiguous
+    lib().ecq_oracle_sgd_step(w, np.ascontiguousarray(gavg, np.float32), eta, w.size)
+    return w
 
 
 def max_threads() -> int:

@@ -15,6 +15,7 @@
  *   encode       r = ceil(log2(2s+1)) bits per element + 1 scale   Section 4, paragraph on cost
  *   accumulate   h <- beta*h + (g - g~)                            Section 4, Eq. (6)
  *   aggregate    g~ = (1/P) sum_p g~_p                             Section 3/4, Eq. (4); Alg. 1
+ *   model update w <- w - eta * g~                                 Eq. (4); Alg. 1, last line
  *
  * Arithmetic: IEEE-754 binary32, round-to-nearest-even, every operation rounded on its own
  * (build with -ffp-contract=off -fno-fast-math; no FMA, denormals kept).  The paper fixes
@@ -239,7 +240,7 @@ void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, 
 {
     float scale = 0.0f;
     if (norm_l2) {
-        float *v = (float *)malloc(sizeof(float) * (size_t)(len > 0 ? len : 1));
+        float *v = (float *)calloc((size_t)(len > 0 ? len : 1), sizeof(float));
         for (int64_t i = 0; i < len; ++i) v[i] = ecq_oracle_compensate(g[i], alpha, h[i]);
         scale = ecq_oracle_bucket_scale_l2(v, len);
         free(v);
@@ -336,5 +337,14 @@ void ecq_oracle_aggregate(const uint8_t *codes, int64_t code_stride, const float
             acc = acc + gt;
         }
         out[i] = acc / (float)P;
+    }
+}
+
+/* Alg. 1 "update model parameters" / Eq. (4): w <- w - eta * g~, the product rounded first. */
+void ecq_oracle_sgd_step(float *w, const float *gavg, float eta, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float stepv = eta * gavg[i];
+        w[i] = w[i] - stepv;
     }
 }

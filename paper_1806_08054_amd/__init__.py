@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     ecq_calib_add,
     ecq_calib_copy,
     ecq_dequant_aggregate,
+    ecq_dequant_aggregate_sgd,
     ecq_error_update,
     ecq_philox_words,
     ecq_quantize,

@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.ecq_quantize_update.argtypes = [shp, vp, vp, f, f, u64, u64, vp, vp, vp]
         L.ecq_quantize_update_ex.argtypes = [shp, vp, vp, f, f, u64, u64, vp, vp, C.POINTER(Tuning), vp]
         L.ecq_dequant_aggregate.argtypes = [shp, vp, vp, vp, vp]
+        L.ecq_dequant_aggregate_sgd.argtypes = [shp, vp, vp, f, vp, vp, vp]
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -73,7 +74,7 @@ def lib() -> C.CDLL:
         L.ecq_version.argtypes = []
         for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
                      "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
-                     "ecq_dequant_aggregate", "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
+                     "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -145,6 +146,11 @@ def ecq_quantize_update_ex(shape: Shape, g, h, alpha: float, beta: float, seed: 
 def ecq_dequant_aggregate(shape: Shape, codes, scales, out, stream=None) -> None:
     _check(lib().ecq_dequant_aggregate(C.byref(shape), _ptr(codes), _ptr(scales), _ptr(out), _stream(stream)),
            "ecq_dequant_aggregate")
+
+
+def ecq_dequant_aggregate_sgd(shape: Shape, codes, scales, eta: float, w, out=None, stream=None) -> None:
+    _check(lib().ecq_dequant_aggregate_sgd(C.byref(shape), _ptr(codes), _ptr(scales), eta, _ptr(w), _ptr(out),
+                                           _stream(stream)), "ecq_dequant_aggregate_sgd")
 
 
 def ecq_philox_words(seed: int, step: int, p: int, i0: int, count: int, words, stream=None) -> None:

@@ -214,6 +214,24 @@ int ecq_dequant_aggregate(const ecq_shape *shape, const uint8_t *codes, const fl
     return ecq::launch_dequant_aggregate(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
 }
 
+int ecq_dequant_aggregate_sgd(const ecq_shape *shape, const uint8_t *codes, const float *scales, float eta,
+                              float *w, float *out, void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!codes || !scales || !w) return ECQ_ERR_NULL;
+    if (!ecq::aligned(w, 16) || !ecq::aligned(out, 16) || !ecq::aligned(codes, 4) || !ecq::aligned(scales, 4))
+        return ECQ_ERR_ALIGN;
+    if (!std::isfinite(eta)) return ECQ_ERR_PARAM;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    a.scales = const_cast<float *>(scales);
+    a.out = out;
+    a.w = w;
+    a.eta = eta;
+    return ecq::launch_dequant_aggregate(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
 int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
                      void *stream)
 {

@@ -13,7 +13,8 @@ struct Args {
     float *h;              // read-only unless the kernel updates the accumulator
     uint8_t *codes;
     float *scales;
-    float *out;            // aggregation output
+    float *out;            // aggregation output (may be null when w is given)
+    float *w;              // model replica updated by the aggregation kernel, or null
     int64_t n;
     int64_t nb;
     int64_t gh_stride;
@@ -27,6 +28,7 @@ struct Args {
     int32_t norm_l2;       // 1: l2 scaling, 0: l_inf
     float alpha;
     float beta;
+    float eta;
     uint32_t key0, key1;   // seed
     uint32_t step_lo, step_hi;
 };

@@ -464,7 +464,17 @@ __device__ __forceinline__ void agg_run_guarded(const Args &a, const float *tabl
     float o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = inv_p > 0.0f ? acc[e] * inv_p : acc[e] / pf;
-    store4(a.out, elem, a.n, o);
+    if (a.out) store4(a.out, elem, a.n, o);
+    if (a.w) {
+        float wv[4];
+        load4(a.w, elem, a.n, wv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float stepv = a.eta * o[e];
+            wv[e] = wv[e] - stepv;
+        }
+        store4(a.w, elem, a.n, wv);
+    }
 }
 
 // The 4*R code bits at bit offset `bitoff` (a multiple of 4) from `tile`, no bounds checks.
@@ -561,7 +571,6 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     }
 
     const float pf = (float)a.workers;
-    float *__restrict__ otile = a.out + base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         f4 o;
@@ -570,7 +579,14 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         } else {
             o.x = acc[j][0] / pf; o.y = acc[j][1] / pf; o.z = acc[j][2] / pf; o.w = acc[j][3] / pf;
         }
-        __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(otile + j * 256 + lane * 4));
+        const int64_t at = base + j * 256 + lane * 4;
+        if (a.out) __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(a.out + at));
+        if (a.w) {                                             // Alg. 1: w <- w - eta * g~
+            f4 wv = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a.w + at));
+            const f4 stepv = o * a.eta;
+            wv = wv - stepv;
+            __builtin_nontemporal_store(wv, reinterpret_cast<f4 *>(a.w + at));
+        }
     }
 }
 

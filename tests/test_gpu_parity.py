@@ -261,6 +261,72 @@ def test_teacher_forced_and_alpha_zero(E):
         _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, t)
 
 
+# ------------------------------------------------------------------ model update -----------
+
+@pytest.mark.parametrize("s,bucket,N,P", [(1, 512, 5000, 4), (4, 1024, 3 * 1024 + 77, 3), (3, 24, 1000, 5),
+                                          (7, 8192, 4_200_000, 2)])
+def test_aggregate_sgd_step(E, s, bucket, N, P):
+    """ecq_dequant_aggregate_sgd: the averaged gradient and w <- w - eta * g~ in one kernel,
+    with and without storing the average."""
+    rng = np.random.default_rng(N)
+    wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="normal",
+                        data_seed=N)
+    st = GpuState(E, P, N, bucket, s)
+    g_np = synth.gradients(wl, 0).numpy()
+    st.g[:, :N] = _dev(g_np)
+    h_ref = np.zeros((P, N), np.float32)
+    codes_ref, scales_ref = _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, 0)
+    gavg = oracle.aggregate(codes_ref, scales_ref, N, bucket, s)
+    w0 = rng.standard_normal(N).astype(np.float32)
+    eta = float(np.float32(0.02))
+    w_ref = oracle.sgd_step(w0.copy(), gavg, eta)
+    for keep_avg in (True, False):
+        w = _dev(w0)
+        st.out.fill_(-7.0)
+        E.ecq_dequant_aggregate_sgd(st.sh, st.codes, st.scales, eta, w, st.out if keep_avg else None)
+        torch.cuda.synchronize()
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+        out = st.out.cpu().numpy()
+        if keep_avg:
+            assert np.array_equal(out.view(np.uint32), gavg.view(np.uint32))
+        else:
+            assert np.all(out == -7.0)
+
+
+def test_closed_loop_least_squares(E):
+    """Algorithm 1 end to end on synthetic least squares (the setting of Section 6.1: l_2
+    scaling, s = 4, alpha = 0.2, beta = 0.9, eta = 0.02): gradients from the current model,
+    quantise + error update, aggregate + model update, for 150 iterations.  The library's model
+    replica must follow the oracle's bit for bit, and the loss must fall."""
+    d, P, mb, s, iters = 2048, 4, 32, 4, 150
+    alpha, beta, eta = float(np.float32(0.2)), float(np.float32(0.9)), float(np.float32(0.02))
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    X = torch.randn(P, 2000, d, generator=gen, device="cuda")
+    wstar = torch.randn(d, generator=gen, device="cuda")
+    y = X @ wstar + 0.1 * torch.randn(P, 2000, generator=gen, device="cuda")
+    st = GpuState(E, P, d, 512, s, norm="l2")
+    w = torch.zeros(d, device="cuda")
+    w_ref = np.zeros(d, np.float32)
+    h_ref = np.zeros((P, d), np.float32)
+    losses = []
+    for t in range(iters):
+        idx = torch.randint(0, 2000, (P, mb), generator=gen, device="cuda")
+        Xb = torch.gather(X, 1, idx[:, :, None].expand(P, mb, d))
+        yb = torch.gather(y, 1, idx)
+        resid = torch.einsum("pmd,d->pm", Xb, w) - yb
+        st.g[:, :d] = torch.einsum("pmd,pm->pd", Xb, resid) / mb
+        losses.append(float((resid ** 2).mean()))
+        g_np = st.g[:, :d].cpu().numpy()
+        E.ecq_quantize_update(st.sh, st.g, st.h, alpha, beta, SEED, t, st.codes, st.scales)
+        E.ecq_dequant_aggregate_sgd(st.sh, st.codes, st.scales, eta, w, None)
+        q, sc, _ = oracle.batch_step(g_np, h_ref, 512, s, alpha, beta, SEED, t, norm="l2")
+        oracle.sgd_step(w_ref, oracle.aggregate(oracle.pack_rows(q, s), sc, d, 512, s), eta)
+        torch.cuda.synchronize()
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32)), f"model differs at step {t}"
+    assert np.array_equal(st.h[:, :d].cpu().numpy().view(np.uint32), h_ref.view(np.uint32))
+    assert np.mean(losses[-10:]) < 0.05 * np.mean(losses[:3])
+
+
 # ------------------------------------------------------------------ boundary errors --------
 
 def test_argument_errors_leave_outputs_untouched(E):

@@ -575,3 +575,61 @@ def test_l2_batch_uses_tree_per_bucket_and_recursion_holds():
                 assert scales[p, k] == oracle.bucket_scale_l2(v[p, k * bucket:(k + 1) * bucket])
         closed = float(beta) * closed + (g.astype(np.float64) - gt)
         assert np.abs(h - closed).max() <= 1e-6 * max(1.0, np.abs(closed).max())
+
+
+# ------------------------------------------------------------------ model update -----------
+
+def test_sgd_step_is_the_update_rule():
+    """Eq. (4) / Alg. 1 last line: w <- w - eta * g~; the product is rounded, then the
+    difference."""
+    rng = np.random.default_rng(21)
+    w = rng.standard_normal(500).astype(np.float32)
+    g = rng.standard_normal(500).astype(np.float32)
+    eta = f32(0.02)
+    got = oracle.sgd_step(w.copy(), g, eta)
+    ref = w.astype(np.float64) - float(eta) * g.astype(np.float64)
+    assert np.abs(got - ref).max() <= 1e-6 * np.abs(ref).max()
+    for i in range(50):
+        want = X.rn32(Fraction(float(w[i])) - X.rn32(Fraction(eta) * Fraction(float(g[i]))))
+        assert Fraction(float(got[i])) == want
+    assert np.array_equal(oracle.sgd_step(w.copy(), g, 0.0), w)
+
+
+def _least_squares_run(d, alpha, beta, quantise, iters=600, P=4, mb=16, s=4, eta=0.02, seed=0):
+    """Distributed least squares as in Section 6.1 (synthetic y = w*^T x + noise, eta = 0.02,
+    l_2 scaling, s = 4), whole vector as one bucket; returns the mean distance to the optimum
+    over the last 100 iterations."""
+    rng = np.random.default_rng(seed)
+    n = 4000
+    Xd = rng.standard_normal((n, d)).astype(np.float32)
+    wstar = rng.standard_normal(d).astype(np.float32)
+    y = (Xd @ wstar + 0.1 * rng.standard_normal(n)).astype(np.float32)
+    wopt = np.linalg.lstsq(Xd.astype(np.float64), y.astype(np.float64), rcond=None)[0]
+    w = np.zeros(d, np.float32)
+    h = np.zeros((P, d), np.float32)
+    shards = np.array_split(np.arange(n), P)
+    dist = []
+    for t in range(iters):
+        g = np.zeros((P, d), np.float32)
+        for p in range(P):
+            idx = rng.choice(shards[p], mb, replace=False)
+            g[p] = (Xd[idx].T @ (Xd[idx] @ w - y[idx]) / mb).astype(np.float32)
+        if quantise:
+            q, sc, _ = oracle.batch_step(g, h, d, s, alpha, beta, 1, t, norm="l2")
+            gavg = oracle.aggregate(oracle.pack_rows(q, s), sc, d, d, s)
+        else:
+            gavg = g.mean(axis=0).astype(np.float32)
+        oracle.sgd_step(w, gavg, eta)
+        dist.append(float(np.linalg.norm(w - wopt)))
+    return float(np.mean(dist[-100:]))
+
+
+def test_closed_loop_error_feedback_shrinks_the_gap():
+    """Section 6.1 / Fig. 2, qualitatively: with the paper's settings (alpha = 0.2, beta = 0.9)
+    the error-compensated run ends closer to the optimum than QSGD (alpha = 0, no feedback),
+    and both stay above the unquantised run."""
+    fp = _least_squares_run(256, 0.0, 0.0, quantise=False)
+    qsgd = _least_squares_run(256, 0.0, 0.0, quantise=True)
+    ecq = _least_squares_run(256, f32(0.2), f32(0.9), quantise=True)
+    assert fp < ecq < qsgd
+    assert (ecq - fp) < 0.5 * (qsgd - fp)
