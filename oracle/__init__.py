@@ -99,6 +99,11 @@ def _declare(L):
     L.ecq_oracle_aggregate.restype = None
     L.ecq_oracle_sgd_step.argtypes = [_f32p, _f32p, C.c_float, C.c_int64]
     L.ecq_oracle_sgd_step.restype = None
+    _u64p = np.ctypeslib.ndpointer(np.uint64, flags="C_CONTIGUOUS")
+    L.ecq_oracle_level_histogram.argtypes = [_i8p, C.c_int64, C.c_int, _u64p]
+    L.ecq_oracle_level_histogram.restype = None
+    L.ecq_oracle_entropy_bound_bits.argtypes = [_u64p, C.c_int]
+    L.ecq_oracle_entropy_bound_bits.restype = C.c_double
 
 
 # ------------------------------------------------------------------ scalar steps ------------
@@ -258,6 +263,20 @@ def sgd_step(w: np.ndarray, gavg: np.ndarray, eta: float) -> np.ndarray:
     assert w.dtype == np.float32 and w.flags.c_contiguous
     lib().ecq_oracle_sgd_step(w, np.ascontiguousarray(gavg, np.float32), eta, w.size)
     return w
+
+
+def level_histogram(q: np.ndarray, s: int) -> np.ndarray:
+    """d_k of Section 4's cost paragraph for one worker row: counts over codes 0..2s."""
+    q = np.ascontiguousarray(q, np.int8).reshape(-1)
+    counts = np.zeros(2 * s + 1, np.uint64)
+    lib().ecq_oracle_level_histogram(q, q.size, s, counts)
+    return counts
+
+
+def entropy_bound_bits(counts: np.ndarray) -> float:
+    """sum_k d_k log2(d/d_k): the entropy-coded length bound of Section 4."""
+    counts = np.ascontiguousarray(counts, np.uint64)
+    return float(lib().ecq_oracle_entropy_bound_bits(counts, counts.size))
 
 
 def max_threads() -> int:

@@ -348,3 +348,21 @@ void ecq_oracle_sgd_step(float *w, const float *gavg, float eta, int64_t n)
         w[i] = w[i] - stepv;
     }
 }
+
+/* d_k of the cost paragraph of Section 4: how many elements sit on each quantisation level.
+ * counts[c] for c = level + s in 0..2s. */
+void ecq_oracle_level_histogram(const int8_t *q, int64_t n, int s, uint64_t *counts)
+{
+    for (int c = 0; c <= 2 * s; ++c) counts[c] = 0;
+    for (int64_t i = 0; i < n; ++i) counts[(int)q[i] + s] += 1;
+}
+
+/* Entropy-coding bound of Section 4: sum_k d_k log2(d / d_k) bits, d = sum_k d_k. */
+double ecq_oracle_entropy_bound_bits(const uint64_t *counts, int bins)
+{
+    double d = 0.0, bits = 0.0;
+    for (int k = 0; k < bins; ++k) d += (double)counts[k];
+    for (int k = 0; k < bins; ++k)
+        if (counts[k] > 0) bits += (double)counts[k] * log2(d / (double)counts[k]);
+    return bits;
+}

@@ -633,3 +633,28 @@ def test_closed_loop_error_feedback_shrinks_the_gap():
     ecq = _least_squares_run(256, f32(0.2), f32(0.9), quantise=True)
     assert fp < ecq < qsgd
     assert (ecq - fp) < 0.5 * (qsgd - fp)
+
+
+# ------------------------------------------------------------------ entropy-coded length ---
+
+def test_level_histogram_and_entropy_bound():
+    """Section 4, cost paragraph: d_k = dimensions on level k; length <= sum_k d_k log2(d/d_k).
+    Closed forms: a single occupied level costs 0 bits, m equally occupied levels cost
+    d log2(m); the bound never exceeds the fixed-length d*r bits."""
+    rng = np.random.default_rng(31)
+    for s in (1, 3, 7, 127):
+        q = rng.integers(-s, s + 1, 5000).astype(np.int8)
+        counts = oracle.level_histogram(q, s)
+        assert np.array_equal(counts, np.bincount(q.astype(np.int64) + s, minlength=2 * s + 1).astype(np.uint64))
+        assert counts.sum() == q.size
+        bits = oracle.entropy_bound_bits(counts)
+        p = counts[counts > 0] / q.size
+        assert abs(bits - q.size * float(-(p * np.log2(p)).sum())) < 1e-6 * bits
+        assert bits <= q.size * oracle.code_bits(s)
+    assert oracle.entropy_bound_bits(np.array([0, 4096, 0], np.uint64)) == 0.0
+    assert oracle.entropy_bound_bits(np.array([100, 100, 100, 100], np.uint64)) == 400 * 2.0
+    assert abs(oracle.entropy_bound_bits(np.array([50, 50, 50], np.uint64)) - 150 * math.log2(3)) < 1e-9
+    # heavy-tailed gradients put most elements on level 0: far below r bits per element
+    g = (1e-3 * rng.standard_t(3, 8192)).astype(np.float32)
+    q, _, _, _ = oracle.bucket_step(g, np.zeros_like(g), 0, 0, 7, 1.0, 1.0, 1, 0)
+    assert oracle.entropy_bound_bits(oracle.level_histogram(q, 7)) < 0.5 * g.size * oracle.code_bits(7)
