@@ -164,6 +164,23 @@ int ecq_dequant_aggregate_sgd(const ecq_shape *shape, const uint8_t *codes, cons
                               float eta, float *w, float *out, void *stream);
 
 /*
+ * d_k of Section 4's cost paragraph: counts[p][c] = number of elements of worker p whose code
+ * is c (c = level + s, 0..2s).  Entropy coding of worker p's message then needs at most
+ * sum_k d_k log2(d/d_k) bits (see ecq_entropy_bound_bits).
+ *   codes   in   as written by ecq_quantize / ecq_quantize_update.
+ *   counts  out  device, uint64 [P][count_stride], count_stride >= 2s+1, 8-byte aligned; the
+ *                first 2s+1 counters of every row are overwritten, the rest left alone.
+ */
+int ecq_level_histogram(const ecq_shape *shape, const uint8_t *codes, uint64_t *counts,
+                        int64_t count_stride, void *stream);
+
+/*
+ * HOST function on HOST memory: *bits = sum_k d_k log2(d / d_k) over one histogram row of
+ * `bins` counters (d = sum_k d_k; empty levels contribute nothing), in float64.
+ */
+int ecq_entropy_bound_bits(const uint64_t *counts_host, int bins, double *bits);
+
+/*
  * The random words of Eq. (9)'s rounding decision, for inspection: words[j] is the word
  * element i0 + j of worker p consumes at iteration `step`.  words: device, [count] uint32.
  */

@@ -12,7 +12,9 @@ from .binding import (  # noqa: F401
     ecq_calib_copy,
     ecq_dequant_aggregate,
     ecq_dequant_aggregate_sgd,
+    ecq_entropy_bound_bits,
     ecq_error_update,
+    ecq_level_histogram,
     ecq_philox_words,
     ecq_quantize,
     ecq_quantize_update,

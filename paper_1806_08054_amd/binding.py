@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.ecq_quantize_update_ex.argtypes = [shp, vp, vp, f, f, u64, u64, vp, vp, C.POINTER(Tuning), vp]
         L.ecq_dequant_aggregate.argtypes = [shp, vp, vp, vp, vp]
         L.ecq_dequant_aggregate_sgd.argtypes = [shp, vp, vp, f, vp, vp, vp]
+        L.ecq_level_histogram.argtypes = [shp, vp, vp, i64, vp]
+        L.ecq_entropy_bound_bits.argtypes = [C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_double)]
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -74,7 +76,8 @@ def lib() -> C.CDLL:
         L.ecq_version.argtypes = []
         for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
                      "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
-                     "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
+                     "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits",
+                     "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -151,6 +154,19 @@ def ecq_dequant_aggregate(shape: Shape, codes, scales, out, stream=None) -> None
 def ecq_dequant_aggregate_sgd(shape: Shape, codes, scales, eta: float, w, out=None, stream=None) -> None:
     _check(lib().ecq_dequant_aggregate_sgd(C.byref(shape), _ptr(codes), _ptr(scales), eta, _ptr(w), _ptr(out),
                                            _stream(stream)), "ecq_dequant_aggregate_sgd")
+
+
+def ecq_level_histogram(shape: Shape, codes, counts, count_stride: int, stream=None) -> None:
+    _check(lib().ecq_level_histogram(C.byref(shape), _ptr(codes), _ptr(counts), count_stride, _stream(stream)),
+           "ecq_level_histogram")
+
+
+def ecq_entropy_bound_bits(counts_host) -> float:
+    """counts_host: a sequence of the 2s+1 counters of one worker row, on the host."""
+    arr = (C.c_uint64 * len(counts_host))(*[int(c) for c in counts_host])
+    bits = C.c_double(0.0)
+    _check(lib().ecq_entropy_bound_bits(arr, len(counts_host), C.byref(bits)), "ecq_entropy_bound_bits")
+    return bits.value
 
 
 def ecq_philox_words(seed: int, step: int, p: int, i0: int, count: int, words, stream=None) -> None:

@@ -232,6 +232,34 @@ int ecq_dequant_aggregate_sgd(const ecq_shape *shape, const uint8_t *codes, cons
     return ecq::launch_dequant_aggregate(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
 }
 
+int ecq_level_histogram(const ecq_shape *shape, const uint8_t *codes, uint64_t *counts, int64_t count_stride,
+                        void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!codes || !counts) return ECQ_ERR_NULL;
+    if (count_stride < 2 * (int64_t)shape->s + 1) return ECQ_ERR_STRIDE;
+    if (!ecq::aligned(codes, 4) || !ecq::aligned(counts, 8)) return ECQ_ERR_ALIGN;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    return ecq::launch_level_histogram(a, reinterpret_cast<unsigned long long *>(counts), count_stride,
+                                       static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_entropy_bound_bits(const uint64_t *counts_host, int bins, double *bits)
+{
+    if (!counts_host || !bits) return ECQ_ERR_NULL;
+    if (bins < 1 || bins > 255) return ECQ_ERR_LEVELS;
+    double d = 0.0, sum = 0.0;
+    for (int k = 0; k < bins; ++k) d += (double)counts_host[k];
+    for (int k = 0; k < bins; ++k)
+        if (counts_host[k]) sum += (double)counts_host[k] * std::log2(d / (double)counts_host[k]);
+    *bits = sum;
+    return ECQ_OK;
+}
+
 int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
                      void *stream)
 {

@@ -591,6 +591,63 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
 }
 
 // ---------------------------------------------------------------------------------------------
+// Level histogram (the d_k of the entropy-coding bound).
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_zero_counts(unsigned long long *counts, int64_t count_stride, int bins)
+{
+    if ((int)threadIdx.x < bins) counts[(int64_t)blockIdx.x * count_stride + threadIdx.x] = 0ull;
+}
+
+// A lane owns runs of 8 elements (R whole bytes); a block walks kHistPerBlock elements of one
+// row, counts into LDS and adds its totals to the row's counters once.  For r = 2 (three
+// levels) counting is done with wave ballots instead of LDS atomics, which would all hit the
+// same three addresses.
+constexpr int kHistPerBlock = 256 * 8 * 16;
+
+template <int R>
+__global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned long long *__restrict__ counts,
+                                                        const int64_t count_stride)
+{
+    __shared__ unsigned int hist[256];
+    for (int c = threadIdx.x; c < 256; c += blockDim.x) hist[c] = 0u;
+    __syncthreads();
+    const uint32_t p = blockIdx.y;
+    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    const int64_t begin = (int64_t)blockIdx.x * kHistPerBlock;
+    const int lane = threadIdx.x & 63;
+    unsigned int c0 = 0, c1 = 0, c2 = 0;                       // r = 2: per-wave totals (lane 0 keeps them)
+    for (int it = 0; it < 16; ++it) {
+        const int64_t elem = begin + ((int64_t)it * 256 + threadIdx.x) * 8;
+        const uint64_t bits = elem < a.n ? load_code_group<R>(crow, a.row_bytes, elem) : 0ull;
+        int64_t rest = a.n - elem;
+        const int valid = rest < 0 ? 0 : (rest > 8 ? 8 : (int)rest);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned int c = (unsigned int)((bits >> (R * e)) & ((1u << R) - 1u));
+            const bool on = e < valid;
+            if constexpr (R == 2) {
+                c0 += __popcll(__ballot(on && c == 0u));
+                c1 += __popcll(__ballot(on && c == 1u));
+                c2 += __popcll(__ballot(on && c == 2u));
+            } else {
+                if (on) atomicAdd(&hist[c], 1u);
+            }
+        }
+    }
+    if constexpr (R == 2) {
+        if (lane == 0) {
+            atomicAdd(&hist[0], c0);
+            atomicAdd(&hist[1], c1);
+            atomicAdd(&hist[2], c2);
+        }
+    }
+    __syncthreads();
+    const int bins = 2 * a.s + 1;
+    for (int c = threadIdx.x; c < bins; c += blockDim.x)
+        if (hist[c]) atomicAdd(&counts[(int64_t)p * count_stride + c], (unsigned long long)hist[c]);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Inspection and calibration kernels.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo,
@@ -728,6 +785,17 @@ hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
     else                                                                                                      \
         hipLaunchKernelGGL((k_dequant_aggregate<RR, 1>), grid, dim3(256), 0, stream, a, bucket_shift,         \
                            uniform_bucket, inv_p)
+    ECQ_DISPATCH_R(a.r, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int64_t count_stride,
+                                  hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_zero_counts, dim3((unsigned)a.workers), dim3(256), 0, stream, counts, count_stride, 2 * a.s + 1);
+    const dim3 grid(cdiv(a.n, kHistPerBlock), (unsigned)a.workers);
+#define CALL(RR) hipLaunchKernelGGL((k_level_histogram<RR>), grid, dim3(256), 0, stream, a, counts, count_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();

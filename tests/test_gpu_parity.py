@@ -327,6 +327,34 @@ def test_closed_loop_least_squares(E):
     assert np.mean(losses[-10:]) < 0.05 * np.mean(losses[:3])
 
 
+# ------------------------------------------------------------------ entropy-coded length ---
+
+@pytest.mark.parametrize("s,bucket,N,P", [(1, 512, 70_001, 3), (3, 64, 5000, 2), (7, 2048, 300_000, 4),
+                                          (127, 8, 9, 2), (1, 512, 1_200_003, 2)])
+def test_level_histogram(E, s, bucket, N, P):
+    """Integer counts per level, bit-exact; ragged tails (pad bits are not counted); the
+    library's entropy bound equals the oracle's."""
+    wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="student_t",
+                        data_seed=N)
+    st = GpuState(E, P, N, bucket, s)
+    g_np = synth.gradients(wl, 0).numpy()
+    st.g[:, :N] = _dev(g_np)
+    h_ref = np.zeros((P, N), np.float32)
+    q, _, _ = oracle.batch_step(g_np, h_ref.copy(), bucket, s, wl.alpha, wl.beta, SEED, 0)
+    _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, 0)
+    stride = 2 * s + 1 + 3
+    counts = torch.full((P, stride), 12345, dtype=torch.int64, device="cuda")
+    E.ecq_level_histogram(st.sh, st.codes, counts, stride)
+    torch.cuda.synchronize()
+    got = counts.cpu().numpy()
+    assert np.all(got[:, 2 * s + 1:] == 12345)
+    for p in range(P):
+        ref = oracle.level_histogram(q[p], s)
+        assert np.array_equal(got[p, : 2 * s + 1].astype(np.uint64), ref)
+        bits = E.ecq_entropy_bound_bits(list(got[p, : 2 * s + 1]))
+        assert abs(bits - oracle.entropy_bound_bits(ref)) <= 1e-9 * max(bits, 1.0)
+
+
 # ------------------------------------------------------------------ boundary errors --------
 
 def test_argument_errors_leave_outputs_untouched(E):
