@@ -188,6 +188,17 @@ int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int6
                      uint32_t *words, void *stream);
 
 /*
+ * Self-check, not part of the method: the kernels obtain |v_i| / ||v|| from a per-bucket
+ * reciprocal instead of one full division per element.  This call compares that routine with
+ * the plain correctly rounded binary32 division for every divisor significand (2^23 of them,
+ * exponents drawn over the whole normal range from `salt`) and `per_divisor` numerators each
+ * (same binade, far smaller, denormal, equal), in both of the forms the kernels use, and adds
+ * the number of differing results to *mismatches (device, uint64, zeroed by the call).
+ * Expected: 0.
+ */
+int ecq_check_division(int per_divisor, uint32_t salt, uint64_t *mismatches, void *stream);
+
+/*
  * Bandwidth calibration, not part of the method: out[i] = a[i] + b[i] over n floats
  * (two reads and one write of 4 bytes per element, the same traffic mix as the fused pass),
  * and a plain copy out[i] = a[i].  All pointers device, 16-byte aligned.

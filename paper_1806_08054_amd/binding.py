@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.ecq_dequant_aggregate_sgd.argtypes = [shp, vp, vp, f, vp, vp, vp]
         L.ecq_level_histogram.argtypes = [shp, vp, vp, i64, vp]
         L.ecq_entropy_bound_bits.argtypes = [C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_double)]
+        L.ecq_check_division.argtypes = [C.c_int, C.c_uint32, vp, vp]
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -76,7 +77,7 @@ def lib() -> C.CDLL:
         L.ecq_version.argtypes = []
         for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
                      "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
-                     "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits",
+                     "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits", "ecq_check_division",
                      "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
@@ -167,6 +168,10 @@ def ecq_entropy_bound_bits(counts_host) -> float:
     bits = C.c_double(0.0)
     _check(lib().ecq_entropy_bound_bits(arr, len(counts_host), C.byref(bits)), "ecq_entropy_bound_bits")
     return bits.value
+
+
+def ecq_check_division(per_divisor: int, salt: int, mismatches, stream=None) -> None:
+    _check(lib().ecq_check_division(per_divisor, salt, _ptr(mismatches), _stream(stream)), "ecq_check_division")
 
 
 def ecq_philox_words(seed: int, step: int, p: int, i0: int, count: int, words, stream=None) -> None:

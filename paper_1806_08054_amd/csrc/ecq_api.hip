@@ -260,6 +260,17 @@ int ecq_entropy_bound_bits(const uint64_t *counts_host, int bins, double *bits)
     return ECQ_OK;
 }
 
+int ecq_check_division(int per_divisor, uint32_t salt, uint64_t *mismatches, void *stream)
+{
+    if (!mismatches) return ECQ_ERR_NULL;
+    if (per_divisor < 1 || per_divisor > 65536) return ECQ_ERR_SHAPE;
+    if (!ecq::aligned(mismatches, 8)) return ECQ_ERR_ALIGN;
+    return ecq::launch_check_division(per_divisor, salt, reinterpret_cast<unsigned long long *>(mismatches),
+                                      static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
 int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
                      void *stream)
 {

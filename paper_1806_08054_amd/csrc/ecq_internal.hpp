@@ -49,6 +49,8 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream);
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream);
 hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int64_t count_stride,
                                   hipStream_t stream);
+hipError_t launch_check_division(int per_divisor, uint32_t salt, unsigned long long *mismatches,
+                                 hipStream_t stream);
 hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, uint32_t step_hi,
                                uint32_t p, uint64_t i0, int64_t count, uint32_t *words,
                                hipStream_t stream);

@@ -650,6 +650,48 @@ __global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned 
 // ---------------------------------------------------------------------------------------------
 // Inspection and calibration kernels.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
+// Division self-check: thread t owns the divisor with significand t (all 2^23) and an exponent
+// drawn from `salt`; numerators never exceed the divisor, as in the kernels.
+template <bool SCALE24>
+__global__ void __launch_bounds__(256) k_check_division(unsigned long long *mismatches, int per_divisor,
+                                                       int wide_exponents, uint32_t salt)
+{
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    const int ex = wide_exponents ? 1 + (int)(mix32(t + salt) % 253u) : 27 + (int)(mix32(t ^ salt) % 201u);
+    const float d = __uint_as_float(((uint32_t)ex << 23) | (t & 0x7FFFFFu));
+    const Ratio rt = make_ratio<SCALE24>(d);
+    unsigned int bad = 0;
+    for (int i = 0; i < per_divisor; ++i) {
+        const uint32_t r = mix32(t * 2654435761u + (uint32_t)i * 40503u + salt);
+        const uint32_t mode = r & 7u;
+        float av;
+        if (mode < 5u) {                                       // same binade or the one below
+            av = __uint_as_float(((uint32_t)(ex - (int)((r >> 3) & 1u)) << 23) | (mix32(r) & 0x7FFFFFu));
+        } else if (mode == 5u) {                               // up to 2^60 smaller
+            int ee = ex - (int)(mix32(r) % 60u);
+            ee = ee < 0 ? 0 : ee;
+            av = __uint_as_float(((uint32_t)ee << 23) | (mix32(r + 1u) & 0x7FFFFFu));
+        } else if (mode == 6u) {                               // tiny, denormals included
+            av = __uint_as_float(mix32(r) & 0x00FFFFFFu);
+        } else {
+            av = d;
+        }
+        if (!(av <= d)) av = d;
+        float want = av / d;
+        if (SCALE24) want = want * 0x1p24f;
+        bad += __float_as_uint(ratio<SCALE24>(av, rt)) != __float_as_uint(want);
+    }
+    if (bad) atomicAdd(mismatches, (unsigned long long)bad);
+}
+
+__global__ void k_zero_u64(unsigned long long *x) { *x = 0ull; }
+
 __global__ void __launch_bounds__(256) k_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo,
                                                      uint32_t step_hi, uint32_t p, uint64_t i0,
                                                      int64_t count, uint32_t *__restrict__ words)
@@ -798,6 +840,18 @@ hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int
 #define CALL(RR) hipLaunchKernelGGL((k_level_histogram<RR>), grid, dim3(256), 0, stream, a, counts, count_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_check_division(int per_divisor, uint32_t salt, unsigned long long *mismatches,
+                                 hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(1), 0, stream, mismatches);
+    const dim3 grid((1u << 23) / 256);
+    for (int wide = 0; wide < 2; ++wide) {
+        hipLaunchKernelGGL(k_check_division<false>, grid, dim3(256), 0, stream, mismatches, per_divisor, wide, salt);
+        hipLaunchKernelGGL(k_check_division<true>, grid, dim3(256), 0, stream, mismatches, per_divisor, wide, salt + 1u);
+    }
     return hipGetLastError();
 }
 

@@ -127,6 +127,15 @@ def test_philox_words_bit_exact(E):
         assert np.array_equal(got, oracle.words(seed, step, p, i0, count))
 
 
+def test_division_routine_matches_ieee_division(E):
+    """The per-bucket-reciprocal quotient equals the correctly rounded division for every
+    divisor significand: 2^23 divisors x 256 numerators x 2 exponent ranges x 2 forms."""
+    bad = torch.full((1,), 77, dtype=torch.int64, device="cuda")
+    E.ecq_check_division(256, 0xC0FFEE, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+
+
 # ------------------------------------------------------------------ the five workloads -----
 
 def test_tiny_free_running(E):
