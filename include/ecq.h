@@ -88,7 +88,10 @@ typedef struct {
                               2 = two-pass (norm kernel, then quantise kernel)             */
     int32_t waves_per_bucket; /* 0 = choose; else 1,2,4,8,16 (path 1, buckets >= 256)      */
     int32_t block_threads; /* 0 = choose; else 64..1024, multiple of 64                    */
-    int32_t reserved;      /* must be 0                                                    */
+    int32_t block_order;   /* path 1, buckets >= 256.  0 = choose; 1 = blocks in address order,
+                              worker rows issued in launches of about 2^28 elements; 2 = the
+                              same with one contiguous region of blocks per XCD; 3 = address
+                              order, all rows in one launch                               */
 } ecq_tuning;
 
 /* r = ceil(log2(2s+1)) bits per encoded element (Section 4, cost paragraph);

@@ -36,7 +36,7 @@ class Shape(C.Structure):
 class Tuning(C.Structure):
     """Mirror of ecq_tuning."""
     _fields_ = [("path", C.c_int32), ("waves_per_bucket", C.c_int32), ("block_threads", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("block_order", C.c_int32)]
 
 
 _lib = None

@@ -67,7 +67,7 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
     const int b = sh.bucket;
     int path = 0, waves = 0, threads = 0;
     if (tu) {
-        if (tu->reserved != 0) return ECQ_ERR_PARAM;
+        if (tu->block_order < 0 || tu->block_order > 3) return ECQ_ERR_PARAM;
         path = tu->path;
         waves = tu->waves_per_bucket;
         threads = tu->block_threads;
@@ -107,6 +107,12 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
         pl.waves_per_bucket = waves;
         pl.vec_per_lane = vec;
         pl.block_threads = threads;
+        const int order = tu ? tu->block_order : 0;
+        pl.xcd_striped = order == 2;
+        if (pl.xcd_striped && (((int64_t)sh.workers * ((sh.n + b - 1) / b)) >> 28) > 0) pl.xcd_striped = 0;
+        // About 2^28 elements per launch (order 3: everything in one launch).
+        const int64_t rows = (((int64_t)1 << 28) + sh.n / 2) / sh.n;
+        pl.rows_per_launch = order == 3 ? 0 : (int)(rows < 1 ? 1 : (rows > sh.workers ? sh.workers : rows));
     }
     *plan = pl;
     return ECQ_OK;

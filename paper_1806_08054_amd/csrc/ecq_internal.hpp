@@ -40,6 +40,8 @@ struct Plan {
     int waves_per_bucket;  // path 1, bucket >= 256
     int vec_per_lane;      // path 1: float4 per lane (1, 2, 4, 8)
     int block_threads;
+    int rows_per_launch;   // path 1, bucket >= 256: worker rows per kernel launch (0 = all)
+    int xcd_striped;       // path 1, bucket >= 256: one contiguous region of blocks per XCD
 };
 
 int make_plan(const ecq_shape &shape, const ecq_tuning *tuning, Plan *plan);

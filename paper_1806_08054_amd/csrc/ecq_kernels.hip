@@ -145,10 +145,25 @@ __device__ __forceinline__ void fill_xi_table(float *xi_tab, int s)
 // Single pass, buckets of 256 elements or more: a team of W waves per bucket, J float4 per lane.
 // ---------------------------------------------------------------------------------------------
 template <int R, int J, bool UPDATE>
-__global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_shift)
+__global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_shift, const int64_t stripe,
+                                                     const uint32_t blocks_per_row, const uint32_t worker0,
+                                                     const uint32_t workers)
 {
     __shared__ float xi_tab[128];
     __shared__ uint32_t wave_norm[16];
+    // Block -> (worker row, block of the row).  Workgroups go to the chip's 8 XCDs round-robin
+    // by id.  With stripe > 0 the launch is one-dimensional and XCD x takes the x-th eighth of
+    // all blocks in address order, so each XCD streams through its own contiguous region and
+    // stays compact in memory however far the XCDs drift apart during a long launch.
+    // A launch covers workers worker0 .. worker0 + workers - 1.
+    uint32_t row_block = blockIdx.x, p = worker0 + blockIdx.y;
+    if (stripe > 0) {
+        const int64_t id = (int64_t)(blockIdx.x & 7u) * stripe + (blockIdx.x >> 3);
+        if (id >= (int64_t)blocks_per_row * workers) return;    // whole block
+        const uint32_t row = (uint32_t)(id / blocks_per_row);
+        p = worker0 + row;
+        row_block = (uint32_t)(id - (int64_t)row * blocks_per_row);
+    }
     if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
 
     const int lane = threadIdx.x & 63;
@@ -157,8 +172,7 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
     const int team = wave >> w_shift;
     const int wit = wave & (W - 1);
     const int teams = blockDim.x >> (6 + w_shift);
-    const int64_t k = (int64_t)blockIdx.x * teams + team;
-    const uint32_t p = blockIdx.y;
+    const int64_t k = (int64_t)row_block * teams + team;
     const bool active = k < a.nb;
     const int64_t e0 = active ? k * (int64_t)a.bucket : 0;
     const int64_t rest = a.n - e0;
@@ -738,11 +752,26 @@ static void launch_team_j(const Args &a, const Plan &plan, bool update, hipStrea
     int w_shift = 0;
     while ((1 << w_shift) < plan.waves_per_bucket) ++w_shift;
     const int teams = plan.block_threads / (64 * plan.waves_per_bucket);
-    const dim3 grid(cdiv(a.nb, teams), (unsigned)a.workers);
-    if (update)
-        hipLaunchKernelGGL((k_fused_team<R, J, true>), grid, dim3(plan.block_threads), 0, st, a, w_shift);
-    else
-        hipLaunchKernelGGL((k_fused_team<R, J, false>), grid, dim3(plan.block_threads), 0, st, a, w_shift);
+    const unsigned blocks_per_row = cdiv(a.nb, teams);
+    // Long launches lose bandwidth on this chip (the XCDs drift apart and the window of
+    // addresses in flight widens); rows are therefore issued in groups of about 2^28 elements,
+    // one launch per group, back to back on the stream.
+    int64_t rows_per_launch = plan.rows_per_launch > 0 ? plan.rows_per_launch : a.workers;
+    for (int64_t w0 = 0; w0 < a.workers; w0 += rows_per_launch) {
+        const unsigned rows = (unsigned)((a.workers - w0 < rows_per_launch) ? a.workers - w0 : rows_per_launch);
+        dim3 grid(blocks_per_row, rows);
+        int64_t stripe = 0;
+        if (plan.xcd_striped) {
+            stripe = ((int64_t)blocks_per_row * rows + 7) / 8;
+            grid = dim3((unsigned)(stripe * 8));
+        }
+        if (update)
+            hipLaunchKernelGGL((k_fused_team<R, J, true>), grid, dim3(plan.block_threads), 0, st, a, w_shift, stripe,
+                               blocks_per_row, (uint32_t)w0, rows);
+        else
+            hipLaunchKernelGGL((k_fused_team<R, J, false>), grid, dim3(plan.block_threads), 0, st, a, w_shift, stripe,
+                               blocks_per_row, (uint32_t)w0, rows);
+    }
 }
 
 template <int R>
