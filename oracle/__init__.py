@@ -104,6 +104,14 @@ def _declare(L):
     L.ecq_oracle_level_histogram.restype = None
     L.ecq_oracle_entropy_bound_bits.argtypes = [_u64p, C.c_int]
     L.ecq_oracle_entropy_bound_bits.restype = C.c_double
+    L.ecq_oracle_huffman_lengths.argtypes = [_u64p, C.c_int, _u8p]
+    L.ecq_oracle_huffman_lengths.restype = None
+    L.ecq_oracle_huffman_codes.argtypes = [_u8p, C.c_int, _u64p]
+    L.ecq_oracle_huffman_codes.restype = None
+    L.ecq_oracle_huffman_encode.argtypes = [_i8p, C.c_int64, C.c_int, _u8p, _u64p, _u8p, C.c_int64, C.c_int64, _u64p]
+    L.ecq_oracle_huffman_encode.restype = C.c_int64
+    L.ecq_oracle_huffman_decode.argtypes = [_u8p, C.c_uint64, C.c_int64, C.c_int, _u8p, _u64p, _i8p]
+    L.ecq_oracle_huffman_decode.restype = None
 
 
 # ------------------------------------------------------------------ scalar steps ------------
@@ -277,6 +285,44 @@ def entropy_bound_bits(counts: np.ndarray) -> float:
     """sum_k d_k log2(d/d_k): the entropy-coded length bound of Section 4."""
     counts = np.ascontiguousarray(counts, np.uint64)
     return float(lib().ecq_oracle_entropy_bound_bits(counts, counts.size))
+
+
+HUFFMAN_TILE = 1024     # elements per independently decodable tile
+
+
+def huffman_lengths(counts: np.ndarray) -> np.ndarray:
+    """Codeword length of every level from its count (Huffman, 1952; deterministic ties)."""
+    counts = np.ascontiguousarray(counts, np.uint64)
+    lengths = np.zeros(counts.size, np.uint8)
+    lib().ecq_oracle_huffman_lengths(counts, counts.size, lengths)
+    return lengths
+
+
+def huffman_codes(lengths: np.ndarray) -> np.ndarray:
+    """Canonical codewords (integers, most significant bit first) from the lengths."""
+    lengths = np.ascontiguousarray(lengths, np.uint8)
+    codes = np.zeros(lengths.size, np.uint64)
+    lib().ecq_oracle_huffman_codes(lengths, lengths.size, codes)
+    return codes
+
+
+def huffman_encode(q: np.ndarray, s: int, lengths: np.ndarray, codes: np.ndarray, tile: int = HUFFMAN_TILE):
+    """One worker row -> (stream bytes, tile bit offsets incl. the total, total bits)."""
+    q = np.ascontiguousarray(q, np.int8).reshape(-1)
+    cap = (row_bytes(q.size, s) + 3) // 4 * 4
+    out = np.zeros(max(cap, 4), np.uint8)
+    offs = np.zeros((q.size + tile - 1) // tile + 1, np.uint64)
+    bits = lib().ecq_oracle_huffman_encode(q, q.size, s, np.ascontiguousarray(lengths, np.uint8),
+                                           np.ascontiguousarray(codes, np.uint64), out, out.size, tile, offs)
+    return out, offs, int(bits)
+
+
+def huffman_decode(stream: np.ndarray, start: int, n: int, s: int, lengths: np.ndarray, codes: np.ndarray):
+    q = np.zeros(n, np.int8)
+    lib().ecq_oracle_huffman_decode(np.ascontiguousarray(stream, np.uint8), start, n, s,
+                                    np.ascontiguousarray(lengths, np.uint8),
+                                    np.ascontiguousarray(codes, np.uint64), q)
+    return q
 
 
 def max_threads() -> int:

@@ -366,3 +366,118 @@ double ecq_oracle_entropy_bound_bits(const uint64_t *counts, int bins)
         if (counts[k] > 0) bits += (double)counts[k] * log2(d / (double)counts[k]);
     return bits;
 }
+
+/* ---------------------------------------------------------------- Huffman coding --------- */
+/* Section 4 names Huffman encoding (Huffman, 1952) as the way to go below r bits per element.
+ * The code is built per worker row from that row's level counts d_k.
+ *
+ * Conventions of this repository (the paper fixes none of them):
+ *  - Construction: leaves are the levels with d_k > 0, numbered by their code c = level + s;
+ *    repeatedly the two live nodes that come first in the order (weight, number) are merged
+ *    into a new node that takes the next free number (2s+1, 2s+2, ...); a level's codeword
+ *    length is its depth.  A row with a single occupied level gives it length 1.
+ *  - Codewords are canonical: levels sorted by (length, c); the first codeword is 0, each next
+ *    one is (previous + 1) shifted left by the growth in length.
+ *  - Bit stream: LSB-first like the fixed-length stream (stream bit j is bit (j & 7) of byte
+ *    (j >> 3)); a codeword is written most significant bit first; pad bits are zero.
+ *  - The row is cut into tiles of `tile` elements; tile_offsets[t] is the stream bit at which
+ *    tile t starts and tile_offsets[number of tiles] the total length, so tiles decode
+ *    independently.
+ */
+
+void ecq_oracle_huffman_lengths(const uint64_t *counts, int bins, uint8_t *lengths)
+{
+    enum { MAXN = 512 };
+    uint64_t weight[MAXN];
+    int parent[MAXN], live[MAXN];
+    int nodes = bins, alive = 0;
+    for (int c = 0; c < bins; ++c) {
+        weight[c] = counts[c];
+        parent[c] = -1;
+        live[c] = counts[c] > 0;
+        alive += live[c];
+        lengths[c] = 0;
+    }
+    if (alive == 1) {
+        for (int c = 0; c < bins; ++c) if (live[c]) lengths[c] = 1;
+        return;
+    }
+    while (alive > 1) {
+        int pick[2];
+        for (int k = 0; k < 2; ++k) {
+            int best = -1;
+            for (int i = 0; i < nodes; ++i)
+                if (live[i] && (best < 0 || weight[i] < weight[best])) best = i;  /* ties: lowest number */
+            live[best] = 0;
+            pick[k] = best;
+        }
+        weight[nodes] = weight[pick[0]] + weight[pick[1]];
+        parent[nodes] = -1;
+        live[nodes] = 1;
+        parent[pick[0]] = nodes;
+        parent[pick[1]] = nodes;
+        ++nodes;
+        --alive;
+    }
+    for (int c = 0; c < bins; ++c) {
+        if (!counts[c]) continue;
+        int depth = 0;
+        for (int i = c; parent[i] >= 0; i = parent[i]) ++depth;
+        lengths[c] = (uint8_t)depth;
+    }
+}
+
+/* Canonical codewords (as integers, most significant bit = first bit) from the lengths. */
+void ecq_oracle_huffman_codes(const uint8_t *lengths, int bins, uint64_t *codes)
+{
+    uint64_t next = 0;
+    int prev_len = 0;
+    for (int c = 0; c < bins; ++c) codes[c] = 0;
+    for (int len = 1; len < 64; ++len)
+        for (int c = 0; c < bins; ++c)
+            if (lengths[c] == len) {
+                if (prev_len) next = (next + 1) << (len - prev_len);
+                codes[c] = next;
+                prev_len = len;
+            }
+}
+
+/* Encodes one worker row.  Returns the total number of bits; out must hold them (it is
+ * zeroed up to out_bytes first).  tile_offsets gets ceil(n/tile) + 1 entries. */
+int64_t ecq_oracle_huffman_encode(const int8_t *q, int64_t n, int s, const uint8_t *lengths,
+                                  const uint64_t *codes, uint8_t *out, int64_t out_bytes, int64_t tile,
+                                  uint64_t *tile_offsets)
+{
+    memset(out, 0, (size_t)out_bytes);
+    int64_t pos = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (i % tile == 0) tile_offsets[i / tile] = (uint64_t)pos;
+        int c = (int)q[i] + s;
+        for (int b = lengths[c] - 1; b >= 0; --b) {            /* most significant bit first */
+            if ((codes[c] >> b) & 1u) out[pos >> 3] |= (uint8_t)(1u << (pos & 7));
+            ++pos;
+        }
+    }
+    tile_offsets[(n + tile - 1) / tile] = (uint64_t)pos;
+    return pos;
+}
+
+/* Decodes n levels starting at stream bit `start` by walking the canonical code. */
+void ecq_oracle_huffman_decode(const uint8_t *stream, uint64_t start, int64_t n, int s, const uint8_t *lengths,
+                               const uint64_t *codes, int8_t *q)
+{
+    int bins = 2 * s + 1;
+    uint64_t pos = start;
+    for (int64_t i = 0; i < n; ++i) {
+        uint64_t word = 0;
+        int len = 0, found = -1;
+        while (found < 0 && len < 64) {
+            word = (word << 1) | (uint64_t)((stream[pos >> 3] >> (pos & 7)) & 1u);
+            ++pos;
+            ++len;
+            for (int c = 0; c < bins; ++c)
+                if (lengths[c] == len && codes[c] == word) found = c;
+        }
+        q[i] = (int8_t)(found - s);
+    }
+}

@@ -186,3 +186,50 @@ def unpack(data: bytes, n: int, s: int):
     r = code_bits(s)
     big = int.from_bytes(data, "little")
     return [((big >> (i * r)) & ((1 << r) - 1)) - s for i in range(n)]
+
+
+# ---------------------------------------------------------------- Huffman coding ------------
+
+def huffman_lengths(counts):
+    """Merge the two live nodes first in (weight, number) order; new nodes take the next
+    number; a level's length is its depth (a lone occupied level gets length 1)."""
+    bins = len(counts)
+    live = {c: counts[c] for c in range(bins) if counts[c] > 0}
+    lengths = [0] * bins
+    if len(live) == 1:
+        lengths[next(iter(live))] = 1
+        return lengths
+    members = {c: [c] for c in live}
+    nxt = bins
+    while len(live) > 1:
+        a = min(live, key=lambda i: (live[i], i)); wa = live.pop(a)
+        b = min(live, key=lambda i: (live[i], i)); wb = live.pop(b)
+        for leaf in members[a] + members[b]:
+            lengths[leaf] += 1
+        live[nxt] = wa + wb
+        members[nxt] = members.pop(a) + members.pop(b)
+        nxt += 1
+    return lengths
+
+
+def huffman_codes(lengths):
+    order = sorted((l, c) for c, l in enumerate(lengths) if l > 0)
+    codes = [0] * len(lengths)
+    code, prev = 0, None
+    for l, c in order:
+        if prev is not None:
+            code = (code + 1) << (l - prev)
+        codes[c] = code
+        prev = l
+    return codes
+
+
+def huffman_encode(levels, s, lengths, codes):
+    """Bit stream as one little-endian big integer; a codeword goes in first-bit-first."""
+    big, pos = 0, 0
+    for q in levels:
+        c = q + s
+        for b in range(lengths[c] - 1, -1, -1):
+            big |= ((codes[c] >> b) & 1) << pos
+            pos += 1
+    return big, pos

@@ -658,3 +658,94 @@ def test_level_histogram_and_entropy_bound():
     g = (1e-3 * rng.standard_t(3, 8192)).astype(np.float32)
     q, _, _, _ = oracle.bucket_step(g, np.zeros_like(g), 0, 0, 7, 1.0, 1.0, 1, 0)
     assert oracle.entropy_bound_bits(oracle.level_histogram(q, 7)) < 0.5 * g.size * oracle.code_bits(7)
+
+
+# ------------------------------------------------------------------ Huffman coding ---------
+
+def _kraft(lengths):
+    return sum(Fraction(1, 1 << int(l)) for l in lengths if l > 0)
+
+
+def test_huffman_textbook_example_and_kraft():
+    """Huffman (1952).  The classic six-symbol example with frequencies 45, 13, 12, 16, 9, 5
+    costs 224 bits with lengths 1,3,3,3,4,4; a full code satisfies Kraft with equality."""
+    counts = np.array([45, 13, 12, 16, 9, 5], np.uint64)
+    lengths = oracle.huffman_lengths(counts)
+    assert list(lengths) == [1, 3, 3, 3, 4, 4]
+    assert int((counts * lengths).sum()) == 224
+    assert _kraft(lengths) == 1
+    assert [int(c) for c in oracle.huffman_codes(lengths)] == [0b0, 0b100, 0b101, 0b110, 0b1110, 0b1111]
+    # degenerate rows
+    assert list(oracle.huffman_lengths(np.array([0, 7, 0], np.uint64))) == [0, 1, 0]
+    assert list(oracle.huffman_lengths(np.array([0, 0, 0], np.uint64))) == [0, 0, 0]
+    assert list(oracle.huffman_lengths(np.array([3, 0, 3], np.uint64))) == [1, 0, 1]
+
+
+def test_huffman_is_optimal_and_between_entropy_bounds():
+    """Optimal among prefix codes (brute force over every length assignment with Kraft <= 1 on
+    small alphabets) and entropy <= length < entropy + d, the window the paper's bound
+    sum_k d_k log2(d/d_k) sits at the bottom of."""
+    import itertools
+    rng = np.random.default_rng(41)
+    for trial in range(60):
+        m = int(rng.integers(2, 6))
+        counts = rng.integers(1, 50, m).astype(np.uint64)
+        if trial % 5 == 0:
+            counts[:] = counts[0]                       # all ties
+        lengths = oracle.huffman_lengths(counts)
+        cost = int((counts * lengths).sum())
+        best = min(int(sum(int(c) * l for c, l in zip(counts, ls)))
+                   for ls in itertools.product(range(1, m + 1), repeat=m) if _kraft(ls) <= 1)
+        assert cost == best
+        assert _kraft(lengths) == 1
+        assert list(lengths) == X.huffman_lengths([int(c) for c in counts])
+    for s in (1, 3, 7, 60, 127):
+        p = rng.dirichlet(np.full(2 * s + 1, 0.3))
+        counts = rng.multinomial(200_000, p).astype(np.uint64)
+        lengths = oracle.huffman_lengths(counts)
+        assert list(lengths) == X.huffman_lengths([int(c) for c in counts])
+        assert [int(c) for c in oracle.huffman_codes(lengths)] == X.huffman_codes([int(l) for l in lengths])
+        bits = int((counts * lengths).sum())
+        h = oracle.entropy_bound_bits(counts)
+        assert h <= bits < h + counts.sum()
+        assert bits <= int(counts.sum()) * oracle.code_bits(s)      # never worse than fixed length
+        assert _kraft(lengths) == 1 and lengths.max() < 64
+
+
+def test_huffman_codes_are_prefix_free_and_canonical():
+    rng = np.random.default_rng(42)
+    counts = rng.integers(0, 1000, 31).astype(np.uint64)
+    counts[5] = 0
+    lengths = oracle.huffman_lengths(counts)
+    codes = oracle.huffman_codes(lengths)
+    words = {c: format(int(codes[c]), "b").zfill(int(lengths[c])) for c in range(31) if lengths[c]}
+    assert 5 not in words and len(set(words.values())) == len(words)
+    for a in words:
+        for b in words:
+            assert a == b or not words[b].startswith(words[a])
+    order = sorted(words, key=lambda c: (lengths[c], c))
+    assert [words[c] for c in order] == sorted(words.values(), key=lambda w: (len(w), w))
+
+
+@pytest.mark.parametrize("s", [1, 3, 7, 100])
+def test_huffman_stream_round_trip_and_tiles(s):
+    """Encode / decode round trip, the stream read as a little-endian integer against the
+    big-integer model, zero pad bits, and independent decoding from every tile offset."""
+    rng = np.random.default_rng(s)
+    n = 3 * oracle.HUFFMAN_TILE + 77
+    g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    q, _, _, _ = oracle.bucket_step(g, np.zeros_like(g), 0, 0, s, 1.0, 1.0, 1, 0)
+    counts = oracle.level_histogram(q, s)
+    lengths = oracle.huffman_lengths(counts)
+    codes = oracle.huffman_codes(lengths)
+    stream, offs, bits = oracle.huffman_encode(q, s, lengths, codes)
+    assert bits == int((counts * lengths).sum()) == int(offs[-1])
+    big, pos = X.huffman_encode([int(x) for x in q], s, [int(l) for l in lengths], [int(c) for c in codes])
+    assert pos == bits and int.from_bytes(bytes(stream), "little") == big
+    assert np.array_equal(oracle.huffman_decode(stream, 0, n, s, lengths, codes), q)
+    T = oracle.HUFFMAN_TILE
+    assert offs.size == 5 and offs[0] == 0 and np.all(np.diff(offs.astype(np.int64)) > 0)
+    for t in range(4):
+        cnt = min(T, n - t * T)
+        assert np.array_equal(oracle.huffman_decode(stream, int(offs[t]), cnt, s, lengths, codes), q[t * T:t * T + cnt])
+    assert bits < n * oracle.code_bits(s)
