@@ -242,4 +242,19 @@ __device__ __forceinline__ void store_code_bytes(uint8_t *dst, uint64_t bits, in
         if (b < nbytes && (int64_t)b < limit) dst[b] = (uint8_t)(bits >> (8 * b));
 }
 
+// ---- reading packed codes ------------------------------------------------------------------
+
+// The R bytes that hold the codes of the 8 elements starting at `elem` (a multiple of 8).
+template <int R>
+__device__ __forceinline__ uint64_t load_code_group(const uint8_t *__restrict__ crow,
+                                                    int64_t row_bytes, int64_t elem)
+{
+    const int64_t byte_off = (elem >> 3) * R;
+    uint64_t bits = 0;
+#pragma unroll
+    for (int b = 0; b < R; ++b)
+        if (byte_off + b < row_bytes) bits |= (uint64_t)crow[byte_off + b] << (8 * b);
+    return bits;
+}
+
 }  // namespace ecq

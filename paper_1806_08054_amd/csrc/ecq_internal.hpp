@@ -60,4 +60,19 @@ hipError_t launch_calib_add(const float *a, const float *b, float *out, int64_t 
                             hipStream_t stream);
 hipError_t launch_calib_copy(const float *a, float *out, int64_t n, hipStream_t stream);
 
+static inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
+
 }  // namespace ecq
+
+// Runs CALL(R) with the code width as a compile-time constant.
+#define ECQ_DISPATCH_R(r, CALL)      \
+    switch (r) {                     \
+    case 2: CALL(2); break;          \
+    case 3: CALL(3); break;          \
+    case 4: CALL(4); break;          \
+    case 5: CALL(5); break;          \
+    case 6: CALL(6); break;          \
+    case 7: CALL(7); break;          \
+    default: CALL(8); break;         \
+    }
+

@@ -335,19 +335,6 @@ __global__ void __launch_bounds__(256) k_zero_scales(const Args a)
 // Decode side.
 // ---------------------------------------------------------------------------------------------
 
-// The R bytes that hold the codes of the 8 elements starting at `elem` (a multiple of 8).
-template <int R>
-__device__ __forceinline__ uint64_t load_code_group(const uint8_t *__restrict__ crow,
-                                                    int64_t row_bytes, int64_t elem)
-{
-    const int64_t byte_off = (elem >> 3) * R;
-    uint64_t bits = 0;
-#pragma unroll
-    for (int b = 0; b < R; ++b)
-        if (byte_off + b < row_bytes) bits |= (uint64_t)crow[byte_off + b] << (8 * b);
-    return bits;
-}
-
 // Eq. (8) from a code: scale * fl(|q|/s), negated iff q < 0.
 template <int R>
 __device__ __forceinline__ float decode_one(uint64_t bits, int e, int s, float scale,
@@ -744,7 +731,6 @@ __global__ void __launch_bounds__(256) k_calib_copy(const float *__restrict__ x,
 // ---------------------------------------------------------------------------------------------
 // Launchers.
 // ---------------------------------------------------------------------------------------------
-static inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
 
 template <int R, int J>
 static void launch_team_j(const Args &a, const Plan &plan, bool update, hipStream_t st)
@@ -809,17 +795,6 @@ static void launch_quantize_r(const Args &a, const Plan &plan, bool update, hipS
         launch_chunk<R>(a, 0, 256, update, st);
     }
 }
-
-#define ECQ_DISPATCH_R(r, CALL)      \
-    switch (r) {                     \
-    case 2: CALL(2); break;          \
-    case 3: CALL(3); break;          \
-    case 4: CALL(4); break;          \
-    case 5: CALL(5); break;          \
-    case 6: CALL(6); break;          \
-    case 7: CALL(7); break;          \
-    default: CALL(8); break;         \
-    }
 
 hipError_t launch_quantize(const Args &a, const Plan &plan, bool update_h, hipStream_t stream)
 {
