@@ -184,6 +184,72 @@ int ecq_level_histogram(const ecq_shape *shape, const uint8_t *codes, uint64_t *
 int ecq_entropy_bound_bits(const uint64_t *counts_host, int bins, double *bits);
 
 /*
+ * Huffman coding of the quantised levels.  Section 4's cost paragraph names Huffman encoding
+ * as the way to go below r bits per element, and the paper's communication-cost figures assume
+ * it.  One code per worker row, built from that row's counts d_k.  Conventions (the paper
+ * fixes none of them):
+ *  - construction: leaves are the levels with d_k > 0, numbered by their code c = level + s;
+ *    the two live nodes that come first in the order (weight, number) are merged into a new
+ *    node that takes the next free number (2s+1, 2s+2, ...); a level's codeword length is its
+ *    depth; a row with a single occupied level gives it length 1; unused levels get length 0;
+ *  - codewords are canonical: levels sorted by (length, c), first codeword 0, each next one
+ *    is (previous + 1) shifted left by the growth in length;
+ *  - the stream is LSB-first like the fixed-length one (stream bit j is bit (j & 7) of byte
+ *    (j >> 3)); a codeword is written most significant bit first; pad bits are zero;
+ *  - a row is cut into tiles of ECQ_HUFFMAN_TILE elements whose bit offsets are kept, so
+ *    tiles encode and decode independently.
+ * A code built from a row's own counts never needs more than n*r bits for that row, so a
+ * stream row of ecq_row_bytes() bytes (rounded up to 4) always suffices.
+ */
+#define ECQ_HUFFMAN_TILE 1024
+
+/* *tiles = ceil(n / ECQ_HUFFMAN_TILE). */
+int ecq_huffman_num_tiles(int64_t n, int64_t *tiles);
+
+/*
+ * Codeword lengths and canonical codewords of every worker row from its level counts.
+ *   counts     in   device, uint64 [workers][table_stride], as written by ecq_level_histogram
+ *                   (each row must sum to at most ECQ_MAX_N: no codeword then exceeds 63 bits).
+ *   lengths    out  device, uint8  [workers][table_stride]: bits of level c's codeword, 0 = unused.
+ *   codewords  out  device, uint64 [workers][table_stride]: the codeword as an integer whose
+ *                   most significant of `length` bits is sent first.  8-byte aligned.
+ * table_stride >= 2s+1; only the first 2s+1 entries of each row are written.
+ */
+int ecq_huffman_build(int workers, int s, const uint64_t *counts, int64_t table_stride,
+                      uint8_t *lengths, uint64_t *codewords, void *stream);
+
+/*
+ * Re-encodes every worker's fixed-length message with its row's Huffman code.
+ *   codes         in   as written by ecq_quantize / ecq_quantize_update (shape describes it).
+ *   lengths, codewords  in  as written by ecq_huffman_build (same table_stride).
+ *   streams       out  device, bytes [workers][stream_stride], 4-byte aligned, stream_stride a
+ *                      multiple of 4 and >= ecq_row_bytes() rounded up to 4.  Row p receives
+ *                      tile_offsets[p][tiles] bits; the bytes that hold them, rounded up to a
+ *                      multiple of 4, are written in full (pad bits zero), the rest of the row
+ *                      is left alone.
+ *   tile_offsets  out  device, uint64 [workers][offset_stride], offset_stride >= tiles + 1:
+ *                      entry t is the stream bit at which tile t of the row starts, entry
+ *                      `tiles` the row's total number of bits.
+ * Tables that do not belong to the codes (a level present in the message but with length 0,
+ * or a total beyond the stream row) give a meaningless stream, never an out-of-range access.
+ */
+int ecq_huffman_encode(const ecq_shape *shape, const uint8_t *codes, const uint8_t *lengths,
+                       const uint64_t *codewords, int64_t table_stride, uint8_t *streams,
+                       int64_t stream_stride, uint64_t *tile_offsets, int64_t offset_stride,
+                       void *stream);
+
+/*
+ * Inverse of ecq_huffman_encode: rebuilds the fixed-length message (which
+ * ecq_dequant_aggregate and ecq_error_update read) from streams, tile offsets and tables.
+ *   codes  out  device, [workers][code_stride] bytes; the first ecq_row_bytes() bytes of every
+ *               row are written in full (pad bits zero).
+ */
+int ecq_huffman_decode(const ecq_shape *shape, const uint8_t *streams, int64_t stream_stride,
+                       const uint64_t *tile_offsets, int64_t offset_stride, const uint8_t *lengths,
+                       const uint64_t *codewords, int64_t table_stride, uint8_t *codes,
+                       void *stream);
+
+/*
  * The random words of Eq. (9)'s rounding decision, for inspection: words[j] is the word
  * element i0 + j of worker p consumes at iteration `step`.  words: device, [count] uint32.
  */

@@ -15,6 +15,10 @@ from .binding import (  # noqa: F401
     ecq_dequant_aggregate_sgd,
     ecq_entropy_bound_bits,
     ecq_error_update,
+    ecq_huffman_build,
+    ecq_huffman_decode,
+    ecq_huffman_encode,
+    huffman_num_tiles,
     ecq_level_histogram,
     ecq_philox_words,
     ecq_quantize,

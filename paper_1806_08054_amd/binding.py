@@ -69,6 +69,10 @@ def lib() -> C.CDLL:
         L.ecq_level_histogram.argtypes = [shp, vp, vp, i64, vp]
         L.ecq_entropy_bound_bits.argtypes = [C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_double)]
         L.ecq_check_division.argtypes = [C.c_int, C.c_uint32, vp, vp]
+        L.ecq_huffman_num_tiles.argtypes = [i64, C.POINTER(i64)]
+        L.ecq_huffman_build.argtypes = [C.c_int, C.c_int, vp, i64, vp, vp, vp]
+        L.ecq_huffman_encode.argtypes = [shp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
+        L.ecq_huffman_decode.argtypes = [shp, vp, i64, vp, i64, vp, vp, i64, vp, vp]
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -78,7 +82,8 @@ def lib() -> C.CDLL:
         for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
                      "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
                      "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits", "ecq_check_division",
-                     "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy",
+                     "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy", "ecq_huffman_num_tiles",
+                     "ecq_huffman_build", "ecq_huffman_encode", "ecq_huffman_decode",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -168,6 +173,34 @@ def ecq_entropy_bound_bits(counts_host) -> float:
     bits = C.c_double(0.0)
     _check(lib().ecq_entropy_bound_bits(arr, len(counts_host), C.byref(bits)), "ecq_entropy_bound_bits")
     return bits.value
+
+
+HUFFMAN_TILE = 1024     # ECQ_HUFFMAN_TILE
+
+
+def huffman_num_tiles(n: int) -> int:
+    out = C.c_int64(0)
+    _check(lib().ecq_huffman_num_tiles(n, C.byref(out)), "ecq_huffman_num_tiles")
+    return out.value
+
+
+def ecq_huffman_build(workers: int, s: int, counts, table_stride: int, lengths, codewords, stream=None) -> None:
+    _check(lib().ecq_huffman_build(workers, s, _ptr(counts), table_stride, _ptr(lengths), _ptr(codewords),
+                                   _stream(stream)), "ecq_huffman_build")
+
+
+def ecq_huffman_encode(shape: Shape, codes, lengths, codewords, table_stride: int, streams, stream_stride: int,
+                       tile_offsets, offset_stride: int, stream=None) -> None:
+    _check(lib().ecq_huffman_encode(C.byref(shape), _ptr(codes), _ptr(lengths), _ptr(codewords), table_stride,
+                                    _ptr(streams), stream_stride, _ptr(tile_offsets), offset_stride,
+                                    _stream(stream)), "ecq_huffman_encode")
+
+
+def ecq_huffman_decode(shape: Shape, streams, stream_stride: int, tile_offsets, offset_stride: int, lengths,
+                       codewords, table_stride: int, codes, stream=None) -> None:
+    _check(lib().ecq_huffman_decode(C.byref(shape), _ptr(streams), stream_stride, _ptr(tile_offsets),
+                                    offset_stride, _ptr(lengths), _ptr(codewords), table_stride, _ptr(codes),
+                                    _stream(stream)), "ecq_huffman_decode")
 
 
 def ecq_check_division(per_divisor: int, salt: int, mismatches, stream=None) -> None:

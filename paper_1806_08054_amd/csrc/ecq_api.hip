@@ -266,6 +266,84 @@ int ecq_entropy_bound_bits(const uint64_t *counts_host, int bins, double *bits)
     return ECQ_OK;
 }
 
+int ecq_huffman_num_tiles(int64_t n, int64_t *tiles)
+{
+    if (!tiles) return ECQ_ERR_NULL;
+    if (n < 0 || n > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    *tiles = (n + ECQ_HUFFMAN_TILE - 1) / ECQ_HUFFMAN_TILE;
+    return ECQ_OK;
+}
+
+int ecq_huffman_build(int workers, int s, const uint64_t *counts, int64_t table_stride, uint8_t *lengths,
+                      uint64_t *codewords, void *stream)
+{
+    if (workers <= 0 || workers > 65535) return ECQ_ERR_SHAPE;
+    if (s < 1 || s > 127) return ECQ_ERR_LEVELS;
+    if (!counts || !lengths || !codewords) return ECQ_ERR_NULL;
+    if (table_stride < 2 * (int64_t)s + 1) return ECQ_ERR_STRIDE;
+    if (!ecq::aligned(counts, 8) || !ecq::aligned(codewords, 8)) return ECQ_ERR_ALIGN;
+    return ecq::launch_huffman_build(workers, 2 * s + 1, reinterpret_cast<const unsigned long long *>(counts),
+                                     table_stride, lengths, reinterpret_cast<unsigned long long *>(codewords),
+                                     static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+namespace ecq {
+// Checks shared by the two Huffman stream entry points.
+static int check_huffman(const ecq_shape *sh, const void *codes, const void *lengths, const void *codewords,
+                         int64_t table_stride, const void *streams, int64_t stream_stride,
+                         const void *tile_offsets, int64_t offset_stride)
+{
+    const int st = check_shape(sh);
+    if (st != ECQ_OK) return st;
+    if (!codes || !lengths || !codewords || !streams || !tile_offsets) return ECQ_ERR_NULL;
+    const int r = code_bits(sh->s);
+    const int64_t row_bytes = (sh->n * r + 7) / 8;
+    const int64_t tiles = (sh->n + ECQ_HUFFMAN_TILE - 1) / ECQ_HUFFMAN_TILE;
+    if (table_stride < 2 * (int64_t)sh->s + 1) return ECQ_ERR_STRIDE;
+    if ((stream_stride & 3) != 0 || stream_stride < (row_bytes + 3) / 4 * 4) return ECQ_ERR_STRIDE;
+    if (offset_stride < tiles + 1) return ECQ_ERR_STRIDE;
+    if (!aligned(codes, 4) || !aligned(streams, 4) || !aligned(tile_offsets, 8) || !aligned(codewords, 8))
+        return ECQ_ERR_ALIGN;
+    return ECQ_OK;
+}
+}  // namespace ecq
+
+int ecq_huffman_encode(const ecq_shape *shape, const uint8_t *codes, const uint8_t *lengths,
+                       const uint64_t *codewords, int64_t table_stride, uint8_t *streams, int64_t stream_stride,
+                       uint64_t *tile_offsets, int64_t offset_stride, void *stream)
+{
+    const int st = ecq::check_huffman(shape, codes, lengths, codewords, table_stride, streams, stream_stride,
+                                      tile_offsets, offset_stride);
+    if (st != ECQ_OK) return st;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    return ecq::launch_huffman_encode(a, lengths, reinterpret_cast<const unsigned long long *>(codewords),
+                                      table_stride, reinterpret_cast<uint32_t *>(streams), stream_stride / 4,
+                                      reinterpret_cast<unsigned long long *>(tile_offsets), offset_stride,
+                                      static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_huffman_decode(const ecq_shape *shape, const uint8_t *streams, int64_t stream_stride,
+                       const uint64_t *tile_offsets, int64_t offset_stride, const uint8_t *lengths,
+                       const uint64_t *codewords, int64_t table_stride, uint8_t *codes, void *stream)
+{
+    const int st = ecq::check_huffman(shape, codes, lengths, codewords, table_stride, streams, stream_stride,
+                                      tile_offsets, offset_stride);
+    if (st != ECQ_OK) return st;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = codes;
+    return ecq::launch_huffman_decode(a, lengths, reinterpret_cast<const unsigned long long *>(codewords),
+                                      table_stride, reinterpret_cast<const uint32_t *>(streams), stream_stride / 4,
+                                      reinterpret_cast<const unsigned long long *>(tile_offsets), offset_stride,
+                                      static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
 int ecq_check_division(int per_divisor, uint32_t salt, uint64_t *mismatches, void *stream)
 {
     if (!mismatches) return ECQ_ERR_NULL;

@@ -51,6 +51,15 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream);
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream);
 hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int64_t count_stride,
                                   hipStream_t stream);
+hipError_t launch_huffman_build(int workers, int bins, const unsigned long long *counts, int64_t table_stride,
+                                uint8_t *lengths, unsigned long long *codewords, hipStream_t stream);
+// a.codes = the fixed-length message (read by encode, written by decode).
+hipError_t launch_huffman_encode(const Args &a, const uint8_t *lengths, const unsigned long long *codewords,
+                                 int64_t table_stride, uint32_t *streams, int64_t stream_stride_words,
+                                 unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream);
+hipError_t launch_huffman_decode(const Args &a, const uint8_t *lengths, const unsigned long long *codewords,
+                                 int64_t table_stride, const uint32_t *streams, int64_t stream_stride_words,
+                                 const unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream);
 hipError_t launch_check_division(int per_divisor, uint32_t salt, unsigned long long *mismatches,
                                  hipStream_t stream);
 hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, uint32_t step_hi,

@@ -91,6 +91,17 @@ def test_entry_points_reject_bad_arguments_before_any_launch(E):
     assert lib.ecq_quantize_update(C.byref(l2_odd), fake, fake, 1.0, 1.0, 1, 0, fake, fake, None) == -4
     l2_big = E.Shape.packed(1 << 20, 1, 65536, 1, norm=1)
     assert lib.ecq_quantize_update(C.byref(l2_big), fake, fake, 1.0, 1.0, 1, 0, fake, fake, None) == -4
+    assert lib.ecq_huffman_build(2, 1, None, 3, None, None, None) == -1
+    assert lib.ecq_huffman_build(2, 1, fake, 2, fake, fake, None) == -5
+    assert lib.ecq_huffman_build(0, 1, fake, 3, fake, fake, None) == -2
+    assert lib.ecq_huffman_build(2, 200, fake, 3, fake, fake, None) == -3
+    assert lib.ecq_huffman_encode(C.byref(sh), fake, fake, fake, 3, fake, 1024, fake, 4, None) == -5   # 4 tiles + 1
+    assert lib.ecq_huffman_encode(C.byref(sh), fake, fake, fake, 3, fake, 1020, fake, 5, None) == -5
+    assert lib.ecq_huffman_encode(C.byref(sh), fake, fake, fake, 2, fake, 1024, fake, 5, None) == -5
+    assert lib.ecq_huffman_encode(C.byref(sh), fake, fake, fake, 3, None, 1024, fake, 5, None) == -1
+    assert lib.ecq_huffman_decode(C.byref(sh), fake, 1024, C.c_void_p(0x1004), 5, fake, fake, 3, fake, None) == -6
+    tiles = C.c_int64(0)
+    assert lib.ecq_huffman_num_tiles(4097, C.byref(tiles)) == 0 and tiles.value == 5
     tu = E.Tuning(1, 3, 0, 0)
     assert lib.ecq_quantize_update_ex(C.byref(sh), fake, fake, 1.0, 1.0, 1, 0, fake, fake, C.byref(tu), None) == -8
 

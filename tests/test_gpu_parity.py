@@ -364,6 +364,126 @@ def test_level_histogram(E, s, bucket, N, P):
         assert abs(bits - oracle.entropy_bound_bits(ref)) <= 1e-9 * max(bits, 1.0)
 
 
+# ------------------------------------------------------------------ Huffman coding ---------
+
+def _huffman_roundtrip(E, sh, P, N, s, codes_dev, q_rows, poison_stream=0xEE):
+    """Histogram -> code construction -> encode -> decode on the GPU, every product compared
+    bit for bit with the oracle run on the same levels q_rows [P][N]."""
+    bins = 2 * s + 1
+    stride = bins + 2
+    tiles = E.huffman_num_tiles(N)
+    assert tiles == (N + oracle.HUFFMAN_TILE - 1) // oracle.HUFFMAN_TILE
+    rb = E.row_bytes(N, s)
+    counts = torch.full((P, stride), 4242, dtype=torch.int64, device="cuda")
+    lengths = torch.full((P, stride), 0xEE, dtype=torch.uint8, device="cuda")
+    codewords = torch.full((P, stride), -1, dtype=torch.int64, device="cuda")
+    stream_stride = (rb + 3) // 4 * 4 + 8
+    streams = torch.full((P, stream_stride), poison_stream, dtype=torch.uint8, device="cuda")
+    offs = torch.full((P, tiles + 3), -1, dtype=torch.int64, device="cuda")
+    E.ecq_level_histogram(sh, codes_dev, counts, stride)
+    E.ecq_huffman_build(P, s, counts, stride, lengths, codewords)
+    E.ecq_huffman_encode(sh, codes_dev, lengths, codewords, stride, streams, stream_stride, offs, tiles + 3)
+    back = torch.full_like(codes_dev, 0x77)
+    E.ecq_huffman_decode(sh, streams, stream_stride, offs, tiles + 3, lengths, codewords, stride, back)
+    torch.cuda.synchronize()
+    len_np, cw_np = lengths.cpu().numpy(), codewords.cpu().numpy().view(np.uint64)
+    str_np, off_np = streams.cpu().numpy(), offs.cpu().numpy().view(np.uint64)
+    cnt_np = counts.cpu().numpy()
+    total_bits = 0
+    for p in range(P):
+        ref_counts = oracle.level_histogram(q_rows[p], s)
+        assert np.array_equal(cnt_np[p, :bins].astype(np.uint64), ref_counts)
+        ref_len = oracle.huffman_lengths(ref_counts)
+        ref_cw = oracle.huffman_codes(ref_len)
+        assert np.array_equal(len_np[p, :bins], ref_len), (p, len_np[p, :bins], ref_len)
+        assert np.array_equal(cw_np[p, :bins], ref_cw)
+        assert np.all(len_np[p, bins:] == 0xEE) and np.all(cw_np[p, bins:] == np.uint64(2**64 - 1))
+        ref_stream, ref_offs, bits = oracle.huffman_encode(q_rows[p], s, ref_len, ref_cw)
+        assert np.array_equal(off_np[p, : tiles + 1], ref_offs)
+        assert np.all(off_np[p, tiles + 1:] == np.uint64(2**64 - 1))
+        nbytes = (bits + 7) // 8
+        written = (nbytes + 3) // 4 * 4
+        assert np.array_equal(str_np[p, :nbytes], ref_stream[:nbytes]), p
+        assert np.all(str_np[p, nbytes:written] == 0)
+        assert np.all(str_np[p, written:] == poison_stream)
+        assert bits <= N * E.code_bits(s)
+        total_bits += bits
+    back_np = back.cpu().numpy()
+    orig = codes_dev.cpu().numpy()
+    assert np.array_equal(back_np[:, :rb], orig[:, :rb])
+    assert np.all(back_np[:, rb:] == 0x77)
+    return total_bits
+
+
+@pytest.mark.parametrize("s,bucket,N,P,kind", [(1, 512, 70_001, 3, "student_t"), (3, 64, 5000, 2, "normal"),
+                                               (7, 2048, 300_000, 4, "student_t"), (127, 8, 9, 2, "normal"),
+                                               (127, 512, 150_000, 2, "student_t"), (1, 512, 1_200_003, 2, "normal"),
+                                               (3, 1024, 1025, 1, "normal"), (1, 8, 1024, 1, "normal"),
+                                               (4, 512, 4_200_000, 2, "normal")])
+def test_huffman_matches_oracle(E, s, bucket, N, P, kind):
+    """Section 4's Huffman encoding of a quantised message: counts, codeword lengths,
+    canonical codewords, tile offsets and the stream itself bit-exact against the oracle;
+    decoding gives back the fixed-length message."""
+    wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind=kind,
+                        data_seed=N + s)
+    st = GpuState(E, P, N, bucket, s)
+    g_np = synth.gradients(wl, 0).numpy()
+    st.g[:, :N] = _dev(g_np)
+    h_ref = np.zeros((P, N), np.float32)
+    q, _, _ = oracle.batch_step(g_np, h_ref.copy(), bucket, s, wl.alpha, wl.beta, SEED, 0)
+    _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, 0)
+    bits = _huffman_roundtrip(E, st.sh, P, N, s, st.codes, q)
+    assert bits < P * N * E.code_bits(s)
+
+
+def test_huffman_degenerate_rows(E):
+    """A message with a single occupied level (all-zero gradient: every level 0) costs one bit
+    per element; a two-level message costs one bit per element too."""
+    P, N, s = 2, 5000, 3
+    sh = E.Shape.packed(N, P, 512, s)
+    q = np.zeros((P, N), np.int8)
+    q[1, ::3] = -2
+    codes = _dev(np.pad(oracle.pack_rows(q, s), ((0, 0), (0, sh.code_stride - E.row_bytes(N, s)))))
+    assert _huffman_roundtrip(E, sh, P, N, s, codes, q) == 2 * N
+
+
+def test_huffman_long_codewords(E):
+    """Level counts that follow the Fibonacci numbers give the deepest possible tree: with 35
+    levels the rarest codeword is 34 bits long, beyond one 32-bit stream word."""
+    s = 17
+    fib = [1, 1]
+    while len(fib) < 2 * s + 1:
+        fib.append(fib[-1] + fib[-2])
+    rng = np.random.default_rng(17)
+    levels = rng.permutation(2 * s + 1) - s
+    q = np.repeat(levels.astype(np.int8), fib)
+    rng.shuffle(q)
+    N = q.size
+    assert int(oracle.huffman_lengths(oracle.level_histogram(q, s)).max()) == 2 * s
+    sh = E.Shape.packed(N, 1, 512, s)
+    packed = oracle.pack_rows(q[None, :], s)
+    codes = _dev(np.pad(packed, ((0, 0), (0, sh.code_stride - packed.shape[1]))))
+    _huffman_roundtrip(E, sh, 1, N, s, codes, q[None, :])
+
+
+def test_huffman_decodes_an_oracle_stream(E):
+    """The decoder reads a stream it did not write: encoded by the oracle, decoded on the GPU."""
+    P, N, s = 1, 40_000, 7
+    rng = np.random.default_rng(3)
+    q = np.clip(np.round(rng.standard_normal(N) * 1.5), -s, s).astype(np.int8)
+    counts = oracle.level_histogram(q, s)
+    lengths = oracle.huffman_lengths(counts)
+    cw = oracle.huffman_codes(lengths)
+    stream, offs, bits = oracle.huffman_encode(q, s, lengths, cw)
+    sh = E.Shape.packed(N, P, 512, s)
+    tiles = E.huffman_num_tiles(N)
+    back = torch.zeros(P, sh.code_stride, dtype=torch.uint8, device="cuda")
+    E.ecq_huffman_decode(sh, _dev(stream[None, :]), stream.size, _dev(offs.view(np.int64)[None, :]), tiles + 1,
+                         _dev(lengths[None, :]), _dev(cw.view(np.int64)[None, :]), 2 * s + 1, back)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy()[0, : E.row_bytes(N, s)], oracle.pack_rows(q[None, :], s)[0])
+
+
 # ------------------------------------------------------------------ boundary errors --------
 
 def test_argument_errors_leave_outputs_untouched(E):
