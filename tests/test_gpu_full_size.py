@@ -159,3 +159,51 @@ def test_vgg16_full(E):
     iterations, sampled buckets of all 32 workers for all 5."""
     wl = synth.WORKLOADS["vgg16"]
     _run(E, wl, full_iters=2, full_rows=[0, 15, wl.P - 1], samples=64)
+
+
+@pytest.mark.parametrize("name,rows", [("resnet50", [0, 7]), ("alexnet", [5]), ("vgg16", [31])])
+def test_huffman_full_size(E, name, rows):
+    """Huffman coding (Section 4) of one iteration's messages at the benchmark's sizes: every
+    row decodes back to its fixed-length message; every row's length lies between the
+    entropy bound sum_k d_k log2(d/d_k) and that bound plus one bit per element; the rows in
+    `rows` are compared in full (counts, code, tile offsets, stream) with the oracle."""
+    wl = synth.WORKLOADS[name]
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s)
+    synth.gradients(wl, 0, device="cuda", out=st.g)
+    E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 0, st.codes, st.scales)
+    del st.g, st.h
+    P, N, s = wl.P, wl.N, wl.s
+    bins, tiles = 2 * s + 1, E.huffman_num_tiles(N)
+    counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    lengths = torch.zeros(P, bins, dtype=torch.uint8, device="cuda")
+    codewords = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    stream_stride = (st.rb + 3) // 4 * 4
+    streams = torch.full((P, stream_stride), 0xEE, dtype=torch.uint8, device="cuda")
+    offs = torch.zeros(P, tiles + 1, dtype=torch.int64, device="cuda")
+    back = torch.zeros_like(st.codes)
+    E.ecq_level_histogram(st.sh, st.codes, counts, bins)
+    E.ecq_huffman_build(P, s, counts, bins, lengths, codewords)
+    E.ecq_huffman_encode(st.sh, st.codes, lengths, codewords, bins, streams, stream_stride, offs, tiles + 1)
+    E.ecq_huffman_decode(st.sh, streams, stream_stride, offs, tiles + 1, lengths, codewords, bins, back)
+    torch.cuda.synchronize()
+    assert torch.equal(back[:, : st.rb], st.codes[:, : st.rb]), "decode(encode(message)) differs from the message"
+    cnt = counts.cpu().numpy().astype(np.uint64)
+    total = offs[:, tiles].cpu().numpy()
+    for p in range(P):
+        assert int(cnt[p].sum()) == N
+        bound = oracle.entropy_bound_bits(cnt[p])
+        assert bound - 1e-6 * N <= int(total[p]) < bound + N, (p, bound, int(total[p]))
+        assert int(total[p]) <= N * E.code_bits(s)
+    for p in rows:
+        q = oracle.unpack(st.codes[p, : st.rb].cpu().numpy(), N, s)
+        ref_counts = oracle.level_histogram(q, s)
+        assert np.array_equal(cnt[p], ref_counts)
+        ref_len = oracle.huffman_lengths(ref_counts)
+        ref_cw = oracle.huffman_codes(ref_len)
+        assert np.array_equal(lengths[p].cpu().numpy(), ref_len)
+        assert np.array_equal(codewords[p].cpu().numpy().view(np.uint64), ref_cw)
+        ref_stream, ref_offs, bits = oracle.huffman_encode(q, s, ref_len, ref_cw)
+        assert np.array_equal(offs[p].cpu().numpy().view(np.uint64), ref_offs)
+        nbytes = (bits + 7) // 8
+        assert np.array_equal(streams[p, :nbytes].cpu().numpy(), ref_stream[:nbytes]), f"stream differs, worker {p}"
+        print(f"{name}: worker {p}: {bits / N:.4f} bits per element (fixed length: {E.code_bits(s)})", flush=True)
