@@ -80,7 +80,7 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     P, N = wl.P, wl.N
-    sh = E.Shape.packed(N, P, wl.bucket, wl.s)
+    sh = E.Shape.aligned(N, P, wl.bucket, wl.s)      # rows start on 128-byte lines
     pool = [synth.gradients(wl, t, device="cuda",
                             out=torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda"))
             for t in range(max(1, args.pool))]

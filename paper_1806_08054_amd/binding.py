@@ -32,6 +32,16 @@ class Shape(C.Structure):
                    gh_stride=(n + 3) // 4 * 4, code_stride=(row_bytes(n, s) + 3) // 4 * 4,
                    scale_stride=num_buckets(n, bucket))
 
+    @classmethod
+    def aligned(cls, n: int, workers: int, bucket: int, s: int, norm: int = 0, line: int = 128) -> "Shape":
+        """Strides rounded up so that every worker row of g, h, codes and scales starts on a
+        `line`-byte boundary (128 = one cache line) when the base pointers do.  A wave's 1 KiB
+        loads then cover whole lines; on MI355X this alone is worth 4-5 % of bandwidth."""
+        up = lambda x, m: (x + m - 1) // m * m
+        return cls(n=n, workers=workers, bucket=bucket, s=s, norm=norm,
+                   gh_stride=up(n, line // 4), code_stride=up(row_bytes(n, s), line),
+                   scale_stride=up(num_buckets(n, bucket), line // 4))
+
 
 class Tuning(C.Structure):
     """Mirror of ecq_tuning."""

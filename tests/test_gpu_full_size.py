@@ -97,13 +97,14 @@ def _check_aggregate_sampled(E, st, wl, ks):
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"aggregate differs in bucket {k}"
 
 
-def _run(E, wl, full_iters, full_rows, samples=48, seed=0):
+def _run(E, wl, full_iters, full_rows, samples=48, seed=0, aligned=True):
     """Free-running GPU iterations.  For t < full_iters the rows in full_rows are compared in
     full (their oracle h runs freely beside the GPU's); every iteration, sampled buckets of all
     rows are recomputed from the inputs the GPU consumed; the aggregate is checked on sampled
-    buckets (in full when full_rows covers every worker)."""
+    buckets (in full when full_rows covers every worker).  aligned: worker rows start on
+    128-byte lines, the layout bench.py times; otherwise the tightest legal strides."""
     rng = np.random.default_rng(seed)
-    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=aligned)
     r = E.code_bits(wl.s)
     h_rows = {p: np.zeros(wl.N, np.float32) for p in full_rows} if full_iters else {}
     for t in range(wl.iters):
@@ -146,6 +147,13 @@ def test_resnet50_full(E):
     _run(E, wl, full_iters=wl.iters, full_rows=list(range(wl.P)))
 
 
+def test_resnet50_tight_rows(E):
+    """Workload 3 with the tightest legal strides (worker rows start 32 bytes into a cache
+    line): 2 iterations, every element."""
+    wl = synth.scaled(synth.WORKLOADS["resnet50"], iters=2)
+    _run(E, wl, full_iters=2, full_rows=list(range(wl.P)), aligned=False)
+
+
 def test_alexnet_full(E):
     """Workload 4: 10 free-running iterations; all 16 workers in full for the first 3,
     sampled buckets of all workers for all 10."""
@@ -168,7 +176,7 @@ def test_huffman_full_size(E, name, rows):
     entropy bound sum_k d_k log2(d/d_k) and that bound plus one bit per element; the rows in
     `rows` are compared in full (counts, code, tile offsets, stream) with the oracle."""
     wl = synth.WORKLOADS[name]
-    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=True)
     synth.gradients(wl, 0, device="cuda", out=st.g)
     E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 0, st.codes, st.scales)
     del st.g, st.h
@@ -177,7 +185,7 @@ def test_huffman_full_size(E, name, rows):
     counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
     lengths = torch.zeros(P, bins, dtype=torch.uint8, device="cuda")
     codewords = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
-    stream_stride = (st.rb + 3) // 4 * 4
+    stream_stride = st.sh.code_stride
     streams = torch.full((P, stream_stride), 0xEE, dtype=torch.uint8, device="cuda")
     offs = torch.zeros(P, tiles + 1, dtype=torch.int64, device="cuda")
     back = torch.zeros_like(st.codes)

@@ -30,9 +30,10 @@ def _dev(x):
 class GpuState:
     """Device buffers of one workload, laid out as the C ABI documents."""
 
-    def __init__(self, E, P, N, bucket, s, pad=0, norm="linf"):
+    def __init__(self, E, P, N, bucket, s, pad=0, norm="linf", aligned=False):
         self.E, self.P, self.N, self.bucket, self.s, self.norm = E, P, N, bucket, s, norm
-        sh = E.Shape.packed(N, P, bucket, s, norm={"linf": 0, "l2": 1}[norm])
+        make = E.Shape.aligned if aligned else E.Shape.packed     # 128-byte rows (as benchmarked) or tight
+        sh = make(N, P, bucket, s, norm={"linf": 0, "l2": 1}[norm])
         sh.gh_stride += 4 * pad
         sh.code_stride += 4 * pad
         sh.scale_stride += pad
