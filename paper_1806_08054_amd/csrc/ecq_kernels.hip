@@ -16,6 +16,7 @@
 namespace ecq {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------------------------
 // Per-lane work on 4 consecutive elements.
@@ -397,42 +398,37 @@ __device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ crow
     return (R == 8) ? w : (w & ((1u << (4 * (R & 7))) - 1u));
 }
 
-// Decode tables of the aggregation kernel, in LDS.
-//   r = 2: a 256-entry table maps a code byte to its four levels {-1,0,+1} as floats;
-//          acc = fma(norm, level, acc) equals acc + norm*level because that product is exact.
-//   else : a signed table sxi[c] = +-fl(|c-s|/s) gives g~ = norm * sxi[c] (Eq. 8).
+// Decode table of the aggregation kernel for r > 2, in LDS: sxi[c] = +-fl(|c-s|/s), so that
+// g~ = norm * sxi[c] (Eq. 8).  r = 2 needs no table (see agg_add).
 template <int R>
 __device__ __forceinline__ void fill_agg_table(float *table, int s)
 {
-    if constexpr (R == 2) {
-        for (int t = threadIdx.x; t < 256; t += blockDim.x) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int c = (t >> (2 * e)) & 3;
-                table[4 * t + e] = c == 0 ? -1.0f : (c == 2 ? 1.0f : 0.0f);
-            }
-        }
-    } else {
+    if constexpr (R != 2) {
         for (int c = threadIdx.x; c < 256; c += blockDim.x) {
             const int q = c - s;
             const int m = q < 0 ? -q : q;
             const float xi = (m <= s) ? (float)m / (float)s : 0.0f;
             table[c] = q < 0 ? -xi : xi;
         }
+        __syncthreads();
     }
-    __syncthreads();
 }
 
 // sum += one worker's dequantised values for a lane's 4 elements.
+//   r = 2: c ^ 1 is the two's complement of -level (level -1 -> 01, 0 -> 00, +1 -> 11), so a
+//          signed field extract gives -level, and sum = fma(-norm, -level, sum) equals
+//          sum + norm * level because that product is exact.
 template <int R>
 __device__ __forceinline__ void agg_add(const float *table, uint32_t bits, float norm, float (&sum)[4])
 {
     if constexpr (R == 2) {
-        const f4 lv = *reinterpret_cast<const f4 *>(&table[4 * (bits & 0xFFu)]);
-        sum[0] = __builtin_fmaf(norm, lv.x, sum[0]);
-        sum[1] = __builtin_fmaf(norm, lv.y, sum[1]);
-        sum[2] = __builtin_fmaf(norm, lv.z, sum[2]);
-        sum[3] = __builtin_fmaf(norm, lv.w, sum[3]);
+        const uint32_t t = bits ^ 0x55u;
+        const float nn = -norm;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int minus_level = (int)(t << (30 - 2 * e)) >> 30;
+            sum[e] = __builtin_fmaf(nn, (float)minus_level, sum[e]);
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -478,109 +474,179 @@ __device__ __forceinline__ void agg_run_guarded(const Args &a, const float *tabl
     }
 }
 
-// The 4*R code bits at bit offset `bitoff` (a multiple of 4) from `tile`, no bounds checks.
+// The codes of the 16 consecutive elements a lane owns: 2*R bytes starting at `src`, which is
+// 4-byte aligned for even R and 2-byte aligned for odd R.  No bounds checks.
 template <int R>
-__device__ __forceinline__ uint32_t load_codes4_inner(const uint8_t *__restrict__ tile, uint32_t bitoff)
-{
-    const uint32_t byte0 = bitoff >> 3;
-    if constexpr (R == 2) {
-        return tile[byte0];
-    } else if constexpr (R == 4) {
-        return *reinterpret_cast<const uint16_t *>(tile + byte0);
-    } else if constexpr (R == 8) {
-        return *reinterpret_cast<const uint32_t *>(tile + byte0);
-    } else {
-        constexpr int NB = (R + 1) / 2;
-        uint32_t w = 0;
+struct Codes16 {
+    static constexpr int kWords = (R + 1) / 2;
+    uint32_t w[kWords];
+    __device__ __forceinline__ void load(const uint8_t *__restrict__ src)
+    {
+        if constexpr ((R & 1) == 0) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) w |= (uint32_t)tile[byte0 + b] << (8 * b);
-        return (w >> (bitoff & 7u)) & ((1u << (4 * R)) - 1u);
+            for (int i = 0; i < R / 2; ++i) w[i] = reinterpret_cast<const uint32_t *>(src)[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kWords; ++i) {
+                const uint32_t lo = reinterpret_cast<const uint16_t *>(src)[2 * i];
+                const uint32_t hi = (2 * i + 1 < R) ? reinterpret_cast<const uint16_t *>(src)[2 * i + 1] : 0u;
+                w[i] = lo | (hi << 16);
+            }
+        }
+    }
+    // Code of element e (compile-time constant after unrolling).
+    __device__ __forceinline__ uint32_t code(int e) const
+    {
+        const int bit = R * e, i = bit >> 5, sh = bit & 31;
+        uint32_t c = w[i] >> sh;
+        if (sh + R > 32) c |= w[i + 1] << (32 - sh);
+        return c & ((1u << R) - 1u);
+    }
+};
+
+// Pair table of the r = 2 fast path: a nibble (two codes) -> the two levels {-1, 0, +1} as
+// floats, one copy per lane of a half-wave.  The LDS serves a 64-bit read to 32 lanes per
+// clock over 64 banks, so with entry `nib` of copy `lane & 31` at float2 index nib*32 + copy
+// the lanes served together always hit 32 different bank pairs: no conflicts whatever the
+// codes are.  (A table shared by all lanes conflicts on three cycles out of four.)
+__device__ __forceinline__ void fill_pair_table(f2 *pair, int)
+{
+    for (int i = threadIdx.x; i < 16 * 32; i += blockDim.x) {
+        const int nib = i >> 5, c0 = nib & 3, c1 = nib >> 2;
+        f2 lv;
+        lv.x = c0 == 0 ? -1.0f : (c0 == 2 ? 1.0f : 0.0f);
+        lv.y = c1 == 0 ? -1.0f : (c1 == 2 ? 1.0f : 0.0f);
+        pair[i] = lv;
+    }
+    __syncthreads();
+}
+
+// acc += one worker's dequantised values for a lane's 16 elements (Eq. 8).
+//   r = 2: levels from the pair table; acc = fma(norm, level, acc) equals acc + norm * level
+//          because that product is exact.
+//   else : g~ = norm * sxi[c], then acc + g~, as in agg_add.
+template <int R>
+__device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint32_t lane_off, const Codes16<R> &cd,
+                                          float norm, float (&acc)[16])
+{
+    if constexpr (R == 2) {
+        const uint32_t x = cd.w[0];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            // Byte offset nib*256 + (lane & 31)*8: the nibble moved to bits 8..11, OR-ed with the
+            // lane's copy offset (bits 3..7).
+            const uint32_t nib8 = 4 * j >= 8 ? (x >> (4 * j - 8)) : (x << (8 - 4 * j));
+            const uint32_t off = (nib8 & 0xF00u) | lane_off;
+            const f2 lv = *reinterpret_cast<const f2 *>(reinterpret_cast<const char *>(pair) + off);
+            acc[2 * j] = __builtin_fmaf(norm, lv.x, acc[2 * j]);
+            acc[2 * j + 1] = __builtin_fmaf(norm, lv.y, acc[2 * j + 1]);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float gt = norm * sxi[cd.code(e)];
+            acc[e] = acc[e] + gt;
+        }
     }
 }
 
-// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
-// A wave owns J runs of 256 consecutive outputs, a lane 4 consecutive outputs of each
-// (coalesced float4 stores).  When every run lies inside one bucket (bucket a multiple of 256)
-// and the tile is complete, the norms are scalar loads and four workers' codes and norms are
-// in flight together; anything else goes through agg_run_guarded.
-// bucket_shift >= 0 when the bucket is a power of two.
-template <int R, int J>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
-                                                           const int uniform_bucket, const float inv_p)
-{
-    __shared__ __attribute__((aligned(16))) float table[R == 2 ? 1024 : 256];
-    fill_agg_table<R>(table, a.s);
+constexpr int kAggRun = 1024;          // outputs per wave
+constexpr int kAggStageStride = 20;    // floats between lanes in the transposition buffer
 
-    constexpr int U = 4;
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    int64_t base = tile * (256 * J);
+// Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
+// A wave owns 1024 consecutive outputs, a lane 16 consecutive ones, so every worker costs a
+// lane one aligned load of 2*R code bytes (a wave reads 128*R contiguous bytes per worker) and
+// one norm (UNIFORM_NORM: the bucket is a multiple of 1024 and the load is scalar; else one per lane; the bucket
+// must be a multiple of 16 so a lane never straddles two).  Four workers' codes and norms are
+// in flight together.  The 16 sums of a lane are then transposed through LDS so the wave
+// stores (and, for the model update, loads) whole contiguous kilobytes as float4 per lane.
+// Ragged tiles and buckets that are not multiples of 16 go through agg_run_guarded.
+// bucket_shift >= 0 when the bucket is a power of two.
+template <int R, bool UNIFORM_NORM>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
+                                                           const int lane_bucket_ok, const float inv_p)
+{
+    // One LDS object with the pair table first: its byte offsets are then LDS addresses, and a
+    // lookup address is a single AND-OR of the shifted codes with the lane's copy offset.
+    struct Lds {
+        f2 pair[R == 2 ? 16 * 32 : 1];
+        float table[R == 2 ? 1 : 256];
+        __attribute__((aligned(16))) float stage[4][64 * kAggStageStride];
+    };
+    __shared__ __attribute__((aligned(4096))) Lds lds;
+    float *table = lds.table;
+    const f2 *pair = lds.pair;
+    fill_agg_table<R>(lds.table, a.s);
+    if constexpr (R == 2) fill_pair_table(lds.pair, 0);
+
+    constexpr int U = R == 2 ? 4 : 2;                          // workers in flight (register budget)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
     base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
            (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
     if (base >= a.n) return;                                   // wave-uniform
-    if (!uniform_bucket || base + 256 * J > a.n) {
+    if (!lane_bucket_ok || base + kAggRun > a.n) {
 #pragma unroll 1
-        for (int j = 0; j < J; ++j)
+        for (int j = 0; j < kAggRun / 256; ++j)
             if (base + j * 256 < a.n) agg_run_guarded<R>(a, table, base + j * 256, lane, bucket_shift, inv_p);
         return;
     }
 
-    // Bucket of each run (wave-uniform): that of the tile's first element, advanced by the
-    // remainder arithmetic in 32 bits.
-    const int64_t k0 = bucket_shift >= 0 ? (base >> bucket_shift) : (base / a.bucket);
-    const uint32_t rem = (uint32_t)(base - k0 * a.bucket);
-    int64_t k[J];
-    uint32_t bitoff[J];
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-        const uint32_t r = rem + 256u * j;
-        k[j] = k0 + (bucket_shift >= 0 ? (r >> bucket_shift) : (r / (uint32_t)a.bucket));
-        bitoff[j] = (uint32_t)(j * 256 + lane * 4) * R;
-    }
-
-    float acc[J][4];
-#pragma unroll
-    for (int j = 0; j < J; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[j][e] = 0.0f;
-
-    const uint8_t *__restrict__ ctile = a.codes + ((base * R) >> 3);
+    const int64_t first = base + lane * 16;
+    const int64_t k_lane = bucket_shift >= 0 ? (first >> bucket_shift) : (first / a.bucket);
+    const int64_t k_wave = bucket_shift >= 0 ? (base >> bucket_shift) : (base / a.bucket);
+    const uint8_t *__restrict__ cptr = a.codes + ((base * R) >> 3) + lane * (2 * R);
     const float *__restrict__ srow = a.scales;
+    const uint32_t lane_off = (uint32_t)(lane & 31) * 8u;
+
+    float acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+
     int p = 0;
     for (; p + U <= a.workers; p += U) {
-        uint32_t bits[U][J];
-        float norm[U][J];
+        Codes16<R> cd[U];
+        float norm[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            cd[u].load(cptr + u * a.code_stride);
+            norm[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+        }
 #pragma unroll
-            for (int j = 0; j < J; ++j) {
-                bits[u][j] = load_codes4_inner<R>(ctile + u * a.code_stride, bitoff[j]);
-                norm[u][j] = srow[u * a.scale_stride + k[j]];
-            }
-#pragma unroll
-        for (int u = 0; u < U; ++u)                           // workers in index order
-#pragma unroll
-            for (int j = 0; j < J; ++j) agg_add<R>(table, bits[u][j], norm[u][j], acc[j]);
-        ctile += U * a.code_stride;
+        for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);   // workers in index order
+        cptr += U * a.code_stride;
         srow += U * a.scale_stride;
     }
     for (; p < a.workers; ++p) {
-#pragma unroll
-        for (int j = 0; j < J; ++j) agg_add<R>(table, load_codes4_inner<R>(ctile, bitoff[j]), srow[k[j]], acc[j]);
-        ctile += a.code_stride;
+        Codes16<R> cd;
+        cd.load(cptr);
+        agg_add16<R>(table, pair, lane_off, cd, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
+        cptr += a.code_stride;
         srow += a.scale_stride;
     }
 
+    // Division by P, then lane-major (16 consecutive outputs per lane) -> float4-per-lane order.
     const float pf = (float)a.workers;
+    float *__restrict__ mine = lds.stage[wave];
 #pragma unroll
-    for (int j = 0; j < J; ++j) {
+    for (int q = 0; q < 4; ++q) {
         f4 o;
         if (inv_p > 0.0f) {
-            o.x = acc[j][0] * inv_p; o.y = acc[j][1] * inv_p; o.z = acc[j][2] * inv_p; o.w = acc[j][3] * inv_p;
+            o.x = acc[4 * q] * inv_p; o.y = acc[4 * q + 1] * inv_p; o.z = acc[4 * q + 2] * inv_p; o.w = acc[4 * q + 3] * inv_p;
         } else {
-            o.x = acc[j][0] / pf; o.y = acc[j][1] / pf; o.z = acc[j][2] / pf; o.w = acc[j][3] / pf;
+            o.x = acc[4 * q] / pf; o.y = acc[4 * q + 1] / pf; o.z = acc[4 * q + 2] / pf; o.w = acc[4 * q + 3] / pf;
         }
-        const int64_t at = base + j * 256 + lane * 4;
+        *reinterpret_cast<f4 *>(&mine[lane * kAggStageStride + 4 * q]) = o;
+    }
+    // Only this wave touches its buffer, and a wave's LDS operations complete in order.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int f = q * 64 + lane;                           // float4 index inside the run
+        const f4 o = *reinterpret_cast<const f4 *>(&mine[(f >> 2) * kAggStageStride + (f & 3) * 4]);
+        const int64_t at = base + 4 * f;
         if (a.out) __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(a.out + at));
         if (a.w) {                                             // Alg. 1: w <- w - eta * g~
             f4 wv = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a.w + at));
@@ -815,22 +881,21 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream)
 
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
 {
-    // Four runs per wave once there are enough outputs to fill the chip with such waves.
-    const int vec = a.n >= ((int64_t)1 << 22) ? 4 : 1;
-    const dim3 grid(cdiv(cdiv(a.n, 256 * vec), 4));
+    const dim3 grid(cdiv(cdiv(a.n, kAggRun), 4));
     int bucket_shift = -1;
     if ((a.bucket & (a.bucket - 1)) == 0)
         for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
-    const int uniform_bucket = (a.bucket % 256) == 0;
+    const int lane_bucket_ok = (a.bucket % 16) == 0;
+    const int uniform_norm = (a.bucket % kAggRun) == 0;
     // Dividing by a power of two and multiplying by its reciprocal round identically.
     const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
 #define CALL(RR)                                                                                              \
-    if (vec == 4)                                                                                             \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, 4>), grid, dim3(256), 0, stream, a, bucket_shift,         \
-                           uniform_bucket, inv_p);                                                            \
+    if (uniform_norm)                                                                                         \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, true>), grid, dim3(256), 0, stream, a, bucket_shift,      \
+                           lane_bucket_ok, inv_p);                                                            \
     else                                                                                                      \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, 1>), grid, dim3(256), 0, stream, a, bucket_shift,         \
-                           uniform_bucket, inv_p)
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, false>), grid, dim3(256), 0, stream, a, bucket_shift,     \
+                           lane_bucket_ok, inv_p)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
