@@ -271,6 +271,17 @@ def test_teacher_forced_and_alpha_zero(E):
         _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, t)
 
 
+@pytest.mark.parametrize("P,s,bucket", [(1, 1, 512), (9, 1, 512), (33, 1, 1024), (7, 3, 2048), (12, 7, 512),
+                                        (33, 127, 1024), (6, 1, 16), (10, 5, 48)])
+def test_aggregate_worker_counts(E, P, s, bucket):
+    """Eq. (4) with worker counts around the kernel's unrolling (also not powers of two, so the
+    final division is a true division), per-lane and per-wave norms, several full runs of 1024
+    outputs plus a ragged tail."""
+    wl = synth.Workload("edge", P=P, N=5 * 1024 + 8 * 13 + 5, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=2,
+                        kind="student_t", data_seed=P * 1000 + s)
+    _free_run(E, wl, 2)
+
+
 # ------------------------------------------------------------------ model update -----------
 
 @pytest.mark.parametrize("s,bucket,N,P", [(1, 512, 5000, 4), (4, 1024, 3 * 1024 + 77, 3), (3, 24, 1000, 5),
