@@ -257,4 +257,52 @@ __device__ __forceinline__ uint64_t load_code_group(const uint8_t *__restrict__ 
     return bits;
 }
 
+// The codes of the 16 consecutive elements a lane owns: 2*R bytes starting at `src`, which is
+// 4-byte aligned for even R and 2-byte aligned for odd R.  No bounds checks.
+template <int R>
+struct Codes16 {
+    static constexpr int kWords = (R + 1) / 2;
+    uint32_t w[kWords];
+    __device__ __forceinline__ void load(const uint8_t *__restrict__ src)
+    {
+        if constexpr ((R & 1) == 0) {
+#pragma unroll
+            for (int i = 0; i < R / 2; ++i) w[i] = reinterpret_cast<const uint32_t *>(src)[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kWords; ++i) {
+                const uint32_t lo = reinterpret_cast<const uint16_t *>(src)[2 * i];
+                const uint32_t hi = (2 * i + 1 < R) ? reinterpret_cast<const uint16_t *>(src)[2 * i + 1] : 0u;
+                w[i] = lo | (hi << 16);
+            }
+        }
+    }
+    // The same for a lane at the ragged end of a row: bytes at or beyond row_bytes read as 0.
+    // `elem` = index of the lane's first element (a multiple of 16).
+    __device__ __forceinline__ void load_guarded(const uint8_t *__restrict__ crow, int64_t row_bytes, int64_t elem)
+    {
+        const uint64_t g0 = elem < 0 ? 0ull : load_code_group<R>(crow, row_bytes, elem);
+        const uint64_t g1 = load_code_group<R>(crow, row_bytes, elem + 8);
+        // 16*R bits: g0 holds the first 8*R, g1 the next 8*R.
+        uint64_t lo = g0, hi = 0;
+        if constexpr (R == 8) hi = g1;
+        else {
+            lo |= g1 << (8 * R);
+            hi = g1 >> (64 - 8 * R);
+        }
+        w[0] = (uint32_t)lo;
+        if constexpr (kWords > 1) w[1] = (uint32_t)(lo >> 32);
+        if constexpr (kWords > 2) w[2] = (uint32_t)hi;
+        if constexpr (kWords > 3) w[3] = (uint32_t)(hi >> 32);
+    }
+    // Code of element e (compile-time constant after unrolling).
+    __device__ __forceinline__ uint32_t code(int e) const
+    {
+        const int bit = R * e, i = bit >> 5, sh = bit & 31;
+        uint32_t c = w[i] >> sh;
+        if (sh + R > 32) c |= w[i + 1] << (32 - sh);
+        return c & ((1u << R) - 1u);
+    }
+};
+
 }  // namespace ecq

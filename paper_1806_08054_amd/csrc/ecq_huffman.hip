@@ -24,10 +24,24 @@ namespace ecq {
 
 constexpr int kTile = ECQ_HUFFMAN_TILE;
 constexpr int kMaxLen = 63;                                    // longest codeword handled
-// Words of LDS a wave needs to assemble one tile: 1024 codewords of up to 63 bits plus the
-// up-to-31-bit shift that aligns the buffer with the 32-bit words of the stream.
-constexpr int kTileWords = (kTile * kMaxLen + 31 + 31) / 32 + 1;
 constexpr int kFastBits = 10;                                  // decode: direct table on 10 stream bits
+constexpr int kBitsTilesPerBlock = 32;                         // pass 1: tiles per block (amortises the table)
+constexpr int kWriteTilesPerWave = 8;                          // pass 3: consecutive tiles per wave
+constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
+constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
+
+// Orders a wave's LDS writes before its later LDS reads of other lanes' data.  Only that wave
+// touches the memory in question, and a wave's LDS operations complete in order.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Words of LDS a wave needs for one tile when no codeword is longer than max_len bits:
+// 1024 codewords plus the up-to-31-bit shift that aligns the buffer with the stream's words.
+static inline int tile_buffer_words(int max_len) { return (kTile * max_len + 31 + 31) / 32 + 1; }
 
 static_assert(kTile == 1024, "a wave encodes one tile: 64 lanes x 16 elements");
 
@@ -136,43 +150,69 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
 // Encoder.
 // ---------------------------------------------------------------------------------------------
 
-// Per-row code table in LDS: length and the codeword with its bits reversed, i.e. in the
-// order in which they enter the LSB-first stream.
+// Per-row code table in LDS.  `packed[c]` = (length << 24) | the codeword with its bits
+// reversed (i.e. in the order in which they enter the LSB-first stream) when no codeword of the
+// row is longer than 24 bits -- the case for every message with fewer than about 2^17
+// elements per occupied level, and checked per row; `rev`/`len` hold the general form.
 struct EncodeTable {
     unsigned long long rev[256];
+    unsigned int packed[256];
     unsigned char len[256];
+    int all_short;
 };
 
 __device__ __forceinline__ void fill_encode_table(EncodeTable &tab, const uint8_t *__restrict__ lengths,
                                                   const unsigned long long *__restrict__ codewords, int bins)
 {
+    if (threadIdx.x == 0) tab.all_short = 1;
+    __syncthreads();
     for (int c = threadIdx.x; c < 256; c += blockDim.x) {
         int l = c < bins ? lengths[c] : 0;
         l = l > kMaxLen ? kMaxLen : l;
         unsigned long long cw = (c < bins && l) ? codewords[c] : 0ull;
         cw &= (1ull << l) - 1ull;
-        tab.rev[c] = l ? (__brevll(cw) >> (64 - l)) : 0ull;
+        const unsigned long long rev = l ? (__brevll(cw) >> (64 - l)) : 0ull;
+        tab.rev[c] = rev;
         tab.len[c] = (unsigned char)l;
+        tab.packed[c] = ((unsigned int)l << 24) | (unsigned int)(rev & 0xFFFFFFull);
+        if (l > 24) tab.all_short = 0;                         // benign race: every writer stores 0
     }
     __syncthreads();
 }
 
-// The fixed-length codes of the 16 elements a lane owns inside its tile, as two groups of 8.
+// The fixed-length codes of the 16 elements a lane owns inside its tile; returns how many exist.
 template <int R>
 __device__ __forceinline__ int load_lane_codes(const uint8_t *__restrict__ crow, int64_t row_bytes, int64_t n,
-                                               int64_t elem, uint64_t (&grp)[2])
+                                               int64_t elem, Codes16<R> &cd)
 {
-    int64_t rest = n - elem;
-    const int valid = rest < 0 ? 0 : (rest > 16 ? 16 : (int)rest);
-    grp[0] = valid > 0 ? load_code_group<R>(crow, row_bytes, elem) : 0ull;
-    grp[1] = valid > 8 ? load_code_group<R>(crow, row_bytes, elem + 8) : 0ull;
-    return valid;
+    const int64_t rest = n - elem;
+    if (rest >= 16) {
+        cd.load(crow + ((elem * R) >> 3));
+        return 16;
+    }
+#pragma unroll
+    for (int i = 0; i < Codes16<R>::kWords; ++i) cd.w[i] = 0u;
+    if (rest <= 0) return 0;
+    cd.load_guarded(crow, row_bytes, elem);
+    return (int)rest;
 }
 
+// Sum of the codeword lengths of a lane's codes.
 template <int R>
-__device__ __forceinline__ unsigned int code_at(const uint64_t (&grp)[2], int e)
+__device__ __forceinline__ unsigned int lane_bits(const EncodeTable &tab, const Codes16<R> &cd, int valid)
 {
-    return (unsigned int)((grp[e >> 3] >> (R * (e & 7))) & ((1u << R) - 1u));
+    unsigned int bits = 0;
+    if constexpr (R == 2) {
+        // Three levels: count them with bit masks; pad codes (zero bits = code 0) are removed
+        // through `valid`.
+        const uint32_t x = cd.w[0], lo = x & 0x55555555u, hi = (x >> 1) & 0x55555555u;
+        const unsigned int n1 = __popc(lo & ~hi), n2 = __popc(hi & ~lo), n3 = __popc(hi & lo);
+        bits = (valid - n1 - n2 - n3) * tab.len[0] + n1 * tab.len[1] + n2 * tab.len[2];
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bits += e < valid ? tab.len[cd.code(e)] : 0u;
+    }
+    return bits;
 }
 
 // Pass 1: number of stream bits of every tile (a wave per tile, a lane per 16 elements).
@@ -187,55 +227,67 @@ __global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const u
     const uint32_t p = blockIdx.y;
     fill_encode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (tile >= tiles) return;                                 // wave-uniform, after the only barrier
-    uint64_t grp[2];
-    const int valid = load_lane_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, a.n,
-                                         tile * kTile + lane * 16, grp);
-    unsigned int bits = 0;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) bits += e < valid ? tab.len[code_at<R>(grp, e)] : 0u;
-    for (int d = 1; d < 64; d <<= 1) bits += __shfl_xor(bits, d, 64);
-    if (lane == 0) tile_offsets[(int64_t)p * offset_stride + tile] = bits;
+    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    // A block walks kBitsTilesPerBlock consecutive tiles, four at a time.
+    const int64_t tile0 = (int64_t)blockIdx.x * kBitsTilesPerBlock + (threadIdx.x >> 6);
+#pragma unroll 2
+    for (int i = 0; i < kBitsTilesPerBlock / 4; ++i) {
+        const int64_t tile = tile0 + 4 * i;
+        if (tile >= tiles) break;                              // wave-uniform
+        Codes16<R> cd;
+        const int valid = load_lane_codes<R>(crow, a.row_bytes, a.n, tile * kTile + lane * 16, cd);
+        unsigned int bits = lane_bits<R>(tab, cd, valid);
+        for (int d = 1; d < 64; d <<= 1) bits += __shfl_xor(bits, d, 64);
+        if (lane == 0) tile_offsets[(int64_t)p * offset_stride + tile] = bits;
+    }
 }
 
-// Pass 2: exclusive prefix sum of the tile sizes of one row (one block per row), in place;
-// entry `tiles` receives the total.  Also clears the 32-bit stream word in which each tile
-// starts and the one that holds the end of the row: those are the words two tiles may share
-// and pass 3 fills them with atomic ORs.
+// Pass 2: exclusive prefix sum of the tile sizes of one row (one block per row), in place,
+// 8192 tiles at a time (8 consecutive tiles per thread, the next chunk's sizes already loading
+// while the current one is scanned); entry `tiles` receives the total.  Also clears the 32-bit
+// stream word in which each tile starts and the one that holds the end of the row: those are
+// the words two tiles may share and pass 3 fills them with atomic ORs.
 __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__restrict__ tile_offsets,
                                                       const int64_t offset_stride, const int64_t tiles,
                                                       uint32_t *__restrict__ streams, const int64_t stream_words,
                                                       const int64_t stream_stride_words)
 {
-    __shared__ unsigned long long wave_total[16];
+    constexpr int K = 8;
+    __shared__ unsigned long long wave_total[2][16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     unsigned long long *__restrict__ row = tile_offsets + (int64_t)blockIdx.x * offset_stride;
     uint32_t *__restrict__ out = streams + (int64_t)blockIdx.x * stream_stride_words;
-    unsigned long long carry = 0;
-    for (int64_t base = 0; base < tiles; base += 4096) {
-        const int64_t i0 = base + (int64_t)tid * 4;
-        unsigned long long v[4];
+    unsigned long long carry = 0, v[K], nxt[K];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = i0 + k < tiles ? row[i0 + k] : 0ull;
-        const unsigned long long mine = (v[0] + v[1]) + (v[2] + v[3]);
+    for (int k = 0; k < K; ++k) nxt[k] = (int64_t)tid * K + k < tiles ? row[(int64_t)tid * K + k] : 0ull;
+    int parity = 0;
+    for (int64_t base = 0; base < tiles; base += 1024 * K, parity ^= 1) {
+        const int64_t i0 = base + (int64_t)tid * K;
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            v[k] = nxt[k];
+            mine += v[k];
+            const int64_t ahead = i0 + 1024 * K + k;
+            nxt[k] = ahead < tiles ? row[ahead] : 0ull;
+        }
         unsigned long long incl = mine;
         for (int d = 1; d < 64; d <<= 1) {
             const unsigned long long up = __shfl_up(incl, d, 64);
             if (lane >= d) incl += up;
         }
-        if (lane == 63) wave_total[wave] = incl;
-        __syncthreads();
+        if (lane == 63) wave_total[parity][wave] = incl;
+        __syncthreads();                                       // one barrier per chunk: the totals alternate buffers
         unsigned long long before = carry, all = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
-            const unsigned long long t = wave_total[w];
+            const unsigned long long t = wave_total[parity][w];
             before += w < wave ? t : 0ull;
             all += t;
         }
         unsigned long long off = before + (incl - mine);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < K; ++k) {
             if (i0 + k < tiles) {
                 row[i0 + k] = off;
                 const unsigned long long word = off >> 5;
@@ -244,7 +296,6 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
             off += v[k];
         }
         carry += all;
-        __syncthreads();                                       // wave_total is reused by the next chunk
     }
     if (tid == 0) {
         row[tiles] = carry;
@@ -253,46 +304,60 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
     }
 }
 
-// Pass 3: a wave assembles the bits of its tile in LDS, aligned with the 32-bit words of the
+// Pass 3: a wave assembles the bits of a tile in LDS, aligned with the 32-bit words of the
 // stream, then stores the words: those that lie wholly inside the tile with plain coalesced
-// stores, the first and last (which neighbouring tiles may share) with atomic ORs.
+// stores, the first and last (which neighbouring tiles may share) with atomic ORs.  A wave
+// walks kWriteTilesPerWave consecutive tiles so that the code table is read once per 32 tiles.
+// buf_words = LDS words per wave: enough for 1024 codewords of the longest length a code over
+// 2s+1 levels can have (2s bits); longer tiles (only possible with a table that does not
+// belong to the message) are cut off.
 template <int R>
 __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8_t *__restrict__ lengths,
                                                       const unsigned long long *__restrict__ codewords,
                                                       const int64_t table_stride, const int64_t tiles,
                                                       const unsigned long long *__restrict__ tile_offsets,
                                                       const int64_t offset_stride, uint32_t *__restrict__ streams,
-                                                      const int64_t stream_words, const int64_t stream_stride_words)
+                                                      const int64_t stream_words, const int64_t stream_stride_words,
+                                                      const int buf_words)
 {
     __shared__ EncodeTable tab;
-    __shared__ unsigned int buf[4][kTileWords];
+    extern __shared__ unsigned int tile_buf[];
     const uint32_t p = blockIdx.y;
     fill_encode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
-    const bool active = tile < tiles;                          // wave-uniform
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    unsigned int *__restrict__ mine = tile_buf + wave * buf_words;
+    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    const unsigned long long *__restrict__ offs = tile_offsets + (int64_t)p * offset_stride;
+    uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
+    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kWriteTilesPerWave;
 
-    unsigned long long start = 0, end = 0;
-    if (active) {
-        start = tile_offsets[(int64_t)p * offset_stride + tile];
-        end = tile_offsets[(int64_t)p * offset_stride + tile + 1];
-        if (end < start) end = start;
-    }
-    const unsigned int shift = (unsigned int)(start & 31ull);
-    const unsigned long long word0 = start >> 5;
-    unsigned long long span = ((end - start) + shift + 31ull) >> 5;
-    const int words = (int)(span < (unsigned long long)kTileWords ? span : (unsigned long long)kTileWords);
-    unsigned int *__restrict__ mine = buf[wave];
-    for (int j = lane; j < words; j += 64) mine[j] = 0u;
-    __syncthreads();
-
-    if (active) {
-        uint64_t grp[2];
-        const int valid = load_lane_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, a.n,
-                                             tile * kTile + lane * 16, grp);
-        unsigned int nbits = 0;
+    // Everything the wave reads from memory is requested up front: the offsets of its tiles
+    // (lane i holds entry first + i) and the codes of all of them.
+    const unsigned long long my_off = (lane <= kWriteTilesPerWave && first + lane <= tiles) ? offs[first + lane] : 0ull;
+    Codes16<R> all_cd[kWriteTilesPerWave];
+    int all_valid[kWriteTilesPerWave];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) nbits += e < valid ? tab.len[code_at<R>(grp, e)] : 0u;
+    for (int i = 0; i < kWriteTilesPerWave; ++i)
+        all_valid[i] = load_lane_codes<R>(crow, a.row_bytes, a.n, (first + i) * kTile + lane * 16, all_cd[i]);
+
+#pragma unroll
+    for (int i = 0; i < kWriteTilesPerWave; ++i) {
+        const int64_t tile = first + i;
+        if (tile >= tiles) break;                              // wave-uniform
+        const unsigned long long start = __shfl(my_off, i, 64);
+        unsigned long long end = __shfl(my_off, i + 1, 64);
+        if (end < start) end = start;
+        const unsigned int shift = (unsigned int)(start & 31ull);
+        const unsigned long long word0 = start >> 5;
+        const unsigned long long span = ((end - start) + shift + 31ull) >> 5;
+        const int words = (int)(span < (unsigned long long)buf_words ? span : (unsigned long long)buf_words);
+        const Codes16<R> &cd = all_cd[i];
+        const int valid = all_valid[i];
+        for (int j = lane; j < words; j += 64) mine[j] = 0u;
+        wave_lds_sync();
+
+        const unsigned int nbits = lane_bits<R>(tab, cd, valid);
         unsigned int incl = nbits;
         for (int d = 1; d < 64; d <<= 1) {
             const unsigned int up = __shfl_up(incl, d, 64);
@@ -303,17 +368,13 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         int w = (int)(pos >> 5);
         unsigned long long acc = 0;
         unsigned int held = pos & 31u;                         // bits of acc below the next free one
-#pragma unroll 1
-        for (int e = 0; e < valid; ++e) {
-            const unsigned int c = code_at<R>(grp, e);
-            unsigned int l = tab.len[c];
-            unsigned long long bits = tab.rev[c];
-            while (l > 0) {                                    // at most two pieces of <= 32 bits
-                const unsigned int piece = l > 32u ? 32u : l;
-                acc |= (bits & ((1ull << piece) - 1ull)) << held;
-                held += piece;
-                bits >>= piece;
-                l -= piece;
+        if (tab.all_short) {
+            // Codewords of at most 24 bits: one table word per element, at most one flush each.
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const unsigned int entry = e < valid ? tab.packed[cd.code(e)] : 0u;
+                acc |= (unsigned long long)(entry & 0xFFFFFFu) << held;
+                held += entry >> 24;
                 if (held >= 32u) {
                     if (w < words) atomicOr(&mine[w], (unsigned int)acc);
                     ++w;
@@ -321,13 +382,32 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
                     held -= 32u;
                 }
             }
+        } else {
+#pragma unroll 1
+            for (int e = 0; e < valid; ++e) {
+                unsigned int c = 0;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) c = k == e ? cd.code(k) : c;
+                unsigned int l = tab.len[c];
+                unsigned long long bits = tab.rev[c];
+                while (l > 0) {                                // at most two pieces of <= 32 bits
+                    const unsigned int piece = l > 32u ? 32u : l;
+                    acc |= (bits & ((1ull << piece) - 1ull)) << held;
+                    held += piece;
+                    bits >>= piece;
+                    l -= piece;
+                    if (held >= 32u) {
+                        if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+                        ++w;
+                        acc >>= 32;
+                        held -= 32u;
+                    }
+                }
+            }
         }
         if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
-    }
-    __syncthreads();
+        wave_lds_sync();
 
-    if (active) {
-        uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
         for (int j = lane; j < words; j += 64) {
             const unsigned long long gw = word0 + (unsigned long long)j;
             if (gw >= (unsigned long long)stream_words) continue;
@@ -336,20 +416,29 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
             if (whole) out[gw] = value;
             else if (value) atomicOr(&out[gw], value);
         }
+        wave_lds_sync();                                       // the buffer is cleared again for the next tile
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Decoder: one lane per tile.
 // ---------------------------------------------------------------------------------------------
+// Decoding a tile is a chain: the position of a codeword is known only once the one before it
+// has been decoded.  To shorten the chain the main table maps the next 10 stream bits to ALL
+// the codewords that end inside them (up to 10, and as many as fit 20 bits of r-bit codes):
+//   multi[i] = packed r-bit codes | bits consumed << 20 | symbols << 24      (symbols = 0: none)
+// A codeword longer than 10 bits, and the last few symbols of a tile, take the single-symbol
+// route: `fast` (first codeword in the 10 bits) or the canonical first-code/count walk.
 struct DecodeTable {
     unsigned long long first_code[64];       // canonical: first codeword of each length
+    unsigned int multi[1 << kFastBits];
     unsigned short count[64];                // codewords of each length
     unsigned short base[64];                 // index into sorted[] of the first one
     unsigned short fast[1 << kFastBits];     // next 10 stream bits -> (length << 8) | code, 0 = longer
     unsigned char sorted[256];               // codes c in the order (length, c)
 };
 
+template <int R>
 __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_t *__restrict__ lengths,
                                                   const unsigned long long *__restrict__ codewords, int bins)
 {
@@ -378,16 +467,12 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
         const int l = lengths[c] > kMaxLen ? kMaxLen : lengths[c];
         if (!l) continue;
         int rank = 0;
-        bool lowest = true;
         for (int j = 0; j < c; ++j) {
             const int lj = lengths[j] > kMaxLen ? kMaxLen : lengths[j];
-            if (lj == l) {
-                ++rank;
-                lowest = false;
-            }
+            rank += lj == l ? 1 : 0;
         }
         const unsigned long long cw = codewords[c] & ((1ull << l) - 1ull);
-        if (lowest) tab.first_code[l] = cw;
+        if (rank == 0) tab.first_code[l] = cw;
         const int slot = tab.base[l] + rank;
         if (slot < 256) tab.sorted[slot] = (unsigned char)c;
         if (l <= kFastBits) {
@@ -397,53 +482,105 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
         }
     }
     __syncthreads();
+    // Chain single-symbol lookups inside the 10-bit window.  Bits beyond the window read as
+    // zeros, so a hit only counts when the whole codeword lies inside the window.
+    constexpr int kMaxSyms = 20 / R < 10 ? 20 / R : 10;
+    for (int i = tid; i < (1 << kFastBits); i += blockDim.x) {
+        unsigned int used = 0, syms = 0, packed = 0;
+        while (syms < (unsigned int)kMaxSyms) {
+            const unsigned int hit = tab.fast[i >> used];
+            const unsigned int l = hit >> 8;
+            if (!hit || used + l > (unsigned int)kFastBits) break;
+            packed |= (hit & ((1u << R) - 1u)) << (R * syms);
+            ++syms;
+            used += l;
+        }
+        tab.multi[i] = syms ? (packed | (used << 20) | (syms << 24)) : 0u;
+    }
+    __syncthreads();
 }
 
 template <int R>
-__global__ void __launch_bounds__(64) k_huffman_decode(const Args a, const uint8_t *__restrict__ lengths,
-                                                      const unsigned long long *__restrict__ codewords,
-                                                      const int64_t table_stride, const int64_t tiles,
-                                                      const unsigned long long *__restrict__ tile_offsets,
-                                                      const int64_t offset_stride,
-                                                      const uint32_t *__restrict__ streams,
-                                                      const int64_t stream_words, const int64_t stream_stride_words)
+__global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint8_t *__restrict__ lengths,
+                                                       const unsigned long long *__restrict__ codewords,
+                                                       const int64_t table_stride, const int64_t tiles,
+                                                       const unsigned long long *__restrict__ tile_offsets,
+                                                       const int64_t offset_stride,
+                                                       const uint32_t *__restrict__ streams,
+                                                       const int64_t stream_words, const int64_t stream_stride_words)
 {
     __shared__ DecodeTable tab;
+    __shared__ __attribute__((aligned(16))) unsigned int out_ring[256 * kRingStride];
     const uint32_t p = blockIdx.y;
-    fill_decode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
+    fill_decode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride,
+                         2 * a.s + 1);
     const int64_t tile = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tile >= tiles) return;
+    if (tile >= tiles) return;                                 // after the last barrier
     const int64_t elem0 = tile * kTile;
-    const int count = (int)((a.n - elem0) < kTile ? (a.n - elem0) : (int64_t)kTile);
+    int remaining = (int)((a.n - elem0) < kTile ? (a.n - elem0) : (int64_t)kTile);
     const uint32_t *__restrict__ in = streams + (int64_t)p * stream_stride_words;
     uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    int64_t out_byte = (elem0 >> 3) * R;                       // a multiple of 128*R: 4-byte aligned in the row
 
     const unsigned long long start = tile_offsets[(int64_t)p * offset_stride + tile];
     unsigned long long next_word = start >> 5;
-    // Bit reservoir: `have` valid bits, the next stream bit is bit 0.
-    unsigned long long res = 0;
-    unsigned int have = 0;
+    // Bit reservoir: `have` valid bits, the next stream bit is bit 0.  One word is always
+    // loaded ahead of its use.
+    auto fetch = [&]() -> unsigned int {
+        const unsigned int wv = next_word < (unsigned long long)stream_words ? in[next_word] : 0u;
+        ++next_word;
+        return wv;
+    };
+    unsigned long long res = fetch();
+    unsigned int have = 32u;
+    unsigned int ahead = fetch();
     auto refill = [&]() {
-        while (have <= 32u) {
-            const unsigned int wv = next_word < (unsigned long long)stream_words ? in[next_word] : 0u;
-            ++next_word;
-            res |= (unsigned long long)wv << have;
+        if (have <= 32u) {
+            res |= (unsigned long long)ahead << have;
             have += 32u;
+            ahead = fetch();
         }
     };
-    refill();
     {
         const unsigned int skip = (unsigned int)(start & 31ull);
         res >>= skip;
         have -= skip;
     }
+    refill();
 
-    for (int e0 = 0; e0 < count; e0 += 8) {
-        uint64_t group = 0;
-        const int in_group = count - e0 < 8 ? count - e0 : 8;
-        for (int e = 0; e < in_group; ++e) {
-            refill();
-            unsigned int c;
+    // Decoded codes are collected in a per-lane LDS ring and leave in 64-byte pieces: global
+    // stores inside the chain would make every later wait for a stream word also wait for them.
+    unsigned long long out_acc = 0;                            // decoded r-bit codes not yet in the ring
+    unsigned int out_held = 0;
+    unsigned int *__restrict__ ring = out_ring + threadIdx.x * kRingStride;
+    int ring_at = 0;
+    auto flush_ring = [&](int count) {
+        if (count == kRingWords && out_byte + 4 * kRingWords <= a.row_bytes) {
+#pragma unroll
+            for (int q = 0; q < kRingWords / 4; ++q) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(&ring[4 * q]);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(crow + out_byte) + 4 * q;
+                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+            }
+        } else {
+            for (int k = 0; k < count; ++k)
+                store_code_bytes(crow + out_byte + 4 * k, ring[k], 4, a.row_bytes - (out_byte + 4 * k));
+        }
+        out_byte += 4 * count;
+    };
+    while (remaining > 0) {
+        refill();                                              // have >= 33 from here
+        const unsigned int m = tab.multi[(unsigned int)res & ((1u << kFastBits) - 1u)];
+        const unsigned int syms = m >> 24;
+        if (syms != 0u && (int)syms <= remaining) {
+            const unsigned int used = (m >> 20) & 15u;
+            out_acc |= (unsigned long long)(m & 0xFFFFFu) << out_held;
+            out_held += syms * R;
+            res >>= used;
+            have -= used;
+            remaining -= (int)syms;
+        } else {
+            unsigned int c = 0;
             const unsigned int hit = tab.fast[(unsigned int)res & ((1u << kFastBits) - 1u)];
             if (hit) {
                 c = hit & 0xFFu;
@@ -452,7 +589,6 @@ __global__ void __launch_bounds__(64) k_huffman_decode(const Args a, const uint8
             } else {
                 // Longer than the table covers: walk the canonical code one bit at a time.
                 unsigned long long word = 0;
-                c = 0;
                 for (int l = 1; l <= kMaxLen; ++l) {
                     if (have == 0u) refill();
                     word = (word << 1) | (res & 1ull);
@@ -465,11 +601,24 @@ __global__ void __launch_bounds__(64) k_huffman_decode(const Args a, const uint8
                     }
                 }
             }
-            group |= (uint64_t)(c & ((1u << R) - 1u)) << (R * e);
+            out_acc |= (unsigned long long)(c & ((1u << R) - 1u)) << out_held;
+            out_held += R;
+            --remaining;
         }
-        const int64_t byte_off = ((elem0 + e0) >> 3) * R;
-        store_code_bytes(crow + byte_off, group, R, a.row_bytes - byte_off);
+        if (out_held >= 32u) {
+            ring[ring_at] = (unsigned int)out_acc;
+            out_acc >>= 32;
+            out_held -= 32u;
+            if (++ring_at == kRingWords) {                      // 64 bytes of codes: send them off together
+                flush_ring(kRingWords);
+                ring_at = 0;
+            }
+        }
     }
+    // What is left of a ragged last tile: whole words, then fewer than 32 bits (pad bits zero).
+    flush_ring(ring_at);
+    if (out_held > 0u && out_byte < a.row_bytes)
+        store_code_bytes(crow + out_byte, out_acc, (int)((out_held + 7u) >> 3), a.row_bytes - out_byte);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -489,17 +638,22 @@ hipError_t launch_huffman_encode(const Args &a, const uint8_t *lengths, const un
 {
     const int64_t tiles = (a.n + kTile - 1) / kTile;
     const int64_t stream_words = stream_stride_words;
-    const dim3 grid(cdiv(tiles, 4), (unsigned)a.workers);
+    const dim3 grid_bits(cdiv(tiles, kBitsTilesPerBlock), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_tile_bits<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride, \
-                       tiles, tile_offsets, offset_stride)
+    hipLaunchKernelGGL((k_huffman_tile_bits<RR>), grid_bits, dim3(256), 0, stream, a, lengths, codewords,        \
+                       table_stride, tiles, tile_offsets, offset_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     hipLaunchKernelGGL(k_huffman_scan, dim3((unsigned)a.workers), dim3(1024), 0, stream, tile_offsets, offset_stride,
                        tiles, streams, stream_words, stream_stride_words);
+    // A prefix code over 2s+1 levels has no codeword longer than 2s bits.
+    const int max_len = 2 * a.s < kMaxLen ? 2 * a.s : kMaxLen;
+    const int buf_words = tile_buffer_words(max_len);
+    const dim3 grid_write(cdiv(tiles, 4 * kWriteTilesPerWave), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_write<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride,   \
-                       tiles, tile_offsets, offset_stride, streams, stream_words, stream_stride_words)
+    hipLaunchKernelGGL((k_huffman_write<RR>), grid_write, dim3(256), 4 * buf_words * sizeof(unsigned int),       \
+                       stream, a, lengths, codewords, table_stride, tiles, tile_offsets, offset_stride, streams, \
+                       stream_words, stream_stride_words, buf_words)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
@@ -510,9 +664,9 @@ hipError_t launch_huffman_decode(const Args &a, const uint8_t *lengths, const un
                                  const unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kTile - 1) / kTile;
-    const dim3 grid(cdiv(tiles, 64), (unsigned)a.workers);
+    const dim3 grid(cdiv(tiles, 256), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_decode<RR>), grid, dim3(64), 0, stream, a, lengths, codewords, table_stride,   \
+    hipLaunchKernelGGL((k_huffman_decode<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride,   \
                        tiles, tile_offsets, offset_stride, streams, stream_stride_words, stream_stride_words)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL

@@ -474,36 +474,6 @@ __device__ __forceinline__ void agg_run_guarded(const Args &a, const float *tabl
     }
 }
 
-// The codes of the 16 consecutive elements a lane owns: 2*R bytes starting at `src`, which is
-// 4-byte aligned for even R and 2-byte aligned for odd R.  No bounds checks.
-template <int R>
-struct Codes16 {
-    static constexpr int kWords = (R + 1) / 2;
-    uint32_t w[kWords];
-    __device__ __forceinline__ void load(const uint8_t *__restrict__ src)
-    {
-        if constexpr ((R & 1) == 0) {
-#pragma unroll
-            for (int i = 0; i < R / 2; ++i) w[i] = reinterpret_cast<const uint32_t *>(src)[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < kWords; ++i) {
-                const uint32_t lo = reinterpret_cast<const uint16_t *>(src)[2 * i];
-                const uint32_t hi = (2 * i + 1 < R) ? reinterpret_cast<const uint16_t *>(src)[2 * i + 1] : 0u;
-                w[i] = lo | (hi << 16);
-            }
-        }
-    }
-    // Code of element e (compile-time constant after unrolling).
-    __device__ __forceinline__ uint32_t code(int e) const
-    {
-        const int bit = R * e, i = bit >> 5, sh = bit & 31;
-        uint32_t c = w[i] >> sh;
-        if (sh + R > 32) c |= w[i + 1] << (32 - sh);
-        return c & ((1u << R) - 1u);
-    }
-};
-
 // Pair table of the r = 2 fast path: a nibble (two codes) -> the two levels {-1, 0, +1} as
 // floats, one copy per lane of a half-wave.  The LDS serves a 64-bit read to 32 lanes per
 // clock over 64 banks, so with entry `nib` of copy `lane & 31` at float2 index nib*32 + copy
@@ -665,53 +635,111 @@ __global__ void __launch_bounds__(256) k_zero_counts(unsigned long long *counts,
     if ((int)threadIdx.x < bins) counts[(int64_t)blockIdx.x * count_stride + threadIdx.x] = 0ull;
 }
 
-// A lane owns runs of 8 elements (R whole bytes); a block walks kHistPerBlock elements of one
-// row, counts into LDS and adds its totals to the row's counters once.  For r = 2 (three
-// levels) counting is done with wave ballots instead of LDS atomics, which would all hit the
-// same three addresses.
-constexpr int kHistPerBlock = 256 * 8 * 16;
+// A lane owns runs of 16 elements (2*R bytes, one aligned load); a block walks kHistPerBlock
+// elements of one row, counts into LDS and adds its totals to the row's counters once.
+//   r = 2: the three levels are counted with bit masks and population counts, 16 codes at a
+//          time, in registers.
+//   else : level 0 (code s), by far the most frequent, is counted in a register; the other
+//          codes go to LDS counters: one private set per thread while there are at most 16
+//          levels (no two lanes ever meet on an address), else one histogram per wave with
+//          atomic adds.
+constexpr int kHistIters = 2;
+constexpr int kHistGroups = 4;                                 // runs of 16 elements a lane loads together
+constexpr int kHistPerBlock = 256 * 16 * kHistGroups * kHistIters;
 
 template <int R>
 __global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned long long *__restrict__ counts,
                                                         const int64_t count_stride)
 {
-    __shared__ unsigned int hist[256];
-    for (int c = threadIdx.x; c < 256; c += blockDim.x) hist[c] = 0u;
+    constexpr bool kPrivate = R > 2 && R <= 4;                 // at most 16 levels
+    constexpr int kPrivStride = 17;                            // odd: spreads the threads' sets over the banks
+    __shared__ unsigned int hist[4][256];
+    __shared__ unsigned int priv[kPrivate ? 256 * kPrivStride : 1];
+    for (int c = threadIdx.x; c < 4 * 256; c += blockDim.x) (&hist[0][0])[c] = 0u;
+    if constexpr (kPrivate)
+        for (int c = 0; c < kPrivStride; ++c) priv[threadIdx.x * kPrivStride + c] = 0u;
     __syncthreads();
     const uint32_t p = blockIdx.y;
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    const int64_t begin = (int64_t)blockIdx.x * kHistPerBlock;
-    const int lane = threadIdx.x & 63;
-    unsigned int c0 = 0, c1 = 0, c2 = 0;                       // r = 2: per-wave totals (lane 0 keeps them)
-    for (int it = 0; it < 16; ++it) {
-        const int64_t elem = begin + ((int64_t)it * 256 + threadIdx.x) * 8;
-        const uint64_t bits = elem < a.n ? load_code_group<R>(crow, a.row_bytes, elem) : 0ull;
-        int64_t rest = a.n - elem;
-        const int valid = rest < 0 ? 0 : (rest > 8 ? 8 : (int)rest);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned int *__restrict__ my_priv = priv + (kPrivate ? threadIdx.x * kPrivStride : 0);
+    unsigned int n_center = 0, n1 = 0, n2 = 0, n3 = 0, n_valid = 0;
+    // The blocks of a row take its chunks of kHistPerBlock elements round robin: few blocks per
+    // row, because their totals meet in the same handful of global counters.
+    for (int64_t begin = (int64_t)blockIdx.x * kHistPerBlock; begin < a.n; begin += (int64_t)gridDim.x * kHistPerBlock)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const unsigned int c = (unsigned int)((bits >> (R * e)) & ((1u << R) - 1u));
-            const bool on = e < valid;
-            if constexpr (R == 2) {
-                c0 += __popcll(__ballot(on && c == 0u));
-                c1 += __popcll(__ballot(on && c == 1u));
-                c2 += __popcll(__ballot(on && c == 2u));
+    for (int it = 0; it < kHistIters; ++it) {
+        // A lane's four runs are contiguous: 8*R bytes per lane, 512*R per wave.
+        const int64_t elem0 = begin + ((int64_t)it * 256 + threadIdx.x) * (16 * kHistGroups);
+        Codes16<R> cd[kHistGroups];
+        int valid[kHistGroups];
+#pragma unroll
+        for (int k = 0; k < kHistGroups; ++k) {
+            const int64_t elem = elem0 + 16 * k;
+            if (elem + 16 <= a.n) {
+                cd[k].load(crow + ((elem * R) >> 3));
+                valid[k] = 16;
+            } else if (elem < a.n) {
+                cd[k].load_guarded(crow, a.row_bytes, elem);
+                valid[k] = (int)(a.n - elem);
             } else {
-                if (on) atomicAdd(&hist[c], 1u);
+#pragma unroll
+                for (int i = 0; i < Codes16<R>::kWords; ++i) cd[k].w[i] = 0u;
+                valid[k] = 0;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kHistGroups; ++k) {
+            if constexpr (R == 2) {
+                // Pad codes are zero bits (code 0) and are removed through n_valid.
+                const uint32_t x = cd[k].w[0], lo = x & 0x55555555u, hi = (x >> 1) & 0x55555555u;
+                n1 += __popc(lo & ~hi);
+                n2 += __popc(hi & ~lo);
+                n3 += __popc(hi & lo);
+                n_valid += valid[k];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const unsigned int c = cd[k].code(e);
+                    if (e < valid[k]) {
+                        if (c == (unsigned int)a.s) ++n_center;
+                        else if constexpr (kPrivate) my_priv[c] += 1u;
+                        else atomicAdd(&hist[wave][c], 1u);
+                    }
+                }
             }
         }
     }
     if constexpr (R == 2) {
+        for (int d = 1; d < 64; d <<= 1) {
+            n1 += __shfl_xor(n1, d, 64);
+            n2 += __shfl_xor(n2, d, 64);
+            n3 += __shfl_xor(n3, d, 64);
+            n_valid += __shfl_xor(n_valid, d, 64);
+        }
         if (lane == 0) {
-            atomicAdd(&hist[0], c0);
-            atomicAdd(&hist[1], c1);
-            atomicAdd(&hist[2], c2);
+            hist[wave][0] = n_valid - n1 - n2 - n3;
+            hist[wave][1] = n1;
+            hist[wave][2] = n2;
+        }
+    } else {
+        for (int d = 1; d < 64; d <<= 1) n_center += __shfl_xor(n_center, d, 64);
+        if (lane == 0 && n_center) atomicAdd(&hist[wave][a.s], n_center);
+        if constexpr (kPrivate) {
+            __syncthreads();
+            // Thread (c, part) adds up level c over a sixteenth of the block's private sets.
+            const int c = threadIdx.x & 15, part = threadIdx.x >> 4;
+            unsigned int sum = 0;
+            for (int t = part * 16; t < part * 16 + 16; ++t) sum += priv[t * kPrivStride + c];
+            if (sum) atomicAdd(&hist[0][c], sum);
         }
     }
     __syncthreads();
     const int bins = 2 * a.s + 1;
-    for (int c = threadIdx.x; c < bins; c += blockDim.x)
-        if (hist[c]) atomicAdd(&counts[(int64_t)p * count_stride + c], (unsigned long long)hist[c]);
+    for (int c = threadIdx.x; c < bins; c += blockDim.x) {
+        const unsigned int total = (hist[0][c] + hist[1][c]) + (hist[2][c] + hist[3][c]);
+        if (total) atomicAdd(&counts[(int64_t)p * count_stride + c], (unsigned long long)total);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -905,7 +933,11 @@ hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int
                                   hipStream_t stream)
 {
     hipLaunchKernelGGL(k_zero_counts, dim3((unsigned)a.workers), dim3(256), 0, stream, counts, count_stride, 2 * a.s + 1);
-    const dim3 grid(cdiv(a.n, kHistPerBlock), (unsigned)a.workers);
+    // Enough blocks to fill the chip a few times over all rows, at most 256 per row.
+    unsigned per_row = cdiv(a.n, kHistPerBlock);
+    const unsigned want = cdiv(4096, a.workers);
+    if (per_row > want) per_row = want > 256 ? 256 : want;
+    const dim3 grid(per_row, (unsigned)a.workers);
 #define CALL(RR) hipLaunchKernelGGL((k_level_histogram<RR>), grid, dim3(256), 0, stream, a, counts, count_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
