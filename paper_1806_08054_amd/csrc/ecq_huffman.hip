@@ -150,21 +150,33 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
 // Encoder.
 // ---------------------------------------------------------------------------------------------
 
-// Per-row code table in LDS.  `packed[c]` = (length << 24) | the codeword with its bits
-// reversed (i.e. in the order in which they enter the LSB-first stream) when no codeword of the
-// row is longer than 24 bits -- the case for every message with fewer than about 2^17
-// elements per occupied level, and checked per row; `rev`/`len` hold the general form.
+// Per-row code table in LDS.
+//   rev/len   every level: codeword with its bits reversed (the order in which they enter the
+//             LSB-first stream) and its length;
+//   packed    (length << 24) | reversed codeword, valid when no codeword of the row is longer
+//             than 24 bits (all_short) -- true unless some level is rarer than about 1 in 2^24;
+//   group     the same for GROUPS of group_k consecutive elements, indexed by their group_k*R
+//             code bits: total length << 24 | the codewords back to back.  group_k is the
+//             largest of 4, 2, 1 with at most 8 index bits and at most 24 stream bits per group,
+//             so short codes (the common case) cost a quarter of the table lookups.
 struct EncodeTable {
     unsigned long long rev[256];
     unsigned int packed[256];
+    unsigned int group[256];
     unsigned char len[256];
     int all_short;
+    int group_k;
+    unsigned int max_len;
 };
 
+template <int R>
 __device__ __forceinline__ void fill_encode_table(EncodeTable &tab, const uint8_t *__restrict__ lengths,
                                                   const unsigned long long *__restrict__ codewords, int bins)
 {
-    if (threadIdx.x == 0) tab.all_short = 1;
+    if (threadIdx.x == 0) {
+        tab.all_short = 1;
+        tab.max_len = 0u;
+    }
     __syncthreads();
     for (int c = threadIdx.x; c < 256; c += blockDim.x) {
         int l = c < bins ? lengths[c] : 0;
@@ -176,6 +188,23 @@ __device__ __forceinline__ void fill_encode_table(EncodeTable &tab, const uint8_
         tab.len[c] = (unsigned char)l;
         tab.packed[c] = ((unsigned int)l << 24) | (unsigned int)(rev & 0xFFFFFFull);
         if (l > 24) tab.all_short = 0;                         // benign race: every writer stores 0
+        if (l) atomicMax(&tab.max_len, (unsigned int)l);
+    }
+    __syncthreads();
+    int k = 1;
+    if (4 * R <= 8 && 4u * tab.max_len <= 24u) k = 4;
+    else if (2 * R <= 8 && 2u * tab.max_len <= 24u) k = 2;
+    if (threadIdx.x == 0) tab.group_k = k;
+    if (k > 1) {
+        for (int idx = threadIdx.x; idx < (1 << (k * R)); idx += blockDim.x) {
+            unsigned int bits = 0, total = 0;
+            for (int j = 0; j < k; ++j) {
+                const unsigned int c = (idx >> (R * j)) & ((1u << R) - 1u);
+                bits |= (unsigned int)tab.rev[c] << total;
+                total += tab.len[c];
+            }
+            tab.group[idx] = (total << 24) | bits;
+        }
     }
     __syncthreads();
 }
@@ -197,6 +226,16 @@ __device__ __forceinline__ int load_lane_codes(const uint8_t *__restrict__ crow,
     return (int)rest;
 }
 
+// The K*R code bits of group g (elements g*K .. g*K+K-1) of a lane's 16 codes.
+template <int R, int K>
+__device__ __forceinline__ unsigned int group_index(const Codes16<R> &cd, int g)
+{
+    const int bit = R * K * g, i = bit >> 5, sh = bit & 31;
+    uint32_t v = cd.w[i] >> sh;
+    if (sh + R * K > 32) v |= cd.w[i + 1] << (32 - sh);
+    return v & ((1u << (R * K)) - 1u);
+}
+
 // Sum of the codeword lengths of a lane's codes.
 template <int R>
 __device__ __forceinline__ unsigned int lane_bits(const EncodeTable &tab, const Codes16<R> &cd, int valid)
@@ -208,11 +247,44 @@ __device__ __forceinline__ unsigned int lane_bits(const EncodeTable &tab, const 
         const uint32_t x = cd.w[0], lo = x & 0x55555555u, hi = (x >> 1) & 0x55555555u;
         const unsigned int n1 = __popc(lo & ~hi), n2 = __popc(hi & ~lo), n3 = __popc(hi & lo);
         bits = (valid - n1 - n2 - n3) * tab.len[0] + n1 * tab.len[1] + n2 * tab.len[2];
+    } else if (R <= 4 && valid == 16 && tab.group_k == 2) {
+        if constexpr (R <= 4) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) bits += tab.group[group_index<R, 2>(cd, g)] >> 24;
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) bits += e < valid ? tab.len[cd.code(e)] : 0u;
     }
     return bits;
+}
+
+// Appends a lane's 16 codewords, K at a time through the group table (K = 1: the per-level
+// table, with missing elements skipped), to the wave's buffer starting at buffer bit `pos`.
+// Every table entry holds at most 24 bits, so one check of the 64-bit accumulator per entry
+// is enough.
+template <int R, int K>
+__device__ __forceinline__ void emit_groups(const EncodeTable &tab, const Codes16<R> &cd, int valid, unsigned int pos,
+                                            unsigned int *__restrict__ mine, int words)
+{
+    int w = (int)(pos >> 5);
+    unsigned long long acc = 0;
+    unsigned int held = pos & 31u;                             // bits of acc below the next free one
+#pragma unroll
+    for (int g = 0; g < 16 / K; ++g) {
+        unsigned int entry;
+        if constexpr (K == 1) entry = g < valid ? tab.packed[cd.code(g)] : 0u;
+        else entry = tab.group[group_index<R, K>(cd, g)];
+        acc |= (unsigned long long)(entry & 0xFFFFFFu) << held;
+        held += entry >> 24;
+        if (held >= 32u) {
+            if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+            ++w;
+            acc >>= 32;
+            held -= 32u;
+        }
+    }
+    if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
 }
 
 // Pass 1: number of stream bits of every tile (a wave per tile, a lane per 16 elements).
@@ -225,7 +297,7 @@ __global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const u
 {
     __shared__ EncodeTable tab;
     const uint32_t p = blockIdx.y;
-    fill_encode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
+    fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     // A block walks kBitsTilesPerBlock consecutive tiles, four at a time.
@@ -323,7 +395,7 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
     __shared__ EncodeTable tab;
     extern __shared__ unsigned int tile_buf[];
     const uint32_t p = blockIdx.y;
-    fill_encode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
+    fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     unsigned int *__restrict__ mine = tile_buf + wave * buf_words;
@@ -332,19 +404,19 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
     uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
     const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kWriteTilesPerWave;
 
-    // Everything the wave reads from memory is requested up front: the offsets of its tiles
-    // (lane i holds entry first + i) and the codes of all of them.
+    // The offsets of the wave's tiles are fetched up front (lane i holds entry first + i); the
+    // codes of a tile are requested while the tile before it is being assembled.
     const unsigned long long my_off = (lane <= kWriteTilesPerWave && first + lane <= tiles) ? offs[first + lane] : 0ull;
-    Codes16<R> all_cd[kWriteTilesPerWave];
-    int all_valid[kWriteTilesPerWave];
-#pragma unroll
-    for (int i = 0; i < kWriteTilesPerWave; ++i)
-        all_valid[i] = load_lane_codes<R>(crow, a.row_bytes, a.n, (first + i) * kTile + lane * 16, all_cd[i]);
+    Codes16<R> cd, cd_next;
+    int valid, valid_next = load_lane_codes<R>(crow, a.row_bytes, a.n, first * kTile + lane * 16, cd_next);
 
-#pragma unroll
+#pragma unroll 1
     for (int i = 0; i < kWriteTilesPerWave; ++i) {
         const int64_t tile = first + i;
         if (tile >= tiles) break;                              // wave-uniform
+        cd = cd_next;
+        valid = valid_next;
+        valid_next = load_lane_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kTile + lane * 16, cd_next);
         const unsigned long long start = __shfl(my_off, i, 64);
         unsigned long long end = __shfl(my_off, i + 1, 64);
         if (end < start) end = start;
@@ -352,8 +424,6 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         const unsigned long long word0 = start >> 5;
         const unsigned long long span = ((end - start) + shift + 31ull) >> 5;
         const int words = (int)(span < (unsigned long long)buf_words ? span : (unsigned long long)buf_words);
-        const Codes16<R> &cd = all_cd[i];
-        const int valid = all_valid[i];
         for (int j = lane; j < words; j += 64) mine[j] = 0u;
         wave_lds_sync();
 
@@ -365,24 +435,19 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         }
         // Bit position of this lane's first codeword in the wave's buffer.
         const unsigned int pos = shift + (incl - nbits);
-        int w = (int)(pos >> 5);
-        unsigned long long acc = 0;
-        unsigned int held = pos & 31u;                         // bits of acc below the next free one
         if (tab.all_short) {
-            // Codewords of at most 24 bits: one table word per element, at most one flush each.
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const unsigned int entry = e < valid ? tab.packed[cd.code(e)] : 0u;
-                acc |= (unsigned long long)(entry & 0xFFFFFFu) << held;
-                held += entry >> 24;
-                if (held >= 32u) {
-                    if (w < words) atomicOr(&mine[w], (unsigned int)acc);
-                    ++w;
-                    acc >>= 32;
-                    held -= 32u;
-                }
+            const int k = valid == 16 ? tab.group_k : 1;
+            if (R <= 2 && k == 4) {
+                if constexpr (R <= 2) emit_groups<R, 4>(tab, cd, valid, pos, mine, words);
+            } else if (R <= 4 && k == 2) {
+                if constexpr (R <= 4) emit_groups<R, 2>(tab, cd, valid, pos, mine, words);
+            } else {
+                emit_groups<R, 1>(tab, cd, valid, pos, mine, words);
             }
         } else {
+            int w = (int)(pos >> 5);
+            unsigned long long acc = 0;
+            unsigned int held = pos & 31u;
 #pragma unroll 1
             for (int e = 0; e < valid; ++e) {
                 unsigned int c = 0;
@@ -404,8 +469,8 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
                     }
                 }
             }
+            if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
         }
-        if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
         wave_lds_sync();
 
         for (int j = lane; j < words; j += 64) {
