@@ -34,8 +34,9 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
     for (int round = 0; round < 10; ++round) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        // a ^ b ^ c in one instruction: the three-input bitwise operation with truth table 0x96.
+        const uint32_t n0 = (uint32_t)__builtin_amdgcn_bitop3_b32((int)(uint32_t)(p1 >> 32), (int)c1, (int)k0, 0x96);
+        const uint32_t n2 = (uint32_t)__builtin_amdgcn_bitop3_b32((int)(uint32_t)(p0 >> 32), (int)c3, (int)k1, 0x96);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
@@ -134,22 +135,22 @@ __device__ __forceinline__ Quantized quantize_ternary(float v, float norm, const
     return out;
 }
 
-// General s.  xi_tab[m] = fl(m/s).  m > 0 implies v != 0, so "v < 0" and the sign bit of v
-// agree whenever the sign is applied.  m <= s always: the quotient never exceeds 1.
+// General s.  sxi_tab[c] = +-fl(|c - s|/s), indexed by the code c = level + s, so the sign of
+// the dequantised value comes with the table entry.  The quotient never exceeds 1, so the
+// level never exceeds s; x >= 0, so truncation is floor and x - floor(x) is exact.
 __device__ __forceinline__ Quantized quantize_levels(float v, float norm, const Ratio &rt, int s, float sf,
-                                                     const float *xi_tab, uint32_t word)
+                                                     const float *sxi_tab, uint32_t word)
 {
     const float a = ratio<false>(__builtin_fabsf(v), rt);
     const float x = a * sf;
-    const float l = __builtin_floorf(x);
-    const float frac = x - l;
+    const float frac = __builtin_amdgcn_fractf(x);
     const float u = (float)(word >> 8) * 0x1p-24f;
-    const int m = (int)l + ((u < frac) ? 1 : 0);
-    const float mag = norm * xi_tab[m];
-    const bool neg = (m > 0) && (__float_as_uint(v) >> 31);
+    const int m = (int)x + ((u < frac) ? 1 : 0);
+    const int smask = (int)__float_as_uint(v) >> 31;          // 0, or -1 for negative v
+    const int c = s + ((m ^ smask) - smask);                   // s - m for negative v, s + m otherwise
     Quantized out;
-    out.gt = neg ? -mag : mag;
-    out.code = (uint32_t)(neg ? s - m : s + m);
+    out.gt = norm * sxi_tab[c];
+    out.code = (uint32_t)c;
     return out;
 }
 

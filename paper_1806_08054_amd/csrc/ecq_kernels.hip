@@ -61,7 +61,8 @@ __device__ __forceinline__ uint32_t compensate4(const float (&g)[4], const float
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         v[e] = compensate(g[e], alpha, h[e]);
-        m = umax(m, __float_as_uint(v[e]) & 0x7FFFFFFFu);
+        // max of non-negative floats; |v| is an operand modifier, so one instruction per element
+        m = __float_as_uint(__builtin_fmaxf(__uint_as_float(m), __builtin_fabsf(v[e])));
     }
     return m;
 }
@@ -142,6 +143,17 @@ __device__ __forceinline__ void fill_xi_table(float *xi_tab, int s)
     __syncthreads();
 }
 
+// Signed table of the rounding step, indexed by the code c = level + s: +-fl(|level|/s).
+__device__ __forceinline__ void fill_sxi_table(float *sxi_tab, int s)
+{
+    for (int c = threadIdx.x; c <= 2 * s; c += blockDim.x) {
+        const int q = c - s;
+        const float xi = (float)(q < 0 ? -q : q) / (float)s;
+        sxi_tab[c] = q < 0 ? -xi : xi;
+    }
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------------------------------------
 // Single pass, buckets of 256 elements or more: a team of W waves per bucket, J float4 per lane.
 // ---------------------------------------------------------------------------------------------
@@ -150,7 +162,7 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
                                                      const uint32_t blocks_per_row, const uint32_t worker0,
                                                      const uint32_t workers)
 {
-    __shared__ float xi_tab[128];
+    __shared__ float xi_tab[256];
     __shared__ uint32_t wave_norm[16];
     // Block -> (worker row, block of the row).  Workgroups go to the chip's 8 XCDs round-robin
     // by id.  With stripe > 0 the launch is one-dimensional and XCD x takes the x-th eighth of
@@ -165,7 +177,7 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
         p = worker0 + row;
         row_block = (uint32_t)(id - (int64_t)row * blocks_per_row);
     }
-    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -262,8 +274,8 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 template <int R, bool UPDATE>
 __global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lanes_per_bucket)
 {
-    __shared__ float xi_tab[128];
-    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    __shared__ float xi_tab[256];
+    if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -349,31 +361,6 @@ __device__ __forceinline__ float decode_one(uint64_t bits, int e, int s, float s
     return q < 0 ? -gt : gt;
 }
 
-// Eq. (6) from an encoded message; a lane owns 8 consecutive elements (R whole bytes).
-template <int R>
-__global__ void __launch_bounds__(256) k_error_update(const Args a)
-{
-    __shared__ float xi_tab[128];
-    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
-    const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-    const uint32_t p = blockIdx.y;
-    if (elem >= a.n) return;
-    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
-    float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
-    const uint64_t bits = load_code_group<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem);
-    const float scale = a.scales[(int64_t)p * a.scale_stride + elem / a.bucket];
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        float g[4], h[4];
-        load4(grow, elem + 4 * half, a.n, g);
-        load4(hrow, elem + 4 * half, a.n, h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            h[e] = error_update(a.beta, h[e], g[e], decode_one<R>(bits, 4 * half + e, a.s, scale, xi_tab));
-        store4(hrow, elem + 4 * half, a.n, h);
-    }
-}
-
 // The 4*R code bits of the 4 elements starting at `elem` (a multiple of 4).  They start at bit
 // 0 or 4 of a byte and span (R+1)/2 bytes.
 template <int R>
@@ -396,6 +383,54 @@ __device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ crow
         if (byte0 + b < row_bytes) w |= (uint32_t)crow[byte0 + b] << (8 * b);
     w >>= (int)(bit0 & 7);
     return (R == 8) ? w : (w & ((1u << (4 * (R & 7))) - 1u));
+}
+
+// Eq. (6) from an encoded message, in the access pattern of the fused kernel: a wave owns two
+// runs of 256 consecutive elements, a lane 4 consecutive elements of each (one float4 of g and
+// of h, 4*R code bits, one norm), everything streamed once with non-temporal accesses.
+// bucket_shift >= 0 when the bucket is a power of two.
+template <int R>
+__global__ void __launch_bounds__(256) k_error_update(const Args a, const int bucket_shift)
+{
+    __shared__ float xi_tab[128];
+    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    constexpr int J = 2;
+    const int lane = threadIdx.x & 63;
+    const uint32_t p = blockIdx.y;
+    int64_t base = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * (256 * J);
+    base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+    if (base >= a.n) return;                                   // wave-uniform
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
+    float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
+    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    const float *__restrict__ srow = a.scales + (int64_t)p * a.scale_stride;
+    // Bucket of the wave's first element, once per wave; lanes add a 32-bit quotient.
+    const int64_t k0 = bucket_shift >= 0 ? (base >> bucket_shift) : (base / a.bucket);
+    const uint32_t rem0 = (uint32_t)(base - k0 * a.bucket);
+
+    float g[J][4], h[J][4], scale[J];
+    uint32_t bits[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t elem = base + j * 256 + lane * 4;
+        load4(grow, elem, a.n, g[j]);
+        load4(hrow, elem, a.n, h[j]);
+        const bool exists = elem < a.n;
+        bits[j] = exists ? load_codes4<R>(crow, a.row_bytes, elem, elem + 4 <= a.n) : 0u;
+        const uint32_t r = rem0 + (uint32_t)(j * 256 + lane * 4);
+        const int64_t k = k0 + (bucket_shift >= 0 ? (r >> bucket_shift) : (r / (uint32_t)a.bucket));
+        scale[j] = exists ? srow[k] : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t elem = base + j * 256 + lane * 4;
+        if (elem >= a.n) continue;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            h[j][e] = error_update(a.beta, h[j][e], g[j][e], decode_one<R>(bits[j], e, a.s, scale[j], xi_tab));
+        store4(hrow, elem, a.n, h[j]);
+    }
 }
 
 // Decode table of the aggregation kernel for r > 2, in LDS: sxi[c] = +-fl(|c-s|/s), so that
@@ -900,8 +935,11 @@ hipError_t launch_quantize(const Args &a, const Plan &plan, bool update_h, hipSt
 
 hipError_t launch_error_update(const Args &a, hipStream_t stream)
 {
-    const dim3 grid(cdiv(cdiv(a.n, 8), 256), (unsigned)a.workers);
-#define CALL(RR) hipLaunchKernelGGL((k_error_update<RR>), grid, dim3(256), 0, stream, a)
+    const dim3 grid(cdiv(cdiv(a.n, 512), 4), (unsigned)a.workers);
+    int bucket_shift = -1;
+    if ((a.bucket & (a.bucket - 1)) == 0)
+        for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
+#define CALL(RR) hipLaunchKernelGGL((k_error_update<RR>), grid, dim3(256), 0, stream, a, bucket_shift)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();

@@ -164,6 +164,7 @@ def test_levels_and_buckets(E, s, bucket):
     wl = synth.Workload("edge", P=3, N=2 * 1024 + 8 * 37 + 3, bucket=bucket, s=s, alpha=0.5, beta=0.75,
                         iters=2, kind="normal", data_seed=s * 131 + bucket)
     _free_run(E, wl, 2, pad=3)
+    _free_run(E, wl, 2, pad=3, fused=False)                    # ecq_quantize, then ecq_error_update
 
 
 @pytest.mark.parametrize("bucket", [16, 24, 32, 128, 256, 264, 2048, 4096, 8192, 16384, 32768, 40000])
@@ -179,6 +180,7 @@ def test_tiny_lengths(E, N, s):
     wl = synth.Workload("edge", P=2, N=N, bucket=512, s=s, alpha=1.0, beta=1.0, iters=2, kind="normal",
                         data_seed=N)
     _free_run(E, wl, 2)
+    _free_run(E, wl, 2, fused=False)
     wl = synth.scaled(wl, bucket=8)
     _free_run(E, wl, 2)
 
