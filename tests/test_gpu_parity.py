@@ -498,6 +498,44 @@ def test_huffman_decodes_an_oracle_stream(E):
     assert np.array_equal(back.cpu().numpy()[0, : E.row_bytes(N, s)], oracle.pack_rows(q[None, :], s)[0])
 
 
+# ------------------------------------------------------------------ HIP graph ---------------
+
+def test_step_under_graph_capture(E):
+    """The library only launches kernels on the caller's stream, so a whole step (fused
+    quantise + update, then aggregate) can be captured into a HIP graph.  Every replay, with
+    eager work and synchronisations in between, must reproduce the eager step bit for bit
+    (the step number is a launch argument, so a replay repeats the captured iteration)."""
+    wl = synth.Workload("edge", P=4, N=300_000 + 40, bucket=512, s=1, alpha=1.0, beta=0.9, iters=1,
+                        kind="normal", data_seed=11)
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=True)
+    g_np = synth.gradients(wl, 0).numpy()
+    st.g[:, : wl.N] = _dev(g_np)
+    h0 = torch.randn_like(st.h) * 0.01
+    st.h.copy_(h0)
+    E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 5, st.codes, st.scales)
+    E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (st.h, st.codes, st.scales, st.out)]
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    st.h.copy_(h0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 5, st.codes, st.scales)
+            E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+    for replay in range(4):
+        st.h.copy_(h0)                                         # eager work between replays
+        st.poison()
+        st.out.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((st.h, st.codes, st.scales, st.out), want):
+            assert torch.equal(got, ref), f"replay {replay} differs from the eager step"
+
+
 # ------------------------------------------------------------------ boundary errors --------
 
 def test_argument_errors_leave_outputs_untouched(E):
