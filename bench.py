@@ -57,6 +57,34 @@ def cpu_baseline(wl, sample_n, g_sample):
             "gelem_per_s": round(P * sample_n / dt / 1e9, 5)}
 
 
+def entropy_coding(E, torch, sh, wl, codes, timed):
+    """Outside the timed region: the Huffman coding of the last step's messages that the
+    paper's communication-cost figures assume (Section 4, cost paragraph), leg by leg."""
+    P, N, s = wl.P, wl.N, wl.s
+    bins, tiles = 2 * s + 1, E.huffman_num_tiles(N)
+    counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    lengths = torch.zeros(P, bins, dtype=torch.uint8, device="cuda")
+    words = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    streams = torch.zeros(P, sh.code_stride, dtype=torch.uint8, device="cuda")
+    offs = torch.zeros(P, tiles + 1, dtype=torch.int64, device="cuda")
+    back = torch.zeros_like(codes)
+    hist_ms = timed(lambda: E.ecq_level_histogram(sh, codes, counts, bins))
+    build_ms = timed(lambda: E.ecq_huffman_build(P, s, counts, bins, lengths, words))
+    enc_ms = timed(lambda: E.ecq_huffman_encode(sh, codes, lengths, words, bins, streams, sh.code_stride, offs,
+                                                tiles + 1))
+    dec_ms = timed(lambda: E.ecq_huffman_decode(sh, streams, sh.code_stride, offs, tiles + 1, lengths, words, bins,
+                                                back))
+    rb = E.row_bytes(N, s)
+    ok = bool(torch.equal(back[:, :rb], codes[:, :rb]))
+    bits = int(offs[:, tiles].sum().item())
+    bound = sum(E.ecq_entropy_bound_bits(row) for row in counts.cpu().tolist())
+    return {"bits_per_element": round(bits / (P * N), 4), "entropy_bound_bits_per_element": round(bound / (P * N), 4),
+            "fixed_length_bits_per_element": E.code_bits(s), "histogram_ms": round(hist_ms, 4),
+            "build_ms": round(build_ms, 4), "encode_ms": round(enc_ms, 4), "decode_ms": round(dec_ms, 4),
+            "encode_gelem_per_s": round(P * N / (enc_ms * 1e-3) / 1e9, 1),
+            "decode_gelem_per_s": round(P * N / (dec_ms * 1e-3) / 1e9, 1), "round_trip_ok": ok}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +93,8 @@ def main():
     ap.add_argument("--workload", default="resnet50", choices=["tiny", "linear", "resnet50", "alexnet", "vgg16"])
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-entropy-coding", action="store_true",
+                    help="skip the Huffman legs (level histogram, code construction, encode, decode)")
     ap.add_argument("--cpu-sample", type=int, default=32 * 1024 * 1024)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -180,6 +210,8 @@ def main():
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch:"):
                 result["roofline"]["traffic"] = int(line.split(":")[1])
+    if not args.no_entropy_coding:
+        result["entropy_coding"] = entropy_coding(E, torch, sh, wl, codes, timed)
     if not args.no_cpu_baseline:
         n_s = min(N, max(wl.bucket, args.cpu_sample // wl.bucket * wl.bucket))
         result["cpu_baseline"] = cpu_baseline(wl, n_s, pool[0][:, :n_s].cpu().numpy())
