@@ -3,9 +3,10 @@
 iteration of each workload.
 
 Where the oracle can cover everything in reasonable time the comparison is total (workloads
-1-3, and selected whole worker rows of 4-5); beyond that, randomly sampled buckets (always
-including each row's first bucket and its ragged last one) are recomputed one by one by the
-oracle from the (g, h) the GPU kernel actually consumed.  Bars as in test_gpu_parity.py.
+1-3, and selected whole worker rows of 4-5); beyond that, buckets sampled once per run (always
+including each row's first bucket and its ragged last one) are followed by the oracle through
+every iteration, free-running from h = 0 on the seeded gradients alone: no oracle input ever
+comes from the library.  Bars as in test_gpu_parity.py.
 """
 import numpy as np
 import pytest
@@ -38,8 +39,9 @@ def _pack_row_chunked(q_row, s, chunk=1 << 20):
     return np.concatenate(parts)
 
 
-def _check_rows(st, wl, t, rows, h_before):
-    """Whole worker rows: oracle from (g row, h row before the step) vs the GPU's outputs."""
+def _check_rows(st, wl, t, rows, h_before, ref_msg=None):
+    """Whole worker rows: oracle from the seeded g row and its own h row vs the GPU's outputs.
+    ref_msg[p] receives the oracle's encoded row and scales."""
     for p in rows:
         g_np = st.g[p, : wl.N].cpu().numpy()[None, :]
         h_np = h_before[p][None, :].copy()
@@ -55,6 +57,8 @@ def _check_rows(st, wl, t, rows, h_before):
         nbits = int((hh.view(np.uint32) != h_np[0].view(np.uint32)).sum())
         assert nbits == 0, f"{nbits} h values not bit-identical, worker {p}, iteration {t}"
         h_before[p] = h_np[0]
+        if ref_msg is not None:
+            ref_msg[p] = (codes_ref, scales[0])
     return h_before
 
 
@@ -71,13 +75,18 @@ def _bucket_extent(wl, k, r):
     return e0, e1, e0 * r // 8, (e1 * r + 7) // 8
 
 
-def _check_sampled(E, st, wl, t, picks, before):
-    """before[(p,k)] = (g slice, h slice) captured ahead of the step."""
+def _check_sampled(E, st, wl, t, picks, g_before, h_oracle, message=None):
+    """g_before[(p,k)] = the bucket's seeded gradient; h_oracle[(p,k)] = the oracle's own
+    accumulator for that bucket, advanced here; message[(p,k)] receives the oracle's encoded
+    bucket and scale."""
     r = E.code_bits(wl.s)
     for (p, k) in picks:
         e0, e1, b0, b1 = _bucket_extent(wl, k, r)
-        g_np, h_np = before[(p, k)]
+        g_np, h_np = g_before[(p, k)], h_oracle[(p, k)]
         q, scale, _, h_next = oracle.bucket_step(g_np, h_np, e0, p, wl.s, wl.alpha, wl.beta, SEED, t)
+        h_oracle[(p, k)] = h_next
+        if message is not None:
+            message[(p, k)] = (oracle.pack(q, wl.s), np.float32(scale))
         assert st.scales[p, k].item() == float(scale), f"scale differs at worker {p} bucket {k}"
         codes = st.codes[p, b0:b1].cpu().numpy()
         assert np.array_equal(codes, oracle.pack(q, wl.s)), f"codes differ at worker {p} bucket {k} iteration {t}"
@@ -85,12 +94,13 @@ def _check_sampled(E, st, wl, t, picks, before):
         assert np.array_equal(hh.view(np.uint32), h_next.view(np.uint32)), f"h differs at worker {p} bucket {k}"
 
 
-def _check_aggregate_sampled(E, st, wl, ks):
+def _check_aggregate_sampled(E, st, wl, ks, message):
+    """Eq. (4) on buckets the oracle followed for every worker: its own messages are averaged."""
     r = E.code_bits(wl.s)
     for k in ks:
         e0, e1, b0, b1 = _bucket_extent(wl, k, r)
-        codes = st.codes[:, b0:b1].cpu().numpy()
-        scales = st.scales[:, k:k + 1].cpu().numpy()
+        codes = np.stack([message[(p, k)][0] for p in range(wl.P)])
+        scales = np.array([[message[(p, k)][1]] for p in range(wl.P)], np.float32)
         ref = oracle.aggregate(codes, scales, e1 - e0, wl.bucket, wl.s)
         got = st.out[e0:e1].cpu().numpy()
         assert _rel_ok(got, ref, wl.bucket)
@@ -100,37 +110,45 @@ def _check_aggregate_sampled(E, st, wl, ks):
 def _run(E, wl, full_iters, full_rows, samples=48, seed=0, aligned=True):
     """Free-running GPU iterations.  For t < full_iters the rows in full_rows are compared in
     full (their oracle h runs freely beside the GPU's); every iteration, sampled buckets of all
-    rows are recomputed from the inputs the GPU consumed; the aggregate is checked on sampled
+    rows are followed by the oracle on its own state; the aggregate is checked on sampled
     buckets (in full when full_rows covers every worker).  aligned: worker rows start on
     128-byte lines, the layout bench.py times; otherwise the tightest legal strides."""
     rng = np.random.default_rng(seed)
     st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=aligned)
     r = E.code_bits(wl.s)
     h_rows = {p: np.zeros(wl.N, np.float32) for p in full_rows} if full_iters else {}
+    picks = _sample_buckets(wl, rng, samples)
+    # Buckets followed for EVERY worker, so that the aggregate can be checked on them.
+    agg_ks = sorted({0, wl.nb - 1} | {int(rng.integers(wl.nb)) for _ in range(4)})
+    picks = sorted(set(picks) | {(p, k) for p in range(wl.P) for k in agg_ks})
+    h_oracle, message = {}, {}
+    for (p, k) in picks:
+        e0, e1, _, _ = _bucket_extent(wl, k, r)
+        h_oracle[(p, k)] = np.zeros(e1 - e0, np.float32)
     for t in range(wl.iters):
         synth.gradients(wl, t, device="cuda", out=st.g)
-        picks = _sample_buckets(wl, rng, samples)
         before = {}
         for (p, k) in picks:
             e0, e1, _, _ = _bucket_extent(wl, k, r)
-            before[(p, k)] = (st.g[p, e0:e1].cpu().numpy(), st.h[p, e0:e1].cpu().numpy())
+            before[(p, k)] = st.g[p, e0:e1].cpu().numpy()
         st.poison()
         E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, t, st.codes, st.scales)
         st.out.fill_(-7.0)
         E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
         torch.cuda.synchronize()
         assert bool((st.codes[:, st.rb:] == 0xEE).all())
-        _check_sampled(E, st, wl, t, picks, before)
+        _check_sampled(E, st, wl, t, picks, before, h_oracle, message)
+        ref_msg = {}
         if t < full_iters:
-            h_rows = _check_rows(st, wl, t, full_rows, h_rows)
+            h_rows = _check_rows(st, wl, t, full_rows, h_rows, ref_msg)
         if t < full_iters and len(full_rows) == wl.P:
-            codes = st.codes[:, : st.rb].cpu().numpy()
-            scales = st.scales[:, : st.nb].cpu().numpy()
+            codes = np.stack([ref_msg[p][0] for p in range(wl.P)])
+            scales = np.stack([ref_msg[p][1] for p in range(wl.P)])
             ref = oracle.aggregate(codes, scales, wl.N, wl.bucket, wl.s)
             got = st.out.cpu().numpy()
             assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "aggregate differs"
         else:
-            _check_aggregate_sampled(E, st, wl, sorted({k for (_, k) in picks}))
+            _check_aggregate_sampled(E, st, wl, agg_ks, message)
         print(f"{wl.name}: iteration {t} ok", flush=True)
 
 
@@ -179,8 +197,14 @@ def test_huffman_full_size(E, name, rows):
     st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=True)
     synth.gradients(wl, 0, device="cuda", out=st.g)
     E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 0, st.codes, st.scales)
-    del st.g, st.h
     P, N, s = wl.P, wl.N, wl.s
+    # The levels of the rows compared in full come from the oracle, run on the seeded gradients.
+    q_rows = {}
+    for p in rows:
+        g_row = st.g[p, :N].cpu().numpy()[None, :]
+        q_rows[p] = oracle.batch_step(g_row, np.zeros_like(g_row), wl.bucket, s, wl.alpha, wl.beta, SEED, 0,
+                                      worker0=p)[0][0]
+    del st.g, st.h
     bins, tiles = 2 * s + 1, E.huffman_num_tiles(N)
     counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
     lengths = torch.zeros(P, bins, dtype=torch.uint8, device="cuda")
@@ -203,7 +227,8 @@ def test_huffman_full_size(E, name, rows):
         assert bound - 1e-6 * N <= int(total[p]) < bound + N, (p, bound, int(total[p]))
         assert int(total[p]) <= N * E.code_bits(s)
     for p in rows:
-        q = oracle.unpack(st.codes[p, : st.rb].cpu().numpy(), N, s)
+        q = q_rows[p]
+        assert np.array_equal(st.codes[p, : st.rb].cpu().numpy(), _pack_row_chunked(q, s))
         ref_counts = oracle.level_histogram(q, s)
         assert np.array_equal(cnt[p], ref_counts)
         ref_len = oracle.huffman_lengths(ref_counts)
