@@ -336,7 +336,8 @@ def test_closed_loop_least_squares(E):
         idx = torch.randint(0, 2000, (P, mb), generator=gen, device="cuda")
         Xb = torch.gather(X, 1, idx[:, :, None].expand(P, mb, d))
         yb = torch.gather(y, 1, idx)
-        resid = torch.einsum("pmd,d->pm", Xb, w) - yb
+        w_in = _dev(w_ref)                                     # gradients come from the oracle's model
+        resid = torch.einsum("pmd,d->pm", Xb, w_in) - yb
         st.g[:, :d] = torch.einsum("pmd,pm->pd", Xb, resid) / mb
         losses.append(float((resid ** 2).mean()))
         g_np = st.g[:, :d].cpu().numpy()
