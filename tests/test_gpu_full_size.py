@@ -240,3 +240,40 @@ def test_huffman_full_size(E, name, rows):
         nbytes = (bits + 7) // 8
         assert np.array_equal(streams[p, :nbytes].cpu().numpy(), ref_stream[:nbytes]), f"stream differs, worker {p}"
         print(f"{name}: worker {p}: {bits / N:.4f} bits per element (fixed length: {E.code_bits(s)})", flush=True)
+
+
+def test_row_longer_than_2_pow_32(E):
+    """One worker row of 2^32 + 5,000 elements (17 GB each of g and h): element indices, byte
+    offsets and the Philox counter beyond 32 bits.  Buckets around the 2^32 boundary, the first
+    and the ragged last one are recomputed by the oracle; the aggregate (P = 1) is checked on
+    the same buckets."""
+    N, bucket, s = (1 << 32) + 5000, 512, 1
+    wl = synth.Workload("long", P=1, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="normal",
+                        data_seed=3)
+    st = GpuState(E, 1, N, bucket, s, aligned=True)
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    step = 1 << 28
+    for e0 in range(0, N, step):                               # seeded input, drawn in slabs
+        e1 = min(N, e0 + step)
+        st.g[0, e0:e1] = torch.randn(e1 - e0, generator=gen, device="cuda") * 0.01
+    r = E.code_bits(s)
+    edge = (1 << 32) // bucket
+    ks = [0, 1, edge - 2, edge - 1, edge, edge + 1, wl.nb - 2, wl.nb - 1, 12345, edge // 2 + 7]
+    before = {k: st.g[0, k * bucket:min(N, (k + 1) * bucket)].cpu().numpy() for k in ks}
+    E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 3, st.codes, st.scales)
+    E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+    torch.cuda.synchronize()
+    for k in ks:
+        e0, e1, b0, b1 = _bucket_extent(wl, k, r)
+        g_np = before[k]
+        q, scale, gt, h_next = oracle.bucket_step(g_np, np.zeros_like(g_np), e0, 0, s, wl.alpha, wl.beta, SEED, 3)
+        assert st.scales[0, k].item() == float(scale), f"scale differs in bucket {k}"
+        assert np.array_equal(st.codes[0, b0:b1].cpu().numpy(), oracle.pack(q, s)), f"codes differ in bucket {k}"
+        assert np.array_equal(st.h[0, e0:e1].cpu().numpy().view(np.uint32), h_next.view(np.uint32))
+        ref = oracle.aggregate(oracle.pack(q, s)[None, :], np.array([[scale]], np.float32), e1 - e0, bucket, s)
+        assert np.array_equal(st.out[e0:e1].cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    assert bool((st.codes[0, st.rb:] == 0xEE).all())
+    w = torch.zeros(8, dtype=torch.int32, device="cuda")
+    E.ecq_philox_words(SEED, 3, 0, (1 << 32) + 4, 8, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), oracle.words(SEED, 3, 0, (1 << 32) + 4, 8))
