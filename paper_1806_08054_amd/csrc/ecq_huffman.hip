@@ -287,7 +287,9 @@ __device__ __forceinline__ void emit_groups(const EncodeTable &tab, const Codes1
     if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
 }
 
-// Pass 1: number of stream bits of every tile (a wave per tile, a lane per 16 elements).
+// Pass 1: number of stream bits of every tile.  Sixteen lanes share a tile (a lane owns four
+// runs of 16 elements, 8*R contiguous bytes), so a wave covers four tiles per step and a block
+// 32 tiles in two steps, with all of a lane's loads requested before any is used.
 template <int R>
 __global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const uint8_t *__restrict__ lengths,
                                                           const unsigned long long *__restrict__ codewords,
@@ -298,19 +300,30 @@ __global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const u
     __shared__ EncodeTable tab;
     const uint32_t p = blockIdx.y;
     fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
-    const int lane = threadIdx.x & 63;
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    // A block walks kBitsTilesPerBlock consecutive tiles, four at a time.
-    const int64_t tile0 = (int64_t)blockIdx.x * kBitsTilesPerBlock + (threadIdx.x >> 6);
-#pragma unroll 2
-    for (int i = 0; i < kBitsTilesPerBlock / 4; ++i) {
-        const int64_t tile = tile0 + 4 * i;
-        if (tile >= tiles) break;                              // wave-uniform
-        Codes16<R> cd;
-        const int valid = load_lane_codes<R>(crow, a.row_bytes, a.n, tile * kTile + lane * 16, cd);
-        unsigned int bits = lane_bits<R>(tab, cd, valid);
-        for (int d = 1; d < 64; d <<= 1) bits += __shfl_xor(bits, d, 64);
-        if (lane == 0) tile_offsets[(int64_t)p * offset_stride + tile] = bits;
+    constexpr int kSteps = kBitsTilesPerBlock / 16;
+    Codes16<R> cd[kSteps][4];
+    int valid[kSteps][4];
+    int64_t tile[kSteps];
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+        tile[i] = (int64_t)blockIdx.x * kBitsTilesPerBlock + i * 16 + (threadIdx.x >> 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            valid[i][k] = load_lane_codes<R>(crow, a.row_bytes, a.n, tile[i] * kTile + ((threadIdx.x & 15) * 4 + k) * 16,
+                                             cd[i][k]);
+    }
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+        unsigned int bits = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) bits += lane_bits<R>(tab, cd[i][k], valid[i][k]);
+        // Sum over the 16 lanes of a tile (one DPP row).
+        bits += dpp_u32<0xB1>(bits);                           // quad_perm [1,0,3,2]
+        bits += dpp_u32<0x4E>(bits);                           // quad_perm [2,3,0,1]
+        bits += dpp_u32<0x141>(bits);                          // row_half_mirror
+        bits += dpp_u32<0x140>(bits);                          // row_mirror
+        if ((threadIdx.x & 15) == 0 && tile[i] < tiles) tile_offsets[(int64_t)p * offset_stride + tile[i]] = bits;
     }
 }
 
