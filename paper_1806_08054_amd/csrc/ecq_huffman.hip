@@ -330,8 +330,8 @@ __global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const u
 // Pass 2: exclusive prefix sum of the tile sizes of one row (one block per row), in place,
 // 8192 tiles at a time (8 consecutive tiles per thread, the next chunk's sizes already loading
 // while the current one is scanned); entry `tiles` receives the total.  Also clears the 32-bit
-// stream word in which each tile starts and the one that holds the end of the row: those are
-// the words two tiles may share and pass 3 fills them with atomic ORs.
+// stream word in which every kWriteTilesPerWave-th tile starts and the one that holds the end of
+// the row: those are the words two waves of pass 3 may share, and they fill them with atomic ORs.
 __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__restrict__ tile_offsets,
                                                       const int64_t offset_stride, const int64_t tiles,
                                                       uint32_t *__restrict__ streams, const int64_t stream_words,
@@ -376,7 +376,7 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
             if (i0 + k < tiles) {
                 row[i0 + k] = off;
                 const unsigned long long word = off >> 5;
-                if (word < (unsigned long long)stream_words) out[word] = 0u;
+                if ((i0 + k) % kWriteTilesPerWave == 0 && word < (unsigned long long)stream_words) out[word] = 0u;
             }
             off += v[k];
         }
@@ -389,10 +389,10 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
     }
 }
 
-// Pass 3: a wave assembles the bits of a tile in LDS, aligned with the 32-bit words of the
-// stream, then stores the words: those that lie wholly inside the tile with plain coalesced
-// stores, the first and last (which neighbouring tiles may share) with atomic ORs.  A wave
-// walks kWriteTilesPerWave consecutive tiles so that the code table is read once per 32 tiles.
+// Pass 3: a wave walks kWriteTilesPerWave consecutive tiles.  It assembles the bits of a tile
+// in LDS, aligned with the 32-bit words of the stream, then stores the words with plain
+// coalesced stores; a partial last word is carried into the next tile, and only the first and
+// last word of the whole run (which a neighbouring wave may share) are filled with atomic ORs.
 // buf_words = LDS words per wave: enough for 1024 codewords of the longest length a code over
 // 2s+1 levels can have (2s bits); longer tiles (only possible with a table that does not
 // belong to the message) are cut off.
@@ -423,6 +423,7 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
     Codes16<R> cd, cd_next;
     int valid, valid_next = load_lane_codes<R>(crow, a.row_bytes, a.n, first * kTile + lane * 16, cd_next);
 
+    unsigned int carry = 0;                                    // partial last word of the tile before (wave-uniform)
 #pragma unroll 1
     for (int i = 0; i < kWriteTilesPerWave; ++i) {
         const int64_t tile = first + i;
@@ -486,13 +487,26 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         }
         wave_lds_sync();
 
-        for (int j = lane; j < words; j += 64) {
-            const unsigned long long gw = word0 + (unsigned long long)j;
-            if (gw >= (unsigned long long)stream_words) continue;
-            const unsigned int value = mine[j];
-            const bool whole = gw * 32ull >= start && (gw + 1ull) * 32ull <= end;
-            if (whole) out[gw] = value;
-            else if (value) atomicOr(&out[gw], value);
+        // Words wholly inside the wave's run of tiles leave with plain stores.  The last word of
+        // a tile, when partial, is carried into the first word of the wave's next tile; only the
+        // two ends of the run (words another wave may share) use atomic ORs.
+        const bool final_tile = i == kWriteTilesPerWave - 1 || tile + 1 >= tiles;
+        const bool has_tail = (end & 31ull) != 0ull;
+        if (words > 0) {
+            for (int j = lane; j < words; j += 64) {
+                const unsigned long long gw = word0 + (unsigned long long)j;
+                if (gw >= (unsigned long long)stream_words) continue;
+                unsigned int value = mine[j];
+                if (j == 0 && i > 0) value |= carry;
+                const bool lower_ok = i > 0 || gw * 32ull >= start;
+                const bool upper_ok = (gw + 1ull) * 32ull <= end;
+                if (lower_ok && upper_ok) out[gw] = value;
+                else if (lower_ok && !final_tile) continue;    // carried below
+                else if (value) atomicOr(&out[gw], value);
+            }
+            unsigned int tail = has_tail && !final_tile ? mine[words - 1] : 0u;
+            if (has_tail && !final_tile && words == 1 && i > 0) tail |= carry;
+            carry = tail;
         }
         wave_lds_sync();                                       // the buffer is cleared again for the next tile
     }
