@@ -26,7 +26,7 @@ constexpr int kTile = ECQ_HUFFMAN_TILE;
 constexpr int kMaxLen = 63;                                    // longest codeword handled
 constexpr int kFastBits = 10;                                  // decode: direct table on 10 stream bits
 constexpr int kBitsTilesPerBlock = 32;                         // pass 1: tiles per block (amortises the table)
-constexpr int kWriteTilesPerWave = 8;                          // pass 3: consecutive tiles per wave
+constexpr int kWriteTilesPerWave = 16;                         // pass 3: consecutive tiles per wave
 constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
 constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
 
