@@ -616,21 +616,37 @@ __global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint
 
     const unsigned long long start = tile_offsets[(int64_t)p * offset_stride + tile];
     unsigned long long next_word = start >> 5;
-    // Bit reservoir: `have` valid bits, the next stream bit is bit 0.  One word is always
-    // loaded ahead of its use.
-    auto fetch = [&]() -> unsigned int {
-        const unsigned int wv = next_word < (unsigned long long)stream_words ? in[next_word] : 0u;
-        ++next_word;
+    // Bit reservoir: `have` valid bits, the next stream bit is bit 0.  Stream words arrive four
+    // at a time and a whole batch ahead of their use, so the chain below waits for memory at
+    // most once per 128 stream bits, for loads issued 128 bits earlier.
+    auto fetch4 = [&]() -> uint4 {
+        uint4 b;
+        b.x = next_word + 0 < (unsigned long long)stream_words ? in[next_word + 0] : 0u;
+        b.y = next_word + 1 < (unsigned long long)stream_words ? in[next_word + 1] : 0u;
+        b.z = next_word + 2 < (unsigned long long)stream_words ? in[next_word + 2] : 0u;
+        b.w = next_word + 3 < (unsigned long long)stream_words ? in[next_word + 3] : 0u;
+        next_word += 4;
+        return b;
+    };
+    uint4 batch = fetch4(), batch_ahead = fetch4();
+    int in_batch = 4;
+    auto take = [&]() -> unsigned int {
+        if (in_batch == 0) {
+            batch = batch_ahead;
+            batch_ahead = fetch4();
+            in_batch = 4;
+        }
+        const unsigned int wv = batch.x;
+        batch.x = batch.y; batch.y = batch.z; batch.z = batch.w;
+        --in_batch;
         return wv;
     };
-    unsigned long long res = fetch();
+    unsigned long long res = take();
     unsigned int have = 32u;
-    unsigned int ahead = fetch();
     auto refill = [&]() {
         if (have <= 32u) {
-            res |= (unsigned long long)ahead << have;
+            res |= (unsigned long long)take() << have;
             have += 32u;
-            ahead = fetch();
         }
     };
     {
