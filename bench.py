@@ -35,8 +35,9 @@ def algorithmic_bytes(P, N, bucket, s, E):
     return fused, dequant
 
 
-def cpu_baseline(wl, sample_n, g_sample):
-    """The oracle as it stands on a prefix of every worker's gradient (whole buckets)."""
+def cpu_baseline(wl, sample_n, g_sample, steps=3):
+    """The oracle as it stands on a prefix of every worker's gradient (whole buckets), `steps`
+    free-running steps: about 10-30 s of CPU work at the default sizes."""
     import numpy as np
     import oracle
     P = wl.P
@@ -44,16 +45,17 @@ def cpu_baseline(wl, sample_n, g_sample):
     h = np.zeros_like(g)
     threads = oracle.max_threads()
     t0 = time.perf_counter()
-    q, scales, _ = oracle.batch_step(g, h, wl.bucket, wl.s, wl.alpha, wl.beta, 1, 0, threads=threads)
-    codes = oracle.pack_rows(q, wl.s)
-    oracle.aggregate(codes, scales, sample_n, wl.bucket, wl.s)
-    dt = time.perf_counter() - t0
+    for t in range(steps):
+        q, scales, _ = oracle.batch_step(g, h, wl.bucket, wl.s, wl.alpha, wl.beta, 1, t, threads=threads)
+        codes = oracle.pack_rows(q, wl.s)
+        oracle.aggregate(codes, scales, sample_n, wl.bucket, wl.s)
+    dt = (time.perf_counter() - t0) / steps
     rb = oracle.row_bytes(sample_n, wl.s)
     nb = (sample_n + wl.bucket - 1) // wl.bucket
     nbytes = P * (12 * sample_n + rb + 4 * nb) + P * (rb + 4 * nb) + 4 * sample_n
     return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {sample_n} elements of each of the {P} workers, 1 step "
-                      f"(quantise+update, pack, aggregate), {dt:.2f} s wall",
+            "sample": f"first {sample_n} elements of each of the {P} workers, {steps} steps "
+                      f"(quantise+update, pack, aggregate), {dt:.2f} s wall per step on {threads} threads",
             "gelem_per_s": round(P * sample_n / dt / 1e9, 5)}
 
 
