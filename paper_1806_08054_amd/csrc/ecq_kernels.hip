@@ -38,6 +38,20 @@ __device__ __forceinline__ void load4(const float *__restrict__ row, int64_t off
     }
 }
 
+// The same without bounds checks.
+__device__ __forceinline__ void load4_full(const float *__restrict__ src, float (&x)[4])
+{
+    const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(src));
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+__device__ __forceinline__ void store4_full(float *__restrict__ dst, const float (&x)[4])
+{
+    f4 t;
+    t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
+    __builtin_nontemporal_store(t, reinterpret_cast<f4 *>(dst));
+}
+
 __device__ __forceinline__ void store4(float *__restrict__ row, int64_t off, int64_t len,
                                        const float (&x)[4])
 {
@@ -157,27 +171,11 @@ __device__ __forceinline__ void fill_sxi_table(float *sxi_tab, int s)
 // ---------------------------------------------------------------------------------------------
 // Single pass, buckets of 256 elements or more: a team of W waves per bucket, J float4 per lane.
 // ---------------------------------------------------------------------------------------------
-template <int R, int J, bool UPDATE>
-__global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_shift, const int64_t stripe,
-                                                     const uint32_t blocks_per_row, const uint32_t worker0,
-                                                     const uint32_t workers)
+// The work of one block of k_fused_team.
+template <int R, int J, bool UPDATE, bool FULL>
+__device__ __forceinline__ void fused_team_block(const Args &a, const int w_shift, const uint32_t p,
+                                                 const uint32_t row_block, const float *xi_tab, uint32_t *wave_norm)
 {
-    __shared__ float xi_tab[256];
-    __shared__ uint32_t wave_norm[16];
-    // Block -> (worker row, block of the row).  Workgroups go to the chip's 8 XCDs round-robin
-    // by id.  With stripe > 0 the launch is one-dimensional and XCD x takes the x-th eighth of
-    // all blocks in address order, so each XCD streams through its own contiguous region and
-    // stays compact in memory however far the XCDs drift apart during a long launch.
-    // A launch covers workers worker0 .. worker0 + workers - 1.
-    uint32_t row_block = blockIdx.x, p = worker0 + blockIdx.y;
-    if (stripe > 0) {
-        const int64_t id = (int64_t)(blockIdx.x & 7u) * stripe + (blockIdx.x >> 3);
-        if (id >= (int64_t)blocks_per_row * workers) return;    // whole block
-        const uint32_t row = (uint32_t)(id / blocks_per_row);
-        p = worker0 + row;
-        row_block = (uint32_t)(id - (int64_t)row * blocks_per_row);
-    }
-    if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -186,10 +184,12 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
     const int wit = wave & (W - 1);
     const int teams = blockDim.x >> (6 + w_shift);
     const int64_t k = (int64_t)row_block * teams + team;
-    const bool active = k < a.nb;
+    // FULL: every team of the block owns a complete bucket of exactly W*J*256 elements, so no
+    // load, store or code needs a bounds check.
+    const bool active = FULL || k < a.nb;
     const int64_t e0 = active ? k * (int64_t)a.bucket : 0;
     const int64_t rest = a.n - e0;
-    const int len = active ? (int)(rest < a.bucket ? rest : (int64_t)a.bucket) : 0;
+    const int len = FULL ? a.bucket : (active ? (int)(rest < a.bucket ? rest : (int64_t)a.bucket) : 0);
 
     const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride + e0;
     float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride + e0;
@@ -201,8 +201,13 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const int off = ((wit * J + j) * 64 + lane) * 4;
-        load4(grow, off, len, g[j]);
-        load4(hrow, off, len, h[j]);
+        if constexpr (FULL) {
+            load4_full(grow + off, g[j]);
+            load4_full(hrow + off, h[j]);
+        } else {
+            load4(grow, off, len, g[j]);
+            load4(hrow, off, len, h[j]);
+        }
     }
     uint32_t mx = 0;
 #pragma unroll
@@ -250,19 +255,61 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const int chunk = (wit * J + j) * 256;
-        if (chunk >= len) continue;                            // wave-uniform
+        if (!FULL && chunk >= len) continue;                   // wave-uniform
         const int off = chunk + lane * 4;
         const int64_t elem = e0 + off;
-        int valid = len - off;
-        valid = valid < 0 ? 0 : (valid > 4 ? 4 : valid);
+        int valid = 4;
+        if constexpr (!FULL) {
+            valid = len - off;
+            valid = valid < 0 ? 0 : (valid > 4 ? 4 : valid);
+        }
         const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
         if constexpr (!kKeepV) compensate4(g[j], h[j], a.alpha, v[0]);
         const uint32_t bits =
             quantize4<R, UPDATE>(g[j], h[j], v[kKeepV ? j : 0], valid, rounder, a.beta, words);
         store_codes<R>(crow, a.row_bytes, elem, valid, bits, lane);
-        if (UPDATE) store4(hrow, off, len, h[j]);
+        if constexpr (UPDATE) {
+            if constexpr (FULL) store4_full(hrow + off, h[j]);
+            else store4(hrow, off, len, h[j]);
+        }
     }
     if (active && wit == 0 && lane == 0) a.scales[(int64_t)p * a.scale_stride + k] = scale;
+}
+
+template <int R, int J, bool UPDATE>
+__global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_shift, const int64_t stripe,
+                                                     const uint32_t blocks_per_row, const uint32_t worker0,
+                                                     const uint32_t workers)
+{
+    __shared__ float xi_tab[256];
+    __shared__ uint32_t wave_norm[16];
+    // Block -> (worker row, block of the row).  Workgroups go to the chip's 8 XCDs round-robin
+    // by id.  With stripe > 0 the launch is one-dimensional and XCD x takes the x-th eighth of
+    // all blocks in address order, so each XCD streams through its own contiguous region and
+    // stays compact in memory however far the XCDs drift apart during a long launch.
+    // A launch covers workers worker0 .. worker0 + workers - 1.
+    uint32_t row_block = blockIdx.x, p = worker0 + blockIdx.y;
+    if (stripe > 0) {
+        const int64_t id = (int64_t)(blockIdx.x & 7u) * stripe + (blockIdx.x >> 3);
+        if (id >= (int64_t)blocks_per_row * workers) return;    // whole block
+        const uint32_t row = (uint32_t)(id / blocks_per_row);
+        p = worker0 + row;
+        row_block = (uint32_t)(id - (int64_t)row * blocks_per_row);
+    }
+    if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
+    // Uniform over the block: all of its buckets are complete and exactly fill their teams.
+    const int teams_per_block = blockDim.x >> (6 + w_shift);
+    const bool full = a.bucket == (J * 256 << w_shift) &&
+                      (int64_t)(row_block + 1) * teams_per_block * a.bucket <= a.n;
+    // The check-free path pays where arithmetic is the limit (quantising without the update of
+    // h: +11 %); with the update the kernel waits for memory either way and the smaller code wins.
+    if constexpr (!UPDATE) {
+        if (full) {
+            fused_team_block<R, J, UPDATE, true>(a, w_shift, p, row_block, xi_tab, wave_norm);
+            return;
+        }
+    }
+    fused_team_block<R, J, UPDATE, false>(a, w_shift, p, row_block, xi_tab, wave_norm);
 }
 
 // ---------------------------------------------------------------------------------------------

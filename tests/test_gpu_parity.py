@@ -239,6 +239,16 @@ def test_unfused_equals_fused(E):
     _free_run(E, wl, 3, fused=False)
 
 
+@pytest.mark.parametrize("bucket,s", [(512, 1), (512, 7), (1024, 3), (2048, 1), (8192, 4), (32768, 1)])
+def test_unfused_whole_blocks(E, bucket, s):
+    """ecq_quantize on rows long enough that most blocks hold only complete buckets (the route
+    without bounds checks) followed by a ragged rest, then ecq_error_update."""
+    wl = synth.Workload("edge", P=2, N=5 * max(4096, bucket) + bucket // 2 + 12, bucket=bucket, s=s, alpha=1.0,
+                        beta=0.9, iters=2, kind="normal", data_seed=bucket + s)
+    _free_run(E, wl, 2, fused=False)
+    _free_run(E, wl, 2, fused=True)
+
+
 def test_degenerate_values(E):
     """All-zero buckets, a zero row, negative zeros, denormals, repeated maxima, huge range."""
     P, N, bucket = 4, 4096, 512
