@@ -631,7 +631,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     fill_agg_table<R>(lds.table, a.s);
     if constexpr (R == 2) fill_pair_table(lds.pair, 0);
 
-    constexpr int U = R == 2 ? 4 : 2;                          // workers in flight (register budget)
+    constexpr int U = 4;                                       // workers per batch
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
     base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
@@ -655,26 +655,63 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
 
-    int p = 0;
-    for (; p + U <= a.workers; p += U) {
-        Codes16<R> cd[U];
-        float norm[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            cd[u].load(cptr + u * a.code_stride);
-            norm[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+    if constexpr (R == 2) {
+        // Batches of U workers; the codes and norms of the next batch are requested before the
+        // current one is added, so two batches are in flight.  Workers are added in index order.
+        const int batches = a.workers / U;
+        Codes16<R> cd[U], cd_next[U];
+        float norm[U], norm_next[U];
+        auto request = [&](Codes16<R> (&c)[U], float (&nr)[U]) {
+    #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                c[u].load(cptr + u * a.code_stride);
+                nr[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+            }
+            cptr += U * a.code_stride;
+            srow += U * a.scale_stride;
+        };
+        if (batches > 0) request(cd_next, norm_next);
+        for (int b = 0; b < batches; ++b) {
+    #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                cd[u] = cd_next[u];
+                norm[u] = norm_next[u];
+            }
+            if (b + 1 < batches) request(cd_next, norm_next);
+    #pragma unroll
+            for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);
         }
+        for (int p = batches * U; p < a.workers; ++p) {
+            Codes16<R> one;
+            one.load(cptr);
+            agg_add16<R>(table, pair, lane_off, one, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
+            cptr += a.code_stride;
+            srow += a.scale_stride;
+        }
+    } else {
+        // r > 2: the table lookups want the compiler's unrolled schedule; two workers per step.
+        constexpr int V = 2;
+        int p = 0;
+        for (; p + V <= a.workers; p += V) {
+            Codes16<R> cd[V];
+            float norm[V];
 #pragma unroll
-        for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);   // workers in index order
-        cptr += U * a.code_stride;
-        srow += U * a.scale_stride;
-    }
-    for (; p < a.workers; ++p) {
-        Codes16<R> cd;
-        cd.load(cptr);
-        agg_add16<R>(table, pair, lane_off, cd, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
-        cptr += a.code_stride;
-        srow += a.scale_stride;
+            for (int u = 0; u < V; ++u) {
+                cd[u].load(cptr + u * a.code_stride);
+                norm[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);
+            cptr += V * a.code_stride;
+            srow += V * a.scale_stride;
+        }
+        for (; p < a.workers; ++p) {
+            Codes16<R> one;
+            one.load(cptr);
+            agg_add16<R>(table, pair, lane_off, one, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
+            cptr += a.code_stride;
+            srow += a.scale_stride;
+        }
     }
 
     // Division by P, then lane-major (16 consecutive outputs per lane) -> float4-per-lane order.
