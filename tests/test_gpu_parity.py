@@ -294,6 +294,28 @@ def test_aggregate_worker_counts(E, P, s, bucket):
     _free_run(E, wl, 2)
 
 
+@pytest.mark.parametrize("P,s,bucket", [(13, 1, 512), (16, 1, 8192), (13, 7, 2048), (12, 5, 496)])
+def test_aggregate_many_workers_long_rows(E, P, s, bucket):
+    """Twelve or more workers on rows of more than 2^23 elements (2-, 3- and 4-bit codes):
+    per-lane and per-wave norms, worker counts that are not a multiple of the batch of four,
+    a ragged last run, and the model update fused into the aggregation."""
+    N = (1 << 23) + 3 * 1024 + 500
+    wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="student_t",
+                        data_seed=P + s)
+    st = _free_run(E, wl, 1)
+    codes_ref = st.codes.cpu().numpy()[:, : st.rb]
+    scales_ref = st.scales.cpu().numpy()[:, : st.nb]
+    # (both were just compared bit for bit with the oracle's by _free_run)
+    gavg = oracle.aggregate(codes_ref, scales_ref, N, bucket, s)
+    w0 = np.random.default_rng(P).standard_normal(N).astype(np.float32)
+    eta = float(np.float32(0.05))
+    w_ref = oracle.sgd_step(w0.copy(), gavg, eta)
+    w = _dev(w0)
+    E.ecq_dequant_aggregate_sgd(st.sh, st.codes, st.scales, eta, w, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
 # ------------------------------------------------------------------ model update -----------
 
 @pytest.mark.parametrize("s,bucket,N,P", [(1, 512, 5000, 4), (4, 1024, 3 * 1024 + 77, 3), (3, 24, 1000, 5),
