@@ -25,8 +25,8 @@ namespace ecq {
 constexpr int kTile = ECQ_HUFFMAN_TILE;
 constexpr int kMaxLen = 63;                                    // longest codeword handled
 constexpr int kFastBits = 10;                                  // decode: direct table on 10 stream bits
-constexpr int kBitsTilesPerBlock = 32;                         // pass 1: tiles per block (amortises the table)
-constexpr int kWriteTilesPerWave = 16;                         // pass 3: consecutive tiles per wave
+constexpr int kRunTiles = 16;                                  // encoder: consecutive tiles (one "run") per wave
+constexpr int kRunElems = kRunTiles * ECQ_HUFFMAN_TILE;
 constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
 constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
 
@@ -39,11 +39,35 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Words of LDS a wave needs for one tile when no codeword is longer than max_len bits:
-// 1024 codewords plus the up-to-31-bit shift that aligns the buffer with the stream's words.
-static inline int tile_buffer_words(int max_len) { return (kTile * max_len + 31 + 31) / 32 + 1; }
+// The encoder's waves take a run in steps of 64 lanes x 16*Q elements: Q = 4 (four tiles per
+// step) while codes have at most 4 bits, fewer for wider codes, whose codewords can be longer,
+// so that a step's bits always fit the wave's LDS buffer.
+template <int R>
+constexpr int kStepGroups = R <= 4 ? 4 : (R == 5 ? 2 : 1);
+static inline int step_groups(int r) { return r <= 4 ? 4 : (r == 5 ? 2 : 1); }
 
-static_assert(kTile == 1024, "a wave encodes one tile: 64 lanes x 16 elements");
+// Words of LDS a wave needs for one step when no codeword is longer than max_len bits: the
+// step's codewords plus the up-to-31-bit shift that aligns the buffer with the stream's words.
+static inline int step_buffer_words(int r, int max_len)
+{
+    return (kTile * step_groups(r) * max_len + 31 + 31) / 32 + 1;
+}
+
+static_assert(kTile == 1024, "a step is 64 lanes x 16*Q elements = Q tiles");
+
+// Inclusive prefix sum over the 64 lanes of a wave: four shifts inside each row of 16 lanes,
+// then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.  Lanes without
+// a source add 0.
+__device__ __forceinline__ unsigned int wave_inclusive_scan(unsigned int x)
+{
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, false);   // row_shr:1
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, false);   // row_shr:2
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false);   // row_shr:4
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, false);   // row_shr:8
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false);   // row_bcast:15
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false);   // row_bcast:31
+    return x;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Code construction: one wave per worker row.
@@ -287,80 +311,169 @@ __device__ __forceinline__ void emit_groups(const EncodeTable &tab, const Codes1
     if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
 }
 
-// Pass 1: number of stream bits of every tile.  Sixteen lanes share a tile (a lane owns four
-// runs of 16 elements, 8*R contiguous bytes), so a wave covers four tiles per step and a block
-// 32 tiles in two steps, with all of a lane's loads requested before any is used.
+// The same for rows with a codeword longer than 24 bits: one level at a time from the 63-bit
+// table, in at most two pieces of 32 bits.
 template <int R>
-__global__ void __launch_bounds__(256) k_huffman_tile_bits(const Args a, const uint8_t *__restrict__ lengths,
-                                                          const unsigned long long *__restrict__ codewords,
-                                                          const int64_t table_stride, const int64_t tiles,
-                                                          unsigned long long *__restrict__ tile_offsets,
-                                                          const int64_t offset_stride)
+__device__ __forceinline__ void emit_long(const EncodeTable &tab, const Codes16<R> &cd, int valid, unsigned int pos,
+                                          unsigned int *__restrict__ mine, int words)
 {
-    __shared__ EncodeTable tab;
-    const uint32_t p = blockIdx.y;
-    fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
-    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    constexpr int kSteps = kBitsTilesPerBlock / 16;
-    Codes16<R> cd[kSteps][4];
-    int valid[kSteps][4];
-    int64_t tile[kSteps];
+    int w = (int)(pos >> 5);
+    unsigned long long acc = 0;
+    unsigned int held = pos & 31u;
+#pragma unroll 1
+    for (int e = 0; e < valid; ++e) {
+        unsigned int c = 0;
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
-        tile[i] = (int64_t)blockIdx.x * kBitsTilesPerBlock + i * 16 + (threadIdx.x >> 4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            valid[i][k] = load_lane_codes<R>(crow, a.row_bytes, a.n, tile[i] * kTile + ((threadIdx.x & 15) * 4 + k) * 16,
-                                             cd[i][k]);
+        for (int k = 0; k < 16; ++k) c = k == e ? cd.code(k) : c;
+        unsigned int l = tab.len[c];
+        unsigned long long bits = tab.rev[c];
+        while (l > 0) {
+            const unsigned int piece = l > 32u ? 32u : l;
+            acc |= (bits & ((1ull << piece) - 1ull)) << held;
+            held += piece;
+            bits >>= piece;
+            l -= piece;
+            if (held >= 32u) {
+                if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+                ++w;
+                acc >>= 32;
+                held -= 32u;
+            }
+        }
     }
-#pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
-        unsigned int bits = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) bits += lane_bits<R>(tab, cd[i][k], valid[i][k]);
-        // Sum over the 16 lanes of a tile (one DPP row).
-        bits += dpp_u32<0xB1>(bits);                           // quad_perm [1,0,3,2]
-        bits += dpp_u32<0x4E>(bits);                           // quad_perm [2,3,0,1]
-        bits += dpp_u32<0x141>(bits);                          // row_half_mirror
-        bits += dpp_u32<0x140>(bits);                          // row_mirror
-        if ((threadIdx.x & 15) == 0 && tile[i] < tiles) tile_offsets[(int64_t)p * offset_stride + tile[i]] = bits;
+    if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+}
+
+// Codeword lengths only, for pass 1: per level, and per PAIR of levels (indexed by their 2*R
+// code bits) while codes have at most 4 bits.
+struct LengthTable {
+    unsigned char len[256];
+    unsigned char pair[256];
+};
+
+template <int R>
+__device__ __forceinline__ void fill_length_table(LengthTable &tab, const uint8_t *__restrict__ lengths, int bins)
+{
+    for (int c = threadIdx.x; c < 256; c += blockDim.x) {
+        const int l = c < bins ? lengths[c] : 0;
+        tab.len[c] = (unsigned char)(l > kMaxLen ? kMaxLen : l);
+    }
+    __syncthreads();
+    if constexpr (R <= 4) {
+        for (int idx = threadIdx.x; idx < (1 << (2 * R)); idx += blockDim.x)
+            tab.pair[idx] = (unsigned char)(tab.len[idx & ((1 << R) - 1)] + tab.len[idx >> R]);
+        __syncthreads();
     }
 }
 
-// Pass 2: exclusive prefix sum of the tile sizes of one row (one block per row), in place,
-// 8192 tiles at a time (8 consecutive tiles per thread, the next chunk's sizes already loading
-// while the current one is scanned); entry `tiles` receives the total.  Also clears the 32-bit
-// stream word in which every kWriteTilesPerWave-th tile starts and the one that holds the end of
-// the row: those are the words two waves of pass 3 may share, and they fill them with atomic ORs.
+// Sum of the codeword lengths of a lane's codes from the length table (the same number that
+// lane_bits gives).
+template <int R>
+__device__ __forceinline__ unsigned int lane_bits_of_lengths(const LengthTable &tab, const unsigned int (&len3)[3],
+                                                             const Codes16<R> &cd, int valid)
+{
+    unsigned int bits = 0;
+    if constexpr (R == 2) {
+        const uint32_t x = cd.w[0], lo = x & 0x55555555u, hi = (x >> 1) & 0x55555555u;
+        const unsigned int n1 = __popc(lo & ~hi), n2 = __popc(hi & ~lo), n3 = __popc(hi & lo);
+        bits = (valid - n1 - n2 - n3) * len3[0] + n1 * len3[1] + n2 * len3[2];
+    } else if (R <= 4 && valid == 16) {
+        if constexpr (R <= 4) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) bits += tab.pair[group_index<R, 2>(cd, g)];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bits += e < valid ? tab.len[cd.code(e)] : 0u;
+    }
+    return bits;
+}
+
+// Pass 1: number of stream bits of every run of kRunTiles tiles, one wave per run, written to
+// the run's first entry of tile_offsets.  A lane owns 16*Q consecutive elements of every step,
+// as in pass 3; the loads of several steps are requested before any is used.
+template <int R>
+__global__ void __launch_bounds__(256) k_huffman_run_bits(const Args a, const uint8_t *__restrict__ lengths,
+                                                         const int64_t table_stride, const int64_t tiles,
+                                                         unsigned long long *__restrict__ tile_offsets,
+                                                         const int64_t offset_stride)
+{
+    constexpr int Q = kStepGroups<R>;
+    constexpr int kStepElems = 64 * 16 * Q;
+    constexpr int kSteps = kRunElems / kStepElems;
+    constexpr int kWords = Codes16<R>::kWords;
+    constexpr int kFit = 32 / (Q * kWords);                    // steps whose codes fit 32 registers
+    constexpr int kBatch = kFit >= kSteps ? kSteps : (kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1)));
+    __shared__ LengthTable tab;
+    const uint32_t p = blockIdx.y;
+    fill_length_table<R>(tab, lengths + (int64_t)p * table_stride, 2 * a.s + 1);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kRunTiles;
+    if (first >= tiles) return;                                // wave-uniform; no barrier follows
+    const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
+    const unsigned int len3[3] = {tab.len[0], tab.len[1], tab.len[2]};
+    unsigned int bits = 0;
+#pragma unroll 1
+    for (int s0 = 0; s0 < kSteps; s0 += kBatch) {
+        Codes16<R> cd[kBatch][Q];
+        int valid[kBatch][Q];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+                valid[i][q] = load_lane_codes<R>(crow, a.row_bytes, a.n,
+                                                 first * kTile + (int64_t)(s0 + i) * kStepElems + (lane * Q + q) * 16,
+                                                 cd[i][q]);
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) bits += lane_bits_of_lengths<R>(tab, len3, cd[i][q], valid[i][q]);
+    }
+    // Sum over the wave; a lane's total stays below 2^32 (16384 elements x 63 bits).
+    bits += dpp_u32<0xB1>(bits);                               // quad_perm [1,0,3,2]
+    bits += dpp_u32<0x4E>(bits);                               // quad_perm [2,3,0,1]
+    bits += dpp_u32<0x141>(bits);                              // row_half_mirror
+    bits += dpp_u32<0x140>(bits);                              // row_mirror
+    const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)bits, 0) +
+                               (unsigned int)__builtin_amdgcn_readlane((int)bits, 16) +
+                               (unsigned int)__builtin_amdgcn_readlane((int)bits, 32) +
+                               (unsigned int)__builtin_amdgcn_readlane((int)bits, 48);
+    if (lane == 0) tile_offsets[(int64_t)p * offset_stride + first] = total;
+}
+
+// Pass 2: exclusive prefix sum of the run sizes of one row (one block per row), in place in the
+// runs' first entries of tile_offsets, 2048 runs at a time with the next chunk's sizes already
+// loading; entry `tiles` receives the total.  Also clears the 32-bit stream word in which every
+// run starts and the one that holds the end of the row: those are the words two waves of pass 3
+// may share, and they fill them with atomic ORs.
 __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__restrict__ tile_offsets,
                                                       const int64_t offset_stride, const int64_t tiles,
                                                       uint32_t *__restrict__ streams, const int64_t stream_words,
                                                       const int64_t stream_stride_words)
 {
-    constexpr int K = 8;
+    constexpr int K = 2;
     __shared__ unsigned long long wave_total[2][16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t runs = (tiles + kRunTiles - 1) / kRunTiles;
     unsigned long long *__restrict__ row = tile_offsets + (int64_t)blockIdx.x * offset_stride;
     uint32_t *__restrict__ out = streams + (int64_t)blockIdx.x * stream_stride_words;
-    unsigned long long carry = 0, v[K], nxt[K];
+    unsigned long long carry = 0;
+    unsigned int v[K], nxt[K];                                 // a run has fewer than 2^32 bits
 #pragma unroll
-    for (int k = 0; k < K; ++k) nxt[k] = (int64_t)tid * K + k < tiles ? row[(int64_t)tid * K + k] : 0ull;
+    for (int k = 0; k < K; ++k) nxt[k] = (int64_t)tid * K + k < runs ? (unsigned int)row[((int64_t)tid * K + k) * kRunTiles] : 0u;
     int parity = 0;
-    for (int64_t base = 0; base < tiles; base += 1024 * K, parity ^= 1) {
+    for (int64_t base = 0; base < runs; base += 1024 * K, parity ^= 1) {
         const int64_t i0 = base + (int64_t)tid * K;
-        unsigned long long mine = 0;
+        unsigned int mine = 0;                                 // a wave's 128 runs: fewer than 2^32 bits
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             v[k] = nxt[k];
             mine += v[k];
             const int64_t ahead = i0 + 1024 * K + k;
-            nxt[k] = ahead < tiles ? row[ahead] : 0ull;
+            nxt[k] = ahead < runs ? (unsigned int)row[ahead * kRunTiles] : 0u;
         }
-        unsigned long long incl = mine;
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned long long up = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += up;
-        }
+        const unsigned int incl = wave_inclusive_scan(mine);
         if (lane == 63) wave_total[parity][wave] = incl;
         __syncthreads();                                       // one barrier per chunk: the totals alternate buffers
         unsigned long long before = carry, all = 0;
@@ -373,10 +486,10 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
         unsigned long long off = before + (incl - mine);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            if (i0 + k < tiles) {
-                row[i0 + k] = off;
+            if (i0 + k < runs) {
+                row[(i0 + k) * kRunTiles] = off;
                 const unsigned long long word = off >> 5;
-                if ((i0 + k) % kWriteTilesPerWave == 0 && word < (unsigned long long)stream_words) out[word] = 0u;
+                if (word < (unsigned long long)stream_words) out[word] = 0u;
             }
             off += v[k];
         }
@@ -389,126 +502,127 @@ __global__ void __launch_bounds__(1024) k_huffman_scan(unsigned long long *__res
     }
 }
 
-// Pass 3: a wave walks kWriteTilesPerWave consecutive tiles.  It assembles the bits of a tile
-// in LDS, aligned with the 32-bit words of the stream, then stores the words with plain
-// coalesced stores; a partial last word is carried into the next tile, and only the first and
-// last word of the whole run (which a neighbouring wave may share) are filled with atomic ORs.
-// buf_words = LDS words per wave: enough for 1024 codewords of the longest length a code over
-// 2s+1 levels can have (2s bits); longer tiles (only possible with a table that does not
+// Pass 3: a wave walks one run (kRunTiles consecutive tiles) in steps of Q tiles.  Per step a
+// lane sums the codeword lengths of its 16*Q consecutive elements, a wave prefix sum places
+// them, the lanes assemble the step's bits in LDS aligned with the 32-bit words of the stream,
+// and the words leave with plain coalesced stores; a partial last word is carried into the next
+// step, and only the first and last word of the whole run (which a neighbouring wave may share)
+// are filled with atomic ORs.  The position inside the run is the wave's own running sum, and
+// the lanes at tile boundaries record it as the tile's offset.
+// buf_words = LDS words per wave: enough for a step's codewords of the longest length a code
+// over 2s+1 levels can have (2s bits); longer steps (only possible with a table that does not
 // belong to the message) are cut off.
 template <int R>
 __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8_t *__restrict__ lengths,
                                                       const unsigned long long *__restrict__ codewords,
                                                       const int64_t table_stride, const int64_t tiles,
-                                                      const unsigned long long *__restrict__ tile_offsets,
+                                                      unsigned long long *__restrict__ tile_offsets,
                                                       const int64_t offset_stride, uint32_t *__restrict__ streams,
                                                       const int64_t stream_words, const int64_t stream_stride_words,
                                                       const int buf_words)
 {
+    constexpr int Q = kStepGroups<R>;
+    constexpr int kStepElems = 64 * 16 * Q;
+    constexpr int kSteps = kRunElems / kStepElems;
+    constexpr int kLanesPerTile = 64 / Q;
     __shared__ EncodeTable tab;
-    extern __shared__ unsigned int tile_buf[];
+    extern __shared__ unsigned int step_buf[];
     const uint32_t p = blockIdx.y;
     fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    unsigned int *__restrict__ mine = tile_buf + wave * buf_words;
+    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kRunTiles;
+    if (first >= tiles) return;                                // wave-uniform; no block barrier follows
+    unsigned int *__restrict__ mine = step_buf + wave * buf_words;
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    const unsigned long long *__restrict__ offs = tile_offsets + (int64_t)p * offset_stride;
+    unsigned long long *__restrict__ offs = tile_offsets + (int64_t)p * offset_stride;
     uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
-    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kWriteTilesPerWave;
+    for (int j = lane; j < buf_words; j += 64) mine[j] = 0u;
+    wave_lds_sync();
 
-    // The offsets of the wave's tiles are fetched up front (lane i holds entry first + i); the
-    // codes of a tile are requested while the tile before it is being assembled.
-    const unsigned long long my_off = (lane <= kWriteTilesPerWave && first + lane <= tiles) ? offs[first + lane] : 0ull;
-    Codes16<R> cd, cd_next;
-    int valid, valid_next = load_lane_codes<R>(crow, a.row_bytes, a.n, first * kTile + lane * 16, cd_next);
-
-    unsigned int carry = 0;                                    // partial last word of the tile before (wave-uniform)
-#pragma unroll 1
-    for (int i = 0; i < kWriteTilesPerWave; ++i) {
-        const int64_t tile = first + i;
-        if (tile >= tiles) break;                              // wave-uniform
-        cd = cd_next;
-        valid = valid_next;
-        valid_next = load_lane_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kTile + lane * 16, cd_next);
-        const unsigned long long start = __shfl(my_off, i, 64);
-        unsigned long long end = __shfl(my_off, i + 1, 64);
-        if (end < start) end = start;
-        const unsigned int shift = (unsigned int)(start & 31ull);
-        const unsigned long long word0 = start >> 5;
-        const unsigned long long span = ((end - start) + shift + 31ull) >> 5;
-        const int words = (int)(span < (unsigned long long)buf_words ? span : (unsigned long long)buf_words);
-        for (int j = lane; j < words; j += 64) mine[j] = 0u;
-        wave_lds_sync();
-
-        const unsigned int nbits = lane_bits<R>(tab, cd, valid);
-        unsigned int incl = nbits;
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned int up = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += up;
-        }
-        // Bit position of this lane's first codeword in the wave's buffer.
-        const unsigned int pos = shift + (incl - nbits);
-        if (tab.all_short) {
-            const int k = valid == 16 ? tab.group_k : 1;
-            if (R <= 2 && k == 4) {
-                if constexpr (R <= 2) emit_groups<R, 4>(tab, cd, valid, pos, mine, words);
-            } else if (R <= 4 && k == 2) {
-                if constexpr (R <= 4) emit_groups<R, 2>(tab, cd, valid, pos, mine, words);
-            } else {
-                emit_groups<R, 1>(tab, cd, valid, pos, mine, words);
-            }
-        } else {
-            int w = (int)(pos >> 5);
-            unsigned long long acc = 0;
-            unsigned int held = pos & 31u;
-#pragma unroll 1
-            for (int e = 0; e < valid; ++e) {
-                unsigned int c = 0;
+    const unsigned long long run_start = offs[first];          // bit offset of the run (pass 2)
+    unsigned long long pos = run_start;                        // ... and of the current step
+    unsigned int carry = 0;                                    // partial last word of the step before
+    const int64_t elem0 = first * kTile + (int64_t)lane * (16 * Q);
+    Codes16<R> cd[Q], cd_next[Q];
+    int valid[Q], valid_next[Q];
 #pragma unroll
-                for (int k = 0; k < 16; ++k) c = k == e ? cd.code(k) : c;
-                unsigned int l = tab.len[c];
-                unsigned long long bits = tab.rev[c];
-                while (l > 0) {                                // at most two pieces of <= 32 bits
-                    const unsigned int piece = l > 32u ? 32u : l;
-                    acc |= (bits & ((1ull << piece) - 1ull)) << held;
-                    held += piece;
-                    bits >>= piece;
-                    l -= piece;
-                    if (held >= 32u) {
-                        if (w < words) atomicOr(&mine[w], (unsigned int)acc);
-                        ++w;
-                        acc >>= 32;
-                        held -= 32u;
-                    }
+    for (int q = 0; q < Q; ++q) valid_next[q] = load_lane_codes<R>(crow, a.row_bytes, a.n, elem0 + q * 16, cd_next[q]);
+
+#pragma unroll 1
+    for (int step = 0; step < kSteps; ++step) {
+        const int64_t step_first = first * kTile + (int64_t)step * kStepElems;
+        if (step_first >= a.n) break;                          // wave-uniform
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            cd[q] = cd_next[q];
+            valid[q] = valid_next[q];
+            valid_next[q] = load_lane_codes<R>(crow, a.row_bytes, a.n, elem0 + (int64_t)(step + 1) * kStepElems + q * 16,
+                                               cd_next[q]);
+        }
+        unsigned int nb[Q], nbits = 0;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            nb[q] = lane_bits<R>(tab, cd[q], valid[q]);
+            nbits += nb[q];
+        }
+        const unsigned int incl = wave_inclusive_scan(nbits);
+        const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)incl, 63);
+        const unsigned int excl = incl - nbits;
+        // Tile offsets inside the run (the run's first one is pass 2's).
+        if ((lane & (kLanesPerTile - 1)) == 0 && (step > 0 || lane > 0)) {
+            const int64_t tile = first + step * Q + lane / kLanesPerTile;
+            if (tile < tiles) offs[tile] = pos + excl;
+        }
+        const unsigned int shift = (unsigned int)(pos & 31ull);
+        const unsigned long long word0 = pos >> 5;
+        const unsigned long long end = pos + total;
+        const unsigned int span = (total + shift + 31u) >> 5;
+        const int words = (int)(span < (unsigned int)buf_words ? span : (unsigned int)buf_words);
+
+        unsigned int at = shift + excl;                        // buffer bit of the lane's next codeword
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (tab.all_short) {
+                const int k = valid[q] == 16 ? tab.group_k : 1;
+                if (R <= 2 && k == 4) {
+                    if constexpr (R <= 2) emit_groups<R, 4>(tab, cd[q], valid[q], at, mine, words);
+                } else if (R <= 4 && k == 2) {
+                    if constexpr (R <= 4) emit_groups<R, 2>(tab, cd[q], valid[q], at, mine, words);
+                } else {
+                    emit_groups<R, 1>(tab, cd[q], valid[q], at, mine, words);
                 }
+            } else {
+                emit_long<R>(tab, cd[q], valid[q], at, mine, words);
             }
-            if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+            at += nb[q];
         }
         wave_lds_sync();
 
-        // Words wholly inside the wave's run of tiles leave with plain stores.  The last word of
-        // a tile, when partial, is carried into the first word of the wave's next tile; only the
-        // two ends of the run (words another wave may share) use atomic ORs.
-        const bool final_tile = i == kWriteTilesPerWave - 1 || tile + 1 >= tiles;
+        // Words wholly inside the run leave with plain stores and their buffer word is cleared
+        // for the next step.  The last word of a step, when partial, is carried into the first
+        // word of the next step; only the two ends of the run use atomic ORs.
+        const bool final_step = step == kSteps - 1 || step_first + kStepElems >= a.n;
         const bool has_tail = (end & 31ull) != 0ull;
         if (words > 0) {
+            unsigned int tail = mine[words - 1];               // same address for all lanes
+            if (words == 1) tail |= carry;
             for (int j = lane; j < words; j += 64) {
+                unsigned int value = mine[j];
+                mine[j] = 0u;
+                if (j == 0) value |= carry;
                 const unsigned long long gw = word0 + (unsigned long long)j;
                 if (gw >= (unsigned long long)stream_words) continue;
-                unsigned int value = mine[j];
-                if (j == 0 && i > 0) value |= carry;
-                const bool lower_ok = i > 0 || gw * 32ull >= start;
+                const bool lower_ok = gw * 32ull >= run_start;
                 const bool upper_ok = (gw + 1ull) * 32ull <= end;
                 if (lower_ok && upper_ok) out[gw] = value;
-                else if (lower_ok && !final_tile) continue;    // carried below
+                else if (!upper_ok && !final_step) continue;   // carried below
                 else if (value) atomicOr(&out[gw], value);
             }
-            unsigned int tail = has_tail && !final_tile ? mine[words - 1] : 0u;
-            if (has_tail && !final_tile && words == 1 && i > 0) tail |= carry;
-            carry = tail;
+            carry = has_tail && !final_step ? tail : 0u;
         }
-        wave_lds_sync();                                       // the buffer is cleared again for the next tile
+        wave_lds_sync();                                       // the buffer is clear again for the next step
+        pos = end;
     }
 }
 
@@ -746,20 +860,19 @@ hipError_t launch_huffman_encode(const Args &a, const uint8_t *lengths, const un
 {
     const int64_t tiles = (a.n + kTile - 1) / kTile;
     const int64_t stream_words = stream_stride_words;
-    const dim3 grid_bits(cdiv(tiles, kBitsTilesPerBlock), (unsigned)a.workers);
+    const dim3 grid_runs(cdiv(tiles, 4 * kRunTiles), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_tile_bits<RR>), grid_bits, dim3(256), 0, stream, a, lengths, codewords,        \
-                       table_stride, tiles, tile_offsets, offset_stride)
+    hipLaunchKernelGGL((k_huffman_run_bits<RR>), grid_runs, dim3(256), 0, stream, a, lengths, table_stride,      \
+                       tiles, tile_offsets, offset_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     hipLaunchKernelGGL(k_huffman_scan, dim3((unsigned)a.workers), dim3(1024), 0, stream, tile_offsets, offset_stride,
                        tiles, streams, stream_words, stream_stride_words);
     // A prefix code over 2s+1 levels has no codeword longer than 2s bits.
     const int max_len = 2 * a.s < kMaxLen ? 2 * a.s : kMaxLen;
-    const int buf_words = tile_buffer_words(max_len);
-    const dim3 grid_write(cdiv(tiles, 4 * kWriteTilesPerWave), (unsigned)a.workers);
+    const int buf_words = step_buffer_words(a.r, max_len);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_write<RR>), grid_write, dim3(256), 4 * buf_words * sizeof(unsigned int),       \
+    hipLaunchKernelGGL((k_huffman_write<RR>), grid_runs, dim3(256), 4 * buf_words * sizeof(unsigned int),        \
                        stream, a, lengths, codewords, table_stride, tiles, tile_offsets, offset_stride, streams, \
                        stream_words, stream_stride_words, buf_words)
     ECQ_DISPATCH_R(a.r, CALL)
