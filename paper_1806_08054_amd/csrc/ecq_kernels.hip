@@ -754,27 +754,35 @@ __global__ void __launch_bounds__(256) k_zero_counts(unsigned long long *counts,
     if ((int)threadIdx.x < bins) counts[(int64_t)blockIdx.x * count_stride + threadIdx.x] = 0ull;
 }
 
-// A lane owns runs of 16 elements (2*R bytes, one aligned load); a block walks kHistPerBlock
-// elements of one row, counts into LDS and adds its totals to the row's counters once.
+// A lane owns four consecutive runs of 16 elements (8*R contiguous bytes); a block walks chunks
+// of kHistPerBlock elements of one row, counts into registers or LDS and adds its totals to the
+// row's counters once.
 //   r = 2: the three levels are counted with bit masks and population counts, 16 codes at a
 //          time, in registers.
+//   r = 3, 4: every thread has a private set of 16 counters in LDS (17 words apart, so that
+//          lanes counting the same level hit 64 different banks) and sends one LDS add per
+//          element, without waiting for it.
 //   else : level 0 (code s), by far the most frequent, is counted in a register; the other
-//          codes go to LDS counters: one private set per thread while there are at most 16
-//          levels (no two lanes ever meet on an address), else one histogram per wave with
-//          atomic adds.
+//          codes go to one histogram per wave with LDS atomic adds.
+// Few, long-lived blocks: all blocks of a row end in the same 2s+1 global counters, and atomic
+// adds to one address are served one at a time (about 80 ns each on this chip).
+constexpr int kHistThreads = 512;
 constexpr int kHistIters = 2;
 constexpr int kHistGroups = 4;                                 // runs of 16 elements a lane loads together
-constexpr int kHistPerBlock = 256 * 16 * kHistGroups * kHistIters;
+constexpr int kHistPerBlock = kHistThreads * 16 * kHistGroups * kHistIters;
+constexpr int kHistBlocks = 768;                               // target for the whole grid: three per CU
 
 template <int R>
-__global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned long long *__restrict__ counts,
-                                                        const int64_t count_stride)
+__global__ void __launch_bounds__(kHistThreads) k_level_histogram(const Args a,
+                                                                 unsigned long long *__restrict__ counts,
+                                                                 const int64_t count_stride)
 {
     constexpr bool kPrivate = R > 2 && R <= 4;                 // at most 16 levels
-    constexpr int kPrivStride = 17;                            // odd: spreads the threads' sets over the banks
-    __shared__ unsigned int hist[4][256];
-    __shared__ unsigned int priv[kPrivate ? 256 * kPrivStride : 1];
-    for (int c = threadIdx.x; c < 4 * 256; c += blockDim.x) (&hist[0][0])[c] = 0u;
+    constexpr int kPrivStride = 17;
+    constexpr int kWaves = kHistThreads / 64;
+    __shared__ unsigned int hist[kWaves][256];
+    __shared__ unsigned int priv[kPrivate ? kHistThreads * kPrivStride : 1];
+    for (int c = threadIdx.x; c < kWaves * 256; c += blockDim.x) (&hist[0][0])[c] = 0u;
     if constexpr (kPrivate)
         for (int c = 0; c < kPrivStride; ++c) priv[threadIdx.x * kPrivStride + c] = 0u;
     __syncthreads();
@@ -783,28 +791,31 @@ __global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned int *__restrict__ my_priv = priv + (kPrivate ? threadIdx.x * kPrivStride : 0);
     unsigned int n_center = 0, n1 = 0, n2 = 0, n3 = 0, n_valid = 0;
-    // The blocks of a row take its chunks of kHistPerBlock elements round robin: few blocks per
-    // row, because their totals meet in the same handful of global counters.
+    // The blocks of a row take its chunks of kHistPerBlock elements round robin.
     for (int64_t begin = (int64_t)blockIdx.x * kHistPerBlock; begin < a.n; begin += (int64_t)gridDim.x * kHistPerBlock)
 #pragma unroll
     for (int it = 0; it < kHistIters; ++it) {
-        // A lane's four runs are contiguous: 8*R bytes per lane, 512*R per wave.
-        const int64_t elem0 = begin + ((int64_t)it * 256 + threadIdx.x) * (16 * kHistGroups);
+        const int64_t elem0 = begin + ((int64_t)it * kHistThreads + threadIdx.x) * (16 * kHistGroups);
         Codes16<R> cd[kHistGroups];
         int valid[kHistGroups];
+        if (elem0 + 16 * kHistGroups <= a.n) {                 // the common case: one contiguous piece
+            const uint8_t *__restrict__ src = crow + ((elem0 * R) >> 3);
 #pragma unroll
-        for (int k = 0; k < kHistGroups; ++k) {
-            const int64_t elem = elem0 + 16 * k;
-            if (elem + 16 <= a.n) {
-                cd[k].load(crow + ((elem * R) >> 3));
+            for (int k = 0; k < kHistGroups; ++k) {
+                cd[k].load(src + k * 2 * R);
                 valid[k] = 16;
-            } else if (elem < a.n) {
-                cd[k].load_guarded(crow, a.row_bytes, elem);
-                valid[k] = (int)(a.n - elem);
-            } else {
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kHistGroups; ++k) {
+                const int64_t elem = elem0 + 16 * k;
 #pragma unroll
                 for (int i = 0; i < Codes16<R>::kWords; ++i) cd[k].w[i] = 0u;
                 valid[k] = 0;
+                if (elem < a.n) {
+                    cd[k].load_guarded(crow, a.row_bytes, elem);
+                    valid[k] = (int)(a.n - elem < 16 ? a.n - elem : 16);
+                }
             }
         }
 #pragma unroll
@@ -816,13 +827,21 @@ __global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned 
                 n2 += __popc(hi & ~lo);
                 n3 += __popc(hi & lo);
                 n_valid += valid[k];
+            } else if constexpr (kPrivate) {
+                if (valid[k] == 16) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) atomicAdd(&my_priv[cd[k].code(e)], 1u);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (e < valid[k]) atomicAdd(&my_priv[cd[k].code(e)], 1u);
+                }
             } else {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const unsigned int c = cd[k].code(e);
                     if (e < valid[k]) {
                         if (c == (unsigned int)a.s) ++n_center;
-                        else if constexpr (kPrivate) my_priv[c] += 1u;
                         else atomicAdd(&hist[wave][c], 1u);
                     }
                 }
@@ -841,22 +860,22 @@ __global__ void __launch_bounds__(256) k_level_histogram(const Args a, unsigned 
             hist[wave][1] = n1;
             hist[wave][2] = n2;
         }
+    } else if constexpr (kPrivate) {
+        __syncthreads();
+        // Thread (c, part) adds up level c over 16 of the block's private sets.
+        const int c = threadIdx.x & 15, part = threadIdx.x >> 4;
+        unsigned int sum = 0;
+        for (int t = part * 16; t < part * 16 + 16; ++t) sum += priv[t * kPrivStride + c];
+        if (sum) atomicAdd(&hist[0][c], sum);
     } else {
         for (int d = 1; d < 64; d <<= 1) n_center += __shfl_xor(n_center, d, 64);
         if (lane == 0 && n_center) atomicAdd(&hist[wave][a.s], n_center);
-        if constexpr (kPrivate) {
-            __syncthreads();
-            // Thread (c, part) adds up level c over a sixteenth of the block's private sets.
-            const int c = threadIdx.x & 15, part = threadIdx.x >> 4;
-            unsigned int sum = 0;
-            for (int t = part * 16; t < part * 16 + 16; ++t) sum += priv[t * kPrivStride + c];
-            if (sum) atomicAdd(&hist[0][c], sum);
-        }
     }
     __syncthreads();
     const int bins = 2 * a.s + 1;
     for (int c = threadIdx.x; c < bins; c += blockDim.x) {
-        const unsigned int total = (hist[0][c] + hist[1][c]) + (hist[2][c] + hist[3][c]);
+        unsigned int total = 0;
+        for (int w = 0; w < kWaves; ++w) total += hist[w][c];
         if (total) atomicAdd(&counts[(int64_t)p * count_stride + c], (unsigned long long)total);
     }
 }
@@ -1055,12 +1074,12 @@ hipError_t launch_level_histogram(const Args &a, unsigned long long *counts, int
                                   hipStream_t stream)
 {
     hipLaunchKernelGGL(k_zero_counts, dim3((unsigned)a.workers), dim3(256), 0, stream, counts, count_stride, 2 * a.s + 1);
-    // Enough blocks to fill the chip a few times over all rows, at most 256 per row.
+    // About kHistBlocks blocks over all rows, each walking its share of a row.
     unsigned per_row = cdiv(a.n, kHistPerBlock);
-    const unsigned want = cdiv(4096, a.workers);
-    if (per_row > want) per_row = want > 256 ? 256 : want;
+    const unsigned want = cdiv(kHistBlocks, a.workers);
+    if (per_row > want) per_row = want;
     const dim3 grid(per_row, (unsigned)a.workers);
-#define CALL(RR) hipLaunchKernelGGL((k_level_histogram<RR>), grid, dim3(256), 0, stream, a, counts, count_stride)
+#define CALL(RR) hipLaunchKernelGGL((k_level_histogram<RR>), grid, dim3(kHistThreads), 0, stream, a, counts, count_stride)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
