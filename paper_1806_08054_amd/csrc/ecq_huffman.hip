@@ -250,6 +250,25 @@ __device__ __forceinline__ int load_lane_codes(const uint8_t *__restrict__ crow,
     return (int)rest;
 }
 
+// The same for the Q consecutive runs of 16 elements a lane owns in one encoder step: when all
+// of them exist they are one contiguous piece of 2*R*Q bytes.
+template <int R, int Q>
+__device__ __forceinline__ void load_lane_step(const uint8_t *__restrict__ crow, int64_t row_bytes, int64_t n,
+                                               int64_t elem, Codes16<R> (&cd)[Q], int (&valid)[Q])
+{
+    if (elem + 16 * Q <= n) {
+        const uint8_t *__restrict__ src = crow + ((elem * R) >> 3);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            cd[q].load(src + q * 2 * R);
+            valid[q] = 16;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) valid[q] = load_lane_codes<R>(crow, row_bytes, n, elem + 16 * q, cd[q]);
+    }
+}
+
 // The K*R code bits of group g (elements g*K .. g*K+K-1) of a lane's 16 codes.
 template <int R, int K>
 __device__ __forceinline__ unsigned int group_index(const Codes16<R> &cd, int g)
@@ -301,6 +320,36 @@ __device__ __forceinline__ void emit_groups(const EncodeTable &tab, const Codes1
         else entry = tab.group[group_index<R, K>(cd, g)];
         acc |= (unsigned long long)(entry & 0xFFFFFFu) << held;
         held += entry >> 24;
+        if (held >= 32u) {
+            if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+            ++w;
+            acc >>= 32;
+            held -= 32u;
+        }
+    }
+    if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+}
+
+// Three levels (r = 2) and no codeword longer than 2 bits -- every code built from the counts of
+// a ternary message: the 16 codewords of a run fit 32 bits, so four group entries are joined in
+// a register and the accumulator is checked once per run instead of once per entry.
+template <int Q>
+__device__ __forceinline__ void emit_ternary(const EncodeTable &tab, const Codes16<2> (&cd)[Q], unsigned int pos,
+                                             unsigned int *__restrict__ mine, int words)
+{
+    int w = (int)(pos >> 5);
+    unsigned long long acc = 0;
+    unsigned int held = pos & 31u;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const uint32_t x = cd[q].w[0];
+        const unsigned int e0 = tab.group[x & 0xFFu], e1 = tab.group[(x >> 8) & 0xFFu];
+        const unsigned int e2 = tab.group[(x >> 16) & 0xFFu], e3 = tab.group[x >> 24];
+        const unsigned int l0 = e0 >> 24, l1 = l0 + (e1 >> 24), l2 = l1 + (e2 >> 24), l3 = l2 + (e3 >> 24);
+        const unsigned int chunk = (e0 & 0xFFFFFFu) | ((e1 & 0xFFFFFFu) << l0) | ((e2 & 0xFFFFFFu) << l1) |
+                                   ((e3 & 0xFFFFFFu) << l2);
+        acc |= (unsigned long long)chunk << held;
+        held += l3;
         if (held >= 32u) {
             if (w < words) atomicOr(&mine[w], (unsigned int)acc);
             ++w;
@@ -420,11 +469,8 @@ __global__ void __launch_bounds__(256) k_huffman_run_bits(const Args a, const ui
         int valid[kBatch][Q];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
-#pragma unroll
-            for (int q = 0; q < Q; ++q)
-                valid[i][q] = load_lane_codes<R>(crow, a.row_bytes, a.n,
-                                                 first * kTile + (int64_t)(s0 + i) * kStepElems + (lane * Q + q) * 16,
-                                                 cd[i][q]);
+            load_lane_step<R, Q>(crow, a.row_bytes, a.n, first * kTile + (int64_t)(s0 + i) * kStepElems + lane * (16 * Q),
+                                 cd[i], valid[i]);
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
 #pragma unroll
@@ -546,8 +592,7 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
     const int64_t elem0 = first * kTile + (int64_t)lane * (16 * Q);
     Codes16<R> cd[Q], cd_next[Q];
     int valid[Q], valid_next[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) valid_next[q] = load_lane_codes<R>(crow, a.row_bytes, a.n, elem0 + q * 16, cd_next[q]);
+    load_lane_step<R, Q>(crow, a.row_bytes, a.n, elem0, cd_next, valid_next);
 
 #pragma unroll 1
     for (int step = 0; step < kSteps; ++step) {
@@ -557,9 +602,8 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         for (int q = 0; q < Q; ++q) {
             cd[q] = cd_next[q];
             valid[q] = valid_next[q];
-            valid_next[q] = load_lane_codes<R>(crow, a.row_bytes, a.n, elem0 + (int64_t)(step + 1) * kStepElems + q * 16,
-                                               cd_next[q]);
         }
+        load_lane_step<R, Q>(crow, a.row_bytes, a.n, elem0 + (int64_t)(step + 1) * kStepElems, cd_next, valid_next);
         unsigned int nb[Q], nbits = 0;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
@@ -581,8 +625,19 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
         const int words = (int)(span < (unsigned int)buf_words ? span : (unsigned int)buf_words);
 
         unsigned int at = shift + excl;                        // buffer bit of the lane's next codeword
+        bool done = false;
+        if constexpr (R == 2) {
+            bool whole = true;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) whole = whole && valid[q] == 16;
+            if (tab.max_len <= 2u && whole) {
+                emit_ternary<Q>(tab, cd, at, mine, words);
+                done = true;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
+            if (done) break;
             if (tab.all_short) {
                 const int k = valid[q] == 16 ? tab.group_k : 1;
                 if (R <= 2 && k == 4) {
