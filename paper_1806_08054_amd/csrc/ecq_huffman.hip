@@ -788,12 +788,22 @@ __global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint
     // Bit reservoir: `have` valid bits, the next stream bit is bit 0.  Stream words arrive four
     // at a time and a whole batch ahead of their use, so the chain below waits for memory at
     // most once per 128 stream bits, for loads issued 128 bits earlier.
+    // Indices are clamped to the row's last word instead of being tested one by one: a message
+    // never reads past its own end, and anything else only has to stay inside the row.
+    const unsigned long long last_word = (unsigned long long)stream_words - 1ull;
     auto fetch4 = [&]() -> uint4 {
         uint4 b;
-        b.x = next_word + 0 < (unsigned long long)stream_words ? in[next_word + 0] : 0u;
-        b.y = next_word + 1 < (unsigned long long)stream_words ? in[next_word + 1] : 0u;
-        b.z = next_word + 2 < (unsigned long long)stream_words ? in[next_word + 2] : 0u;
-        b.w = next_word + 3 < (unsigned long long)stream_words ? in[next_word + 3] : 0u;
+        if (next_word + 3 <= last_word) {
+            b.x = in[next_word + 0];
+            b.y = in[next_word + 1];
+            b.z = in[next_word + 2];
+            b.w = in[next_word + 3];
+        } else {
+            b.x = in[next_word + 0 < last_word ? next_word + 0 : last_word];
+            b.y = in[next_word + 1 < last_word ? next_word + 1 : last_word];
+            b.z = in[next_word + 2 < last_word ? next_word + 2 : last_word];
+            b.w = in[next_word + 3 < last_word ? next_word + 3 : last_word];
+        }
         next_word += 4;
         return b;
     };
@@ -846,7 +856,10 @@ __global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint
         out_byte += 4 * count;
     };
     while (remaining > 0) {
-        refill();                                              // have >= 33 from here
+      refill();                                                // have >= 33 here: enough for three lookups
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        if (remaining <= 0 || have < (unsigned int)kFastBits) break;   // (a long codeword may have used more)
         const unsigned int m = tab.multi[(unsigned int)res & ((1u << kFastBits) - 1u)];
         const unsigned int syms = m >> 24;
         if (syms != 0u && (int)syms <= remaining) {
@@ -882,15 +895,18 @@ __global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint
             out_held += R;
             --remaining;
         }
-        if (out_held >= 32u) {
-            ring[ring_at] = (unsigned int)out_acc;
-            out_acc >>= 32;
-            out_held -= 32u;
-            if (++ring_at == kRingWords) {                      // 64 bytes of codes: send them off together
-                flush_ring(kRingWords);
-                ring_at = 0;
-            }
+        // The low word goes to the ring's next slot whether it is complete or not; the slot is
+        // only given up once it is.
+        const bool full = out_held >= 32u;
+        ring[ring_at] = (unsigned int)out_acc;
+        out_acc = full ? out_acc >> 32 : out_acc;
+        out_held -= full ? 32u : 0u;
+        ring_at += full ? 1 : 0;
+        if (ring_at == kRingWords) {                            // 64 bytes of codes: send them off together
+            flush_ring(kRingWords);
+            ring_at = 0;
         }
+      }
     }
     // What is left of a ragged last tile: whole words, then fewer than 32 bits (pad bits zero).
     flush_ring(ring_at);
