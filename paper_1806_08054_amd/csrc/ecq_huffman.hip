@@ -27,6 +27,7 @@ constexpr int kMaxLen = 63;                                    // longest codewo
 constexpr int kFastBits = 10;                                  // decode: direct table on 10 stream bits
 constexpr int kRunTiles = 16;                                  // encoder: consecutive tiles (one "run") per wave
 constexpr int kRunElems = kRunTiles * ECQ_HUFFMAN_TILE;
+constexpr int kDecodeThreads = 128;                            // decode: tiles (lanes) per block
 constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
 constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
 
@@ -736,11 +737,16 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
         if (rank == 0) tab.first_code[l] = cw;
         const int slot = tab.base[l] + rank;
         if (slot < 256) tab.sorted[slot] = (unsigned char)c;
-        if (l <= kFastBits) {
-            const unsigned int rev = (unsigned int)(__brevll(cw) >> (64 - l));
-            for (unsigned int hi = 0; hi < (1u << (kFastBits - l)); ++hi)
-                tab.fast[rev | (hi << l)] = (unsigned short)((l << 8) | c);
-        }
+    }
+    // Every window whose low bits are a codeword of at most kFastBits bits: the block goes
+    // through the levels together and shares out each one's 2^(kFastBits - length) windows.
+    for (int c = 0; c < bins; ++c) {
+        const int l = lengths[c] > kMaxLen ? kMaxLen : lengths[c];
+        if (!l || l > kFastBits) continue;                     // block-uniform
+        const unsigned long long cw = codewords[c] & ((1ull << l) - 1ull);
+        const unsigned int rev = (unsigned int)(__brevll(cw) >> (64 - l));
+        for (unsigned int hi = tid; hi < (1u << (kFastBits - l)); hi += blockDim.x)
+            tab.fast[rev | (hi << l)] = (unsigned short)((l << 8) | c);
     }
     __syncthreads();
     // Chain single-symbol lookups inside the 10-bit window.  Bits beyond the window read as
@@ -762,7 +768,7 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
 }
 
 template <int R>
-__global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint8_t *__restrict__ lengths,
+__global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a, const uint8_t *__restrict__ lengths,
                                                        const unsigned long long *__restrict__ codewords,
                                                        const int64_t table_stride, const int64_t tiles,
                                                        const unsigned long long *__restrict__ tile_offsets,
@@ -771,7 +777,7 @@ __global__ void __launch_bounds__(256) k_huffman_decode(const Args a, const uint
                                                        const int64_t stream_words, const int64_t stream_stride_words)
 {
     __shared__ DecodeTable tab;
-    __shared__ __attribute__((aligned(16))) unsigned int out_ring[256 * kRingStride];
+    __shared__ __attribute__((aligned(16))) unsigned int out_ring[kDecodeThreads * kRingStride];
     const uint32_t p = blockIdx.y;
     fill_decode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride,
                          2 * a.s + 1);
@@ -956,9 +962,9 @@ hipError_t launch_huffman_decode(const Args &a, const uint8_t *lengths, const un
                                  const unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kTile - 1) / kTile;
-    const dim3 grid(cdiv(tiles, 256), (unsigned)a.workers);
+    const dim3 grid(cdiv(tiles, kDecodeThreads), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
-    hipLaunchKernelGGL((k_huffman_decode<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride,   \
+    hipLaunchKernelGGL((k_huffman_decode<RR>), grid, dim3(kDecodeThreads), 0, stream, a, lengths, codewords, table_stride,   \
                        tiles, tile_offsets, offset_stride, streams, stream_stride_words, stream_stride_words)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
