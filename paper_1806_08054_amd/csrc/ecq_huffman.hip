@@ -694,7 +694,7 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
 struct DecodeTable {
     unsigned long long first_code[64];       // canonical: first codeword of each length
     unsigned int multi[1 << kFastBits];
-    unsigned short count[64];                // codewords of each length
+    unsigned int count[64];                  // codewords of each length
     unsigned short base[64];                 // index into sorted[] of the first one
     unsigned short fast[1 << kFastBits];     // next 10 stream bits -> (length << 8) | code, 0 = longer
     unsigned char sorted[256];               // codes c in the order (length, c)
@@ -711,18 +711,16 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
     }
     for (int i = tid; i < (1 << kFastBits); i += blockDim.x) tab.fast[i] = 0;
     __syncthreads();
-    if (tid == 0) {
-        // Canonical order: by (length, c).  bins <= 255, so this small serial pass is cheap.
-        for (int c = 0; c < bins; ++c) {
-            const int l = lengths[c] > kMaxLen ? kMaxLen : lengths[c];
-            if (l) tab.count[l] = (unsigned short)(tab.count[l] + 1);
-        }
-        unsigned short at = 0;
-        for (int l = 1; l < 64; ++l) {
-            tab.base[l] = at;
-            at = (unsigned short)(at + tab.count[l]);
-        }
-        tab.base[0] = 0;
+    // Canonical order: by (length, c).
+    for (int c = tid; c < bins; c += blockDim.x) {
+        const int l = lengths[c] > kMaxLen ? kMaxLen : lengths[c];
+        if (l) atomicAdd(&tab.count[l], 1u);
+    }
+    __syncthreads();
+    for (int l = tid; l < 64; l += blockDim.x) {
+        unsigned int at = 0;
+        for (int j = 1; j < l; ++j) at += tab.count[j];
+        tab.base[l] = (unsigned short)at;
     }
     __syncthreads();
     for (int c = tid; c < bins; c += blockDim.x) {
@@ -751,18 +749,42 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
     __syncthreads();
     // Chain single-symbol lookups inside the 10-bit window.  Bits beyond the window read as
     // zeros, so a hit only counts when the whole codeword lies inside the window.
+    // A thread walks four windows side by side, so that their table reads overlap.
     constexpr int kMaxSyms = 20 / R < 10 ? 20 / R : 10;
-    for (int i = tid; i < (1 << kFastBits); i += blockDim.x) {
-        unsigned int used = 0, syms = 0, packed = 0;
-        while (syms < (unsigned int)kMaxSyms) {
-            const unsigned int hit = tab.fast[i >> used];
-            const unsigned int l = hit >> 8;
-            if (!hit || used + l > (unsigned int)kFastBits) break;
-            packed |= (hit & ((1u << R) - 1u)) << (R * syms);
-            ++syms;
-            used += l;
+    constexpr int kSide = 4;
+    for (int i0 = tid; i0 < (1 << kFastBits); i0 += kSide * blockDim.x) {
+        unsigned int used[kSide], syms[kSide], packed[kSide];
+        bool open[kSide];
+#pragma unroll
+        for (int e = 0; e < kSide; ++e) {
+            used[e] = syms[e] = packed[e] = 0u;
+            open[e] = i0 + e * (int)blockDim.x < (1 << kFastBits);
         }
-        tab.multi[i] = syms ? (packed | (used << 20) | (syms << 24)) : 0u;
+#pragma unroll 1
+        for (int step = 0; step < kMaxSyms; ++step) {
+            unsigned int hit[kSide];
+#pragma unroll
+            for (int e = 0; e < kSide; ++e)
+                hit[e] = open[e] ? tab.fast[((unsigned int)(i0 + e * (int)blockDim.x) >> used[e]) & ((1u << kFastBits) - 1u)] : 0u;
+            bool any = false;
+#pragma unroll
+            for (int e = 0; e < kSide; ++e) {
+                const unsigned int l = hit[e] >> 8;
+                open[e] = open[e] && hit[e] != 0u && used[e] + l <= (unsigned int)kFastBits;
+                if (open[e]) {
+                    packed[e] |= (hit[e] & ((1u << R) - 1u)) << (R * syms[e]);
+                    ++syms[e];
+                    used[e] += l;
+                }
+                any = any || open[e];
+            }
+            if (!any) break;
+        }
+#pragma unroll
+        for (int e = 0; e < kSide; ++e) {
+            const int i = i0 + e * (int)blockDim.x;
+            if (i < (1 << kFastBits)) tab.multi[i] = syms[e] ? (packed[e] | (used[e] << 20) | (syms[e] << 24)) : 0u;
+        }
     }
     __syncthreads();
 }
