@@ -181,14 +181,17 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
 //   packed    (length << 24) | reversed codeword, valid when no codeword of the row is longer
 //             than 24 bits (all_short) -- true unless some level is rarer than about 1 in 2^24;
 //   group     the same for GROUPS of group_k consecutive elements, indexed by their group_k*R
-//             code bits: total length << 24 | the codewords back to back.  group_k is the
-//             largest of 4, 2, 1 with at most 8 index bits and at most 24 stream bits per group,
-//             so short codes (the common case) cost a quarter of the table lookups.
+//             code bits: total length << 24 | the codewords back to back.  group_k = 4 for
+//             2-bit codes whose codewords have at most 6 bits, else 2 while codes have at most
+//             4 bits (a pair whose codewords exceed 24 bits together has 255 in the length
+//             field and no bits; pair_len holds every pair's true length), else 1: short
+//             codes, the common case, cost a quarter or half of the table lookups.
 struct EncodeTable {
     unsigned long long rev[256];
     unsigned int packed[256];
     unsigned int group[256];
     unsigned char len[256];
+    unsigned char pair_len[256];
     int all_short;
     int group_k;
     unsigned int max_len;
@@ -218,17 +221,19 @@ __device__ __forceinline__ void fill_encode_table(EncodeTable &tab, const uint8_
     __syncthreads();
     int k = 1;
     if (4 * R <= 8 && 4u * tab.max_len <= 24u) k = 4;
-    else if (2 * R <= 8 && 2u * tab.max_len <= 24u) k = 2;
+    else if (2 * R <= 8) k = 2;
     if (threadIdx.x == 0) tab.group_k = k;
     if (k > 1) {
         for (int idx = threadIdx.x; idx < (1 << (k * R)); idx += blockDim.x) {
-            unsigned int bits = 0, total = 0;
+            unsigned int total = 0;
+            unsigned long long bits = 0;
             for (int j = 0; j < k; ++j) {
                 const unsigned int c = (idx >> (R * j)) & ((1u << R) - 1u);
-                bits |= (unsigned int)tab.rev[c] << total;
+                bits |= tab.rev[c] << total;
                 total += tab.len[c];
             }
-            tab.group[idx] = (total << 24) | bits;
+            tab.group[idx] = total <= 24u ? ((total << 24) | (unsigned int)bits) : 0xFF000000u;
+            if (k == 2) tab.pair_len[idx] = (unsigned char)total;
         }
     }
     __syncthreads();
@@ -294,7 +299,7 @@ __device__ __forceinline__ unsigned int lane_bits(const EncodeTable &tab, const 
     } else if (R <= 4 && valid == 16 && tab.group_k == 2) {
         if constexpr (R <= 4) {
 #pragma unroll
-            for (int g = 0; g < 8; ++g) bits += tab.group[group_index<R, 2>(cd, g)] >> 24;
+            for (int g = 0; g < 8; ++g) bits += tab.pair_len[group_index<R, 2>(cd, g)];
         }
     } else {
 #pragma unroll
@@ -326,6 +331,56 @@ __device__ __forceinline__ void emit_groups(const EncodeTable &tab, const Codes1
             ++w;
             acc >>= 32;
             held -= 32u;
+        }
+    }
+    if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+}
+
+// Codes of at most 4 bits through the pair table, four pairs at a time: when their codewords
+// fit 32 bits together (nearly always: most levels are 0 and have the shortest codeword) they
+// are joined in a register and the accumulator is checked once; else pair by pair, and a pair
+// without a table entry level by level.
+template <int R>
+__device__ __forceinline__ void emit_pairs(const EncodeTable &tab, const Codes16<R> &cd, unsigned int pos,
+                                           unsigned int *__restrict__ mine, int words)
+{
+    int w = (int)(pos >> 5);
+    unsigned long long acc = 0;
+    unsigned int held = pos & 31u;
+    auto append = [&](unsigned int bits, unsigned int len) {   // len <= 32, held < 32
+        acc |= (unsigned long long)bits << held;
+        held += len;
+        if (held >= 32u) {
+            if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+            ++w;
+            acc >>= 32;
+            held -= 32u;
+        }
+    };
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        unsigned int e[4], idx[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            idx[j] = group_index<R, 2>(cd, 4 * half + j);
+            e[j] = tab.group[idx[j]];
+        }
+        const unsigned int l0 = e[0] >> 24, l1 = l0 + (e[1] >> 24), l2 = l1 + (e[2] >> 24), l3 = l2 + (e[3] >> 24);
+        if (l3 <= 32u) {
+            const unsigned int chunk = (e[0] & 0xFFFFFFu) | ((e[1] & 0xFFFFFFu) << l0) | ((e[2] & 0xFFFFFFu) << l1) |
+                                       ((e[3] & 0xFFFFFFu) << l2);
+            append(chunk, l3);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if ((e[j] >> 24) != 255u) {
+                    append(e[j] & 0xFFFFFFu, e[j] >> 24);
+                } else {
+                    const unsigned int p0 = tab.packed[idx[j] & ((1u << R) - 1u)], p1 = tab.packed[idx[j] >> R];
+                    append(p0 & 0xFFFFFFu, p0 >> 24);
+                    append(p1 & 0xFFFFFFu, p1 >> 24);
+                }
+            }
         }
     }
     if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
@@ -644,7 +699,7 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
                 if (R <= 2 && k == 4) {
                     if constexpr (R <= 2) emit_groups<R, 4>(tab, cd[q], valid[q], at, mine, words);
                 } else if (R <= 4 && k == 2) {
-                    if constexpr (R <= 4) emit_groups<R, 2>(tab, cd[q], valid[q], at, mine, words);
+                    if constexpr (R <= 4) emit_pairs<R>(tab, cd[q], at, mine, words);
                 } else {
                     emit_groups<R, 1>(tab, cd[q], valid[q], at, mine, words);
                 }
@@ -687,8 +742,8 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
 // ---------------------------------------------------------------------------------------------
 // Decoding a tile is a chain: the position of a codeword is known only once the one before it
 // has been decoded.  To shorten the chain the main table maps the next 10 stream bits to ALL
-// the codewords that end inside them (up to 10, and as many as fit 20 bits of r-bit codes):
-//   multi[i] = packed r-bit codes | bits consumed << 20 | symbols << 24      (symbols = 0: none)
+// the codewords that end inside them (up to 10, and as many as fit 24 bits of r-bit codes):
+//   multi[i] = packed r-bit codes | bits consumed << 24 | symbols << 28      (symbols = 0: none)
 // A codeword longer than 10 bits, and the last few symbols of a tile, take the single-symbol
 // route: `fast` (first codeword in the 10 bits) or the canonical first-code/count walk.
 struct DecodeTable {
@@ -750,7 +805,7 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
     // Chain single-symbol lookups inside the 10-bit window.  Bits beyond the window read as
     // zeros, so a hit only counts when the whole codeword lies inside the window.
     // A thread walks four windows side by side, so that their table reads overlap.
-    constexpr int kMaxSyms = 20 / R < 10 ? 20 / R : 10;
+    constexpr int kMaxSyms = 24 / R < 10 ? 24 / R : 10;
     constexpr int kSide = 4;
     for (int i0 = tid; i0 < (1 << kFastBits); i0 += kSide * blockDim.x) {
         unsigned int used[kSide], syms[kSide], packed[kSide];
@@ -783,7 +838,7 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
 #pragma unroll
         for (int e = 0; e < kSide; ++e) {
             const int i = i0 + e * (int)blockDim.x;
-            if (i < (1 << kFastBits)) tab.multi[i] = syms[e] ? (packed[e] | (used[e] << 20) | (syms[e] << 24)) : 0u;
+            if (i < (1 << kFastBits)) tab.multi[i] = syms[e] ? (packed[e] | (used[e] << 24) | (syms[e] << 28)) : 0u;
         }
     }
     __syncthreads();
@@ -889,10 +944,10 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
       for (int k = 0; k < 3; ++k) {
         if (remaining <= 0 || have < (unsigned int)kFastBits) break;   // (a long codeword may have used more)
         const unsigned int m = tab.multi[(unsigned int)res & ((1u << kFastBits) - 1u)];
-        const unsigned int syms = m >> 24;
+        const unsigned int syms = m >> 28;
         if (syms != 0u && (int)syms <= remaining) {
-            const unsigned int used = (m >> 20) & 15u;
-            out_acc |= (unsigned long long)(m & 0xFFFFFu) << out_held;
+            const unsigned int used = (m >> 24) & 15u;
+            out_acc |= (unsigned long long)(m & 0xFFFFFFu) << out_held;
             out_held += syms * R;
             res >>= used;
             have -= used;

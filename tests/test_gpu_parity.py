@@ -494,16 +494,19 @@ def test_huffman_degenerate_rows(E):
     assert _huffman_roundtrip(E, sh, P, N, s, codes, q) == 2 * N
 
 
-def test_huffman_long_codewords(E):
+@pytest.mark.parametrize("s", [17, 7, 3])
+def test_huffman_long_codewords(E, s):
     """Level counts that follow the Fibonacci numbers give the deepest possible tree: with 35
-    levels the rarest codeword is 34 bits long, beyond one 32-bit stream word."""
-    s = 17
+    levels (s = 17) the rarest codeword is 34 bits long, beyond one 32-bit stream word; with 15
+    levels (s = 7, 4-bit codes) two codewords together can exceed the 24 bits a pair-table
+    entry holds; with 7 levels every pair fits."""
     fib = [1, 1]
     while len(fib) < 2 * s + 1:
         fib.append(fib[-1] + fib[-2])
     rng = np.random.default_rng(17)
     levels = rng.permutation(2 * s + 1) - s
     q = np.repeat(levels.astype(np.int8), fib)
+    q = np.tile(q, max(1, 40_000 // q.size))                  # the same proportions, several tiles
     rng.shuffle(q)
     N = q.size
     assert int(oracle.huffman_lengths(oracle.level_histogram(q, s)).max()) == 2 * s
