@@ -466,7 +466,14 @@ def _huffman_roundtrip(E, sh, P, N, s, codes_dev, q_rows, poison_stream=0xEE):
                                                (7, 2048, 300_000, 4, "student_t"), (127, 8, 9, 2, "normal"),
                                                (127, 512, 150_000, 2, "student_t"), (1, 512, 1_200_003, 2, "normal"),
                                                (3, 1024, 1025, 1, "normal"), (1, 8, 1024, 1, "normal"),
-                                               (4, 512, 4_200_000, 2, "normal")])
+                                               (4, 512, 4_200_000, 2, "normal"),
+                                               # whole runs of 16 tiles, whole steps, one element more
+                                               (1, 512, 16_384, 2, "normal"), (1, 512, 16_385, 1, "student_t"),
+                                               (1, 512, 4_096 + 16, 2, "normal"), (1, 512, 65_536 + 3, 3, "normal"),
+                                               (7, 512, 32_768 + 1_023, 2, "normal"),
+                                               # 5-, 6- and 7-bit codes: two tiles, then one tile per step
+                                               (9, 512, 40_000, 2, "normal"), (20, 512, 33_000, 2, "student_t"),
+                                               (40, 512, 20_000, 1, "normal")])
 def test_huffman_matches_oracle(E, s, bucket, N, P, kind):
     """Section 4's Huffman encoding of a quantised message: counts, codeword lengths,
     canonical codewords, tile offsets and the stream itself bit-exact against the oracle;
