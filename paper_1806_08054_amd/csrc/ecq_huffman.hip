@@ -511,22 +511,26 @@ __global__ void __launch_bounds__(256) k_huffman_run_bits(const Args a, const ui
     constexpr int kBatch = kFit >= kSteps ? kSteps : (kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1)));
     __shared__ LengthTable tab;
     const uint32_t p = blockIdx.y;
-    fill_length_table<R>(tab, lengths + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kRunTiles;
-    if (first >= tiles) return;                                // wave-uniform; no barrier follows
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    const unsigned int len3[3] = {tab.len[0], tab.len[1], tab.len[2]};
-    unsigned int bits = 0;
-#pragma unroll 1
-    for (int s0 = 0; s0 < kSteps; s0 += kBatch) {
-        Codes16<R> cd[kBatch][Q];
-        int valid[kBatch][Q];
+    Codes16<R> cd[kBatch][Q];
+    int valid[kBatch][Q];
+    auto request = [&](int s0) {                               // (nothing is read beyond the row's n elements)
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
             load_lane_step<R, Q>(crow, a.row_bytes, a.n, first * kTile + (int64_t)(s0 + i) * kStepElems + lane * (16 * Q),
                                  cd[i], valid[i]);
+    };
+    request(0);                                                // in flight while the table is made
+    fill_length_table<R>(tab, lengths + (int64_t)p * table_stride, 2 * a.s + 1);
+    if (first >= tiles) return;                                // wave-uniform; no barrier follows
+    const unsigned int len3[3] = {tab.len[0], tab.len[1], tab.len[2]};
+    unsigned int bits = 0;
+#pragma unroll 1
+    for (int s0 = 0; s0 < kSteps; s0 += kBatch) {
+        if (s0 > 0) request(s0);
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
 #pragma unroll
@@ -630,25 +634,26 @@ __global__ void __launch_bounds__(256) k_huffman_write(const Args a, const uint8
     __shared__ EncodeTable tab;
     extern __shared__ unsigned int step_buf[];
     const uint32_t p = blockIdx.y;
-    fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * kRunTiles;
-    if (first >= tiles) return;                                // wave-uniform; no block barrier follows
     unsigned int *__restrict__ mine = step_buf + wave * buf_words;
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     unsigned long long *__restrict__ offs = tile_offsets + (int64_t)p * offset_stride;
     uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
-    for (int j = lane; j < buf_words; j += 64) mine[j] = 0u;
-    wave_lds_sync();
-
-    const unsigned long long run_start = offs[first];          // bit offset of the run (pass 2)
-    unsigned long long pos = run_start;                        // ... and of the current step
-    unsigned int carry = 0;                                    // partial last word of the step before
+    // The run's offset (pass 2) and the first step's codes are in flight while the table is made.
+    const unsigned long long run_start = first < tiles ? offs[first] : 0ull;
     const int64_t elem0 = first * kTile + (int64_t)lane * (16 * Q);
     Codes16<R> cd[Q], cd_next[Q];
     int valid[Q], valid_next[Q];
     load_lane_step<R, Q>(crow, a.row_bytes, a.n, elem0, cd_next, valid_next);
+    fill_encode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, 2 * a.s + 1);
+    if (first >= tiles) return;                                // wave-uniform; no block barrier follows
+    for (int j = lane; j < buf_words; j += 64) mine[j] = 0u;
+    wave_lds_sync();
+
+    unsigned long long pos = run_start;                        // bit offset of the current step
+    unsigned int carry = 0;                                    // partial last word of the step before
 
 #pragma unroll 1
     for (int step = 0; step < kSteps; ++step) {
