@@ -359,8 +359,15 @@ __global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lan
 
 // First pass of the two-pass route: scales[p][k] = max |g + alpha*h| over bucket k, taken with
 // an unsigned atomic max on the bit patterns (order-preserving for non-negative floats).
-// scales must hold zeros on entry.
-__global__ void __launch_bounds__(256) k_bucket_norm(const Args a)
+// scales must hold zeros on entry.  Atomic operations on one address are served one at a time,
+// so both kernels below reduce as far as they can before they issue one.
+//
+// Buckets shorter than 256 elements (and not a power of two): a lane owns one float4, which
+// never straddles buckets (they are multiples of 8 elements).  The lanes of a bucket are
+// neighbours, so a segmented prefix maximum over the wave (six shuffle steps on the pair
+// (bucket, max)) leaves each bucket's maximum in its last lane, and only that lane sends it:
+// at most two atomic operations per bucket and wave boundary.
+__global__ void __launch_bounds__(256) k_bucket_norm_small(const Args a)
 {
     const int lane = threadIdx.x & 63;
     const int64_t elem = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -369,19 +376,63 @@ __global__ void __launch_bounds__(256) k_bucket_norm(const Args a)
     load4(a.g + (int64_t)p * a.gh_stride, elem, a.n, g);
     load4(a.h + (int64_t)p * a.gh_stride, elem, a.n, h);
     float v[4];
-    const uint32_t mx = compensate4(g, h, a.alpha, v);
+    uint32_t mx = compensate4(g, h, a.alpha, v);
     const bool exists = elem < a.n;
-    const long long k = exists ? (long long)(elem / a.bucket) : -1;
     // Element indices grow with the lane, so lane 0 holds the wave's lowest bucket, and if lane 0
-    // is past the end of the row the whole wave is.  Lanes past the end carry a zero norm.
-    const long long k_lead = __shfl(k, 0, 64);
-    if (k_lead < 0) return;
-    uint32_t *dst = reinterpret_cast<uint32_t *>(a.scales + (int64_t)p * a.scale_stride);
-    if (__all(!exists || k == k_lead)) {
-        const uint32_t norm = wave_max_uniform(mx);
-        if (lane == 0) atomicMax(dst + k_lead, norm);
-    } else if (exists) {
-        atomicMax(dst + k, mx);
+    // is past the end of the row the whole wave is.
+    const int64_t wave_elem = elem - (int64_t)lane * 4;
+    if (wave_elem >= a.n) return;                              // wave-uniform
+    const int64_t k_lead = wave_elem / a.bucket;
+    // Bucket relative to the wave's first one; lanes past the end get one no bucket has.
+    const int k = exists ? (int)(elem / a.bucket - k_lead) : 0x7FFFFFFF;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int below_k = __shfl_up(k, d, 64);
+        const uint32_t below_mx = (uint32_t)__shfl_up((int)mx, d, 64);
+        if (lane >= d && below_k == k) mx = umax(mx, below_mx);
+    }
+    const int next_k = __shfl_down(k, 1, 64);
+    const bool last_of_bucket = lane == 63 || next_k != k;
+    if (exists && last_of_bucket)
+        atomicMax(reinterpret_cast<uint32_t *>(a.scales + (int64_t)p * a.scale_stride) + (k_lead + k), mx);
+}
+
+// Buckets longer than 32768 elements, up to the whole row: a bucket is cut into `parts` pieces
+// of `part_len` elements (a multiple of 1024); a block walks one piece, 2048 elements at a
+// time, and sends one atomic max for it.  blockIdx.x = bucket * parts + part.
+__global__ void __launch_bounds__(256) k_bucket_norm_large(const Args a, const int parts, const int64_t part_len)
+{
+    __shared__ uint32_t wave_norm[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t p = blockIdx.y;
+    const int64_t k = blockIdx.x / parts;
+    const int part = (int)(blockIdx.x - k * parts);
+    const int64_t bucket_begin = k * (int64_t)a.bucket;
+    int64_t bucket_end = bucket_begin + a.bucket;
+    if (bucket_end > a.n) bucket_end = a.n;
+    const int64_t begin = bucket_begin + (int64_t)part * part_len;
+    int64_t end = begin + part_len;
+    if (end > bucket_end) end = bucket_end;
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
+    const float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
+    uint32_t mx = 0;
+    // `end` is a multiple of 4 or the row's end, so load4's own guard (elements >= end read as
+    // 0, and |0| never raises a maximum) is all a ragged piece needs.
+    for (int64_t at = begin + (int64_t)threadIdx.x * 4; at < end; at += 2048) {
+        float g0[4], h0[4], g1[4], h1[4], v[4];
+        load4(grow, at, end, g0);
+        load4(hrow, at, end, h0);
+        load4(grow, at + 1024, end, g1);
+        load4(hrow, at + 1024, end, h1);
+        mx = umax(mx, compensate4(g0, h0, a.alpha, v));
+        mx = umax(mx, compensate4(g1, h1, a.alpha, v));
+    }
+    mx = wave_max_uniform(mx);
+    if (lane == 0) wave_norm[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0 && begin < end) {
+        const uint32_t norm = umax(umax(wave_norm[0], wave_norm[1]), umax(wave_norm[2], wave_norm[3]));
+        atomicMax(reinterpret_cast<uint32_t *>(a.scales + (int64_t)p * a.scale_stride) + k, norm);
     }
 }
 
@@ -1023,7 +1074,18 @@ static void launch_quantize_r(const Args &a, const Plan &plan, bool update, hipS
         launch_chunk<R>(a, plan.lanes_per_bucket, 256, update, st);
     } else {
         hipLaunchKernelGGL(k_zero_scales, dim3(cdiv(a.nb, 256), (unsigned)a.workers), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(k_bucket_norm, dim3(cdiv(cdiv(a.n, 4), 256), (unsigned)a.workers), dim3(256), 0, st, a);
+        if (a.bucket < 256) {
+            hipLaunchKernelGGL(k_bucket_norm_small, dim3(cdiv(cdiv(a.n, 4), 256), (unsigned)a.workers), dim3(256), 0, st,
+                               a);
+        } else {
+            // At most 256 pieces per bucket, none shorter than 8192 elements (unless the bucket is).
+            int64_t parts = cdiv((int64_t)a.bucket, 8192);
+            if (parts > 256) parts = 256;
+            const int64_t part_len = cdiv(cdiv((int64_t)a.bucket, parts), 1024) * 1024;
+            parts = cdiv((int64_t)a.bucket, part_len);
+            hipLaunchKernelGGL(k_bucket_norm_large, dim3((unsigned)(a.nb * parts), (unsigned)a.workers), dim3(256), 0,
+                               st, a, (int)parts, part_len);
+        }
         launch_chunk<R>(a, 0, 256, update, st);
     }
 }

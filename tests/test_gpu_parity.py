@@ -167,11 +167,26 @@ def test_levels_and_buckets(E, s, bucket):
     _free_run(E, wl, 2, pad=3, fused=False)                    # ecq_quantize, then ecq_error_update
 
 
-@pytest.mark.parametrize("bucket", [16, 24, 32, 128, 256, 264, 2048, 4096, 8192, 16384, 32768, 40000])
+@pytest.mark.parametrize("bucket", [16, 24, 32, 40, 96, 128, 248, 256, 264, 2048, 4096, 8192, 16384, 32768, 40000,
+                                    65536, 100_000, 1 << 20])
 def test_bucket_routes(E, bucket):
+    """Every mapping of buckets to lanes: lane groups (powers of two up to 128), teams of waves
+    (256 ... 32768), and the two-pass route with its two first passes (other buckets below 256;
+    buckets beyond 32768, cut into several pieces)."""
     wl = synth.Workload("edge", P=2, N=3 * bucket + bucket // 2 + 5, bucket=bucket, s=3, alpha=1.0, beta=0.9,
                         iters=2, kind="normal", data_seed=bucket)
     _free_run(E, wl, 2)
+
+
+@pytest.mark.parametrize("N,s", [(700_001, 1), (2_500_000, 4)])
+def test_one_norm_per_row(E, N, s):
+    """Eq. (8) as first stated, without buckets: the bucket is the whole row (one norm per
+    worker), here as the smallest multiple of 8 that holds the row."""
+    bucket = (N + 7) // 8 * 8
+    wl = synth.Workload("edge", P=3, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=2, kind="student_t",
+                        data_seed=N)
+    _free_run(E, wl, 2)
+    _free_run(E, wl, 2, fused=False)
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8, 9, 255, 256, 257, 511, 513])
