@@ -101,6 +101,8 @@ struct Rounder {
 // Rounds, encodes and (optionally) accumulates the error for a lane's 4 elements.
 //   valid : how many of the 4 exist (0..4); codes of missing elements are zero bits.
 // Returns the 4*R encoded bits, element e in bits [e*R, (e+1)*R).
+constexpr int kChunksPerWave = 2;
+
 template <int R, bool UPDATE>
 __device__ __forceinline__ uint32_t quantize4(const float (&g)[4], float (&h)[4], const float (&v)[4],
                                               int valid, const Rounder<R> &rounder, float beta,
@@ -313,7 +315,8 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 }
 
 // ---------------------------------------------------------------------------------------------
-// One float4 per lane, one 256-element chunk per wave.  Two uses:
+// A wave owns two consecutive chunks of 256 elements, a lane one float4 of each (all loads are
+// issued before any is used).  Two uses:
 //   lanes_per_bucket > 0 : single pass for small power-of-two buckets (8..128 elements): the
 //                          norm is a max over aligned groups of lanes_per_bucket lanes;
 //   lanes_per_bucket == 0: second pass of the two-pass route: the norm is read from scales.
@@ -324,37 +327,47 @@ __global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lan
     __shared__ float xi_tab[256];
     if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
 
+    constexpr int J = kChunksPerWave;                          // consecutive chunks of 256 elements per wave
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int64_t chunk = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
-    const int64_t elem = chunk * 256 + lane * 4;
+    const int64_t chunk0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave) * J;
     const uint32_t p = blockIdx.y;
-    if (chunk * 256 >= a.n) return;                            // wave-uniform
+    if (chunk0 * 256 >= a.n) return;                           // wave-uniform
 
     const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
     float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
-    float g[4], h[4], v[4];
-    load4(grow, elem, a.n, g);
-    load4(hrow, elem, a.n, h);
-    int64_t rest = a.n - elem;
-    const int valid = rest < 0 ? 0 : (rest > 4 ? 4 : (int)rest);
-    const uint32_t mx = compensate4(g, h, a.alpha, v);
-
-    float scale;
-    const int64_t k = elem / a.bucket;
-    if (lanes_per_bucket > 0) {
-        scale = a.norm_l2 ? __builtin_sqrtf(group_sum_tree(sum_squares4(v), lanes_per_bucket))
-                          : __uint_as_float(group_max(mx, lanes_per_bucket));
-        if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
-            a.scales[(int64_t)p * a.scale_stride + k] = scale;
-    } else {
-        scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + k] : 0.0f;
+    float g[J][4], h[J][4], v[J][4];
+    uint32_t mx[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {                              // all loads first (nothing is read beyond n)
+        const int64_t elem = (chunk0 + j) * 256 + lane * 4;
+        load4(grow, elem, a.n, g[j]);
+        load4(hrow, elem, a.n, h[j]);
     }
-    const Rounder<R> rounder(scale, a.s, xi_tab);
-    const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
-    const uint32_t bits = quantize4<R, UPDATE>(g, h, v, valid, rounder, a.beta, words);
-    store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem, valid, bits, lane);
-    if (UPDATE) store4(hrow, elem, a.n, h);
+#pragma unroll
+    for (int j = 0; j < J; ++j) mx[j] = compensate4(g[j], h[j], a.alpha, v[j]);
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        if ((chunk0 + j) * 256 >= a.n) break;                  // wave-uniform
+        const int64_t elem = (chunk0 + j) * 256 + lane * 4;
+        const int64_t rest = a.n - elem;
+        const int valid = rest < 0 ? 0 : (rest > 4 ? 4 : (int)rest);
+        float scale;
+        const int64_t k = elem / a.bucket;
+        if (lanes_per_bucket > 0) {
+            scale = a.norm_l2 ? __builtin_sqrtf(group_sum_tree(sum_squares4(v[j]), lanes_per_bucket))
+                              : __uint_as_float(group_max(mx[j], lanes_per_bucket));
+            if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
+                a.scales[(int64_t)p * a.scale_stride + k] = scale;
+        } else {
+            scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + k] : 0.0f;
+        }
+        const Rounder<R> rounder(scale, a.s, xi_tab);
+        const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
+        const uint32_t bits = quantize4<R, UPDATE>(g[j], h[j], v[j], valid, rounder, a.beta, words);
+        store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem, valid, bits, lane);
+        if (UPDATE) store4(hrow, elem, a.n, h[j]);
+    }
 }
 
 // First pass of the two-pass route: scales[p][k] = max |g + alpha*h| over bucket k, taken with
@@ -1058,7 +1071,7 @@ template <int R>
 static void launch_chunk(const Args &a, int lanes_per_bucket, int block_threads, bool update, hipStream_t st)
 {
     const int waves = block_threads / 64;
-    const dim3 grid(cdiv(cdiv(a.n, 256), waves), (unsigned)a.workers);
+    const dim3 grid(cdiv(cdiv(a.n, 256), waves * kChunksPerWave), (unsigned)a.workers);
     if (update)
         hipLaunchKernelGGL((k_quant_chunk<R, true>), grid, dim3(block_threads), 0, st, a, lanes_per_bucket);
     else
