@@ -643,12 +643,15 @@ __device__ __forceinline__ void fill_pair_table(f2 *pair, int)
 //   else : g~ = norm * sxi[c], then acc + g~, as in agg_add.
 template <int R>
 __device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint32_t lane_off, const Codes16<R> &cd,
-                                          float norm, float (&acc)[16])
+                                          float norm_lo, float norm_hi, float (&acc)[16])
 {
+    // norm_lo scales the lane's first 8 outputs, norm_hi the other 8 (two buckets when the bucket
+    // size is an odd multiple of 8; else the same value twice).
     if constexpr (R == 2) {
         const uint32_t x = cd.w[0];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
+            const float norm = j < 4 ? norm_lo : norm_hi;
             // Byte offset nib*256 + (lane & 31)*8: the nibble moved to bits 8..11, OR-ed with the
             // lane's copy offset (bits 3..7).
             const uint32_t nib8 = 4 * j >= 8 ? (x >> (4 * j - 8)) : (x << (8 - 4 * j));
@@ -660,7 +663,7 @@ __device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint
     } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const float gt = norm * sxi[cd.code(e)];
+            const float gt = (e < 8 ? norm_lo : norm_hi) * sxi[cd.code(e)];
             acc[e] = acc[e] + gt;
         }
     }
@@ -672,15 +675,15 @@ constexpr int kAggStageStride = 20;    // floats between lanes in the transposit
 // Eq. (4): out[i] = (sum_{p=0}^{P-1} g~_p[i]) / P, workers added in index order.
 // A wave owns 1024 consecutive outputs, a lane 16 consecutive ones, so every worker costs a
 // lane one aligned load of 2*R code bytes (a wave reads 128*R contiguous bytes per worker) and
-// one norm (UNIFORM_NORM: the bucket is a multiple of 1024 and the load is scalar; else one per lane; the bucket
-// must be a multiple of 16 so a lane never straddles two).  Four workers' codes and norms are
-// in flight together.  The 16 sums of a lane are then transposed through LDS so the wave
-// stores (and, for the model update, loads) whole contiguous kilobytes as float4 per lane.
-// Ragged tiles and buckets that are not multiples of 16 go through agg_run_guarded.
+// its norms: NORMS = 0 when the bucket is a multiple of 1024 (one norm per wave, a scalar
+// load), 1 when it is a multiple of 16 (one per lane), 2 otherwise (buckets are multiples of 8,
+// so the lane's two halves of 8 outputs may lie in two buckets: one norm each).  Four workers'
+// codes and norms are in flight together.  The 16 sums of a lane are then transposed through
+// LDS so the wave stores (and, for the model update, loads) whole contiguous kilobytes as
+// float4 per lane.  The ragged last run of a row goes through agg_run_guarded.
 // bucket_shift >= 0 when the bucket is a power of two.
-template <int R, bool UNIFORM_NORM>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift,
-                                                           const int lane_bucket_ok, const float inv_p)
+template <int R, int NORMS>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift, const float inv_p)
 {
     // One LDS object with the pair table first: its byte offsets are then LDS addresses, and a
     // lookup address is a single AND-OR of the shifted codes with the lane's copy offset.
@@ -701,7 +704,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
            (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
     if (base >= a.n) return;                                   // wave-uniform
-    if (!lane_bucket_ok || base + kAggRun > a.n) {
+    if (base + kAggRun > a.n) {
 #pragma unroll 1
         for (int j = 0; j < kAggRun / 256; ++j)
             if (base + j * 256 < a.n) agg_run_guarded<R>(a, table, base + j * 256, lane, bucket_shift, inv_p);
@@ -710,10 +713,16 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
 
     const int64_t first = base + lane * 16;
     const int64_t k_lane = bucket_shift >= 0 ? (first >> bucket_shift) : (first / a.bucket);
+    const int64_t k_half = bucket_shift >= 0 ? ((first + 8) >> bucket_shift) : ((first + 8) / a.bucket);
     const int64_t k_wave = bucket_shift >= 0 ? (base >> bucket_shift) : (base / a.bucket);
     const uint8_t *__restrict__ cptr = a.codes + ((base * R) >> 3) + lane * (2 * R);
     const float *__restrict__ srow = a.scales;
     const uint32_t lane_off = (uint32_t)(lane & 31) * 8u;
+    // One worker's norms for the lane's first and second 8 outputs.
+    auto norms_of = [&](const float *__restrict__ row, float &lo, float &hi) {
+        lo = NORMS == 0 ? row[k_wave] : row[k_lane];
+        hi = NORMS == 2 ? row[k_half] : lo;
+    };
 
     float acc[16];
 #pragma unroll
@@ -724,31 +733,34 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         // current one is added, so two batches are in flight.  Workers are added in index order.
         const int batches = a.workers / U;
         Codes16<R> cd[U], cd_next[U];
-        float norm[U], norm_next[U];
-        auto request = [&](Codes16<R> (&c)[U], float (&nr)[U]) {
+        float lo[U], hi[U], lo_next[U], hi_next[U];
+        auto request = [&](Codes16<R> (&c)[U], float (&nl)[U], float (&nh)[U]) {
     #pragma unroll
             for (int u = 0; u < U; ++u) {
                 c[u].load(cptr + u * a.code_stride);
-                nr[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+                norms_of(srow + u * a.scale_stride, nl[u], nh[u]);
             }
             cptr += U * a.code_stride;
             srow += U * a.scale_stride;
         };
-        if (batches > 0) request(cd_next, norm_next);
+        if (batches > 0) request(cd_next, lo_next, hi_next);
         for (int b = 0; b < batches; ++b) {
     #pragma unroll
             for (int u = 0; u < U; ++u) {
                 cd[u] = cd_next[u];
-                norm[u] = norm_next[u];
+                lo[u] = lo_next[u];
+                hi[u] = hi_next[u];
             }
-            if (b + 1 < batches) request(cd_next, norm_next);
+            if (b + 1 < batches) request(cd_next, lo_next, hi_next);
     #pragma unroll
-            for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);
+            for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], lo[u], hi[u], acc);
         }
         for (int p = batches * U; p < a.workers; ++p) {
             Codes16<R> one;
+            float one_lo, one_hi;
             one.load(cptr);
-            agg_add16<R>(table, pair, lane_off, one, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
+            norms_of(srow, one_lo, one_hi);
+            agg_add16<R>(table, pair, lane_off, one, one_lo, one_hi, acc);
             cptr += a.code_stride;
             srow += a.scale_stride;
         }
@@ -758,21 +770,23 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         int p = 0;
         for (; p + V <= a.workers; p += V) {
             Codes16<R> cd[V];
-            float norm[V];
+            float lo[V], hi[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 cd[u].load(cptr + u * a.code_stride);
-                norm[u] = UNIFORM_NORM ? srow[u * a.scale_stride + k_wave] : srow[u * a.scale_stride + k_lane];
+                norms_of(srow + u * a.scale_stride, lo[u], hi[u]);
             }
 #pragma unroll
-            for (int u = 0; u < V; ++u) agg_add16<R>(table, pair, lane_off, cd[u], norm[u], acc);
+            for (int u = 0; u < V; ++u) agg_add16<R>(table, pair, lane_off, cd[u], lo[u], hi[u], acc);
             cptr += V * a.code_stride;
             srow += V * a.scale_stride;
         }
         for (; p < a.workers; ++p) {
             Codes16<R> one;
+            float one_lo, one_hi;
             one.load(cptr);
-            agg_add16<R>(table, pair, lane_off, one, UNIFORM_NORM ? srow[k_wave] : srow[k_lane], acc);
+            norms_of(srow, one_lo, one_hi);
+            agg_add16<R>(table, pair, lane_off, one, one_lo, one_hi, acc);
             cptr += a.code_stride;
             srow += a.scale_stride;
         }
@@ -1129,17 +1143,16 @@ hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
     int bucket_shift = -1;
     if ((a.bucket & (a.bucket - 1)) == 0)
         for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
-    const int lane_bucket_ok = (a.bucket % 16) == 0;
-    const int uniform_norm = (a.bucket % kAggRun) == 0;
+    const int norms = (a.bucket % kAggRun) == 0 ? 0 : ((a.bucket % 16) == 0 ? 1 : 2);
     // Dividing by a power of two and multiplying by its reciprocal round identically.
     const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
 #define CALL(RR)                                                                                              \
-    if (uniform_norm)                                                                                         \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, true>), grid, dim3(256), 0, stream, a, bucket_shift,      \
-                           lane_bucket_ok, inv_p);                                                            \
+    if (norms == 0)                                                                                           \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, 0>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p); \
+    else if (norms == 1)                                                                                      \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, 1>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p); \
     else                                                                                                      \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, false>), grid, dim3(256), 0, stream, a, bucket_shift,     \
-                           lane_bucket_ok, inv_p)
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, 2>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();
