@@ -243,6 +243,31 @@ __device__ __forceinline__ void store_code_bytes(uint8_t *dst, uint64_t bits, in
         if (b < nbytes && (int64_t)b < limit) dst[b] = (uint8_t)(bits >> (8 * b));
 }
 
+// Store the low NBYTES bytes of `bits` at dst (any address) in as few pieces as possible: a
+// dword, a short and a byte where needed.  Global stores need no natural alignment here.
+template <int NBYTES>
+__device__ __forceinline__ void store_code_bytes_whole(uint8_t *dst, uint64_t bits)
+{
+    static_assert(NBYTES >= 1 && NBYTES <= 8, "at most one 64-bit word");
+    int at = 0;
+    if constexpr (NBYTES >= 4) {
+        const uint32_t w = (uint32_t)bits;
+        __builtin_memcpy(dst, &w, 4);
+        at = 4;
+    }
+    if constexpr ((NBYTES & 3) >= 2) {
+        const uint16_t w = (uint16_t)(bits >> (8 * at));
+        __builtin_memcpy(dst + at, &w, 2);
+        at += 2;
+    }
+    if constexpr (NBYTES == 8) {
+        const uint32_t w = (uint32_t)(bits >> 32);
+        __builtin_memcpy(dst + 4, &w, 4);
+    } else if constexpr ((NBYTES & 1) == 1) {
+        dst[at] = (uint8_t)(bits >> (8 * at));
+    }
+}
+
 // ---- reading packed codes ------------------------------------------------------------------
 
 // The R bytes that hold the codes of the 8 elements starting at `elem` (a multiple of 8).

@@ -138,7 +138,7 @@ __device__ __forceinline__ void store_codes(uint8_t *__restrict__ crow, int64_t 
             } else if constexpr (NB == 4) {
                 *reinterpret_cast<uint32_t *>(dst) = bits;
             } else {
-                store_code_bytes(dst, bits, NB, NB);
+                store_code_bytes_whole<NB>(dst, bits);
             }
         } else if (valid > 0) {
             store_code_bytes(crow + byte_off, bits, NB, row_bytes - byte_off);
@@ -148,7 +148,10 @@ __device__ __forceinline__ void store_codes(uint8_t *__restrict__ crow, int64_t 
         if ((lane & 1) == 0 && valid > 0) {
             const uint64_t both = (uint64_t)bits | ((uint64_t)next << (4 * R));
             const int64_t byte_off = (elem >> 3) * R;
-            store_code_bytes(crow + byte_off, both, R, row_bytes - byte_off);
+            // Bits of elements past the row's end are zero, so whole bytes inside the row are
+            // written as they are.
+            if (byte_off + R <= row_bytes) store_code_bytes_whole<R>(crow + byte_off, both);
+            else store_code_bytes(crow + byte_off, both, R, row_bytes - byte_off);
         }
     }
 }
