@@ -70,8 +70,12 @@ typedef enum {
  *   ECQ_NORM_L2    sqrt of the sum of fl(v_i^2), the sum taken over a balanced binary tree by
  *                  element index (the bucket padded with zeros to a power of two), then one
  *                  correctly rounded square root.  Needs a bucket that is a power of two in
- *                  8..128 or any multiple of 8 in 256..32768; other buckets give
- *                  ECQ_ERR_BUCKET.  Squares must stay inside the binary32 range. */
+ *                  8..128, any multiple of 8 from 256 on, or any bucket that holds the whole
+ *                  row (n <= bucket: one norm per worker, Eq. (8) without buckets); other
+ *                  buckets give ECQ_ERR_BUCKET.  Squares must stay inside the binary32 range.
+ * Buckets beyond 32768 elements take two passes over g and h (20 instead of 12 bytes per
+ * element); with ECQ_NORM_L2 the first pass borrows a few bytes per 8192 elements of the
+ * worker's row of `codes`, which the second pass then overwrites as documented. */
 #define ECQ_NORM_LINF 0
 #define ECQ_NORM_L2 1
 

@@ -78,9 +78,11 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
     const bool pow2 = (b & (b - 1)) == 0;
     const bool small_ok = pow2 && b >= 8 && b <= 128;
     const bool team_ok = b >= 256 && b <= 32768;
-    // The l2 sum has a fixed tree order that only the single-pass mappings reproduce.
-    if (sh.norm == ECQ_NORM_L2 && !(small_ok || team_ok)) return ECQ_ERR_BUCKET;
-    if (sh.norm == ECQ_NORM_L2 && path == 2) return ECQ_ERR_PARAM;
+    // The l2 sum has a fixed tree order: the single-pass mappings reproduce it, and so does the
+    // two-pass route for buckets beyond 32768 (sums of 8192-element pieces, then a tree over the
+    // pieces); other buckets below 256 do not fit the lanes' tree.
+    if (sh.norm == ECQ_NORM_L2 && !(small_ok || team_ok || b > 32768)) return ECQ_ERR_BUCKET;
+    if (sh.norm == ECQ_NORM_L2 && path == 2 && b <= 32768) return ECQ_ERR_PARAM;
     if (path == 0) path = (small_ok || team_ok) ? 1 : 2;
     if (path == 1 && !(small_ok || team_ok)) return ECQ_ERR_PARAM;
     pl.path = path;
@@ -131,10 +133,25 @@ static int run_quantize(const ecq_shape *sh, const float *g, const float *h, flo
     if (!aligned(g, 16) || !aligned(h, 16) || !aligned(codes, 4) || !aligned(scales, 4)) return ECQ_ERR_ALIGN;
     if (!std::isfinite(alpha) || alpha < 0.0f) return ECQ_ERR_PARAM;
     if (update_h && !(beta >= 0.0f && beta <= 1.0f)) return ECQ_ERR_PARAM;
+    // A bucket that holds the whole row (Eq. (8) without buckets) is the same as any other that
+    // does: one norm, zeros beyond the row's end change neither norm.  Take the tightest size a
+    // single-pass mapping accepts, so that the cost follows the row and not the bucket.
+    ecq_shape shape = *sh;
+    if ((int64_t)shape.bucket >= shape.n) {
+        const int64_t n8 = (shape.n + 7) / 8 * 8;
+        int64_t b = n8;
+        if (n8 <= 128) {
+            b = 8;
+            while (b < n8) b *= 2;
+        } else if (n8 < 256) {
+            b = 256;
+        }
+        shape.bucket = (int32_t)b;
+    }
     Plan plan;
-    const int ps = make_plan(*sh, tuning, &plan);
+    const int ps = make_plan(shape, tuning, &plan);
     if (ps != ECQ_OK) return ps;
-    Args a = make_args(*sh);
+    Args a = make_args(shape);
     a.g = g;
     a.h = const_cast<float *>(h);
     a.codes = codes;

@@ -452,6 +452,81 @@ __global__ void __launch_bounds__(256) k_bucket_norm_large(const Args a, const i
     }
 }
 
+// l2 norm of buckets longer than 32768 elements (two launches).  The sum of squares follows the
+// balanced tree by element index (the bucket padded with zeros to a power of two; adding a
+// zero changes nothing): a block takes an aligned piece of 8192 elements of one bucket -- the
+// lanes of each 256-element run, the four runs of a kilo-element, the eight kilo-elements --
+// and leaves the piece's sum in `pieces`; then one block per bucket adds the pieces pairwise by
+// index, level by level between two buffers, and takes the square root.
+// The caller lends the buffers: `pieces` and `spare` live in the worker's row of `codes`, which
+// the second pass overwrites afterwards.  blockIdx.x = bucket * pieces_per_bucket + piece.
+constexpr int kSumPiece = 8192;
+
+__global__ void __launch_bounds__(256) k_bucket_sumsq(const Args a, const int64_t pieces_per_bucket)
+{
+    __shared__ float wave_sum[kSumPiece / 1024][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t p = blockIdx.y;
+    const int64_t k = blockIdx.x / pieces_per_bucket;
+    const int64_t piece = blockIdx.x - k * pieces_per_bucket;
+    const int64_t bucket_begin = k * (int64_t)a.bucket;
+    int64_t bucket_end = bucket_begin + a.bucket;
+    if (bucket_end > a.n) bucket_end = a.n;
+    const int64_t begin = bucket_begin + piece * kSumPiece + (int64_t)threadIdx.x * 4;
+    const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
+    const float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
+#pragma unroll
+    for (int i = 0; i < kSumPiece / 1024; ++i) {
+        // Elements at or beyond the bucket's end read as 0 and add 0.
+        float g[4], h[4], v[4];
+        load4(grow, begin + i * 1024, bucket_end, g);
+        load4(hrow, begin + i * 1024, bucket_end, h);
+        compensate4(g, h, a.alpha, v);
+        const float run = group_sum_tree(sum_squares4(v), 64);
+        if (lane == 0) wave_sum[i][wave] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t[kSumPiece / 1024];
+#pragma unroll
+        for (int i = 0; i < kSumPiece / 1024; ++i) {
+            const float lo = wave_sum[i][0] + wave_sum[i][1];
+            const float hi = wave_sum[i][2] + wave_sum[i][3];
+            t[i] = lo + hi;
+        }
+#pragma unroll
+        for (int w = 1; w < kSumPiece / 1024; w *= 2)
+#pragma unroll
+            for (int i = 0; i + w < kSumPiece / 1024; i += 2 * w) t[i] = t[i] + t[i + w];
+        reinterpret_cast<float *>(a.codes + (int64_t)p * a.code_stride)[blockIdx.x] = t[0];
+    }
+}
+
+__global__ void __launch_bounds__(256) k_bucket_sumsq_finish(const Args a, const int64_t pieces_per_bucket)
+{
+    const uint32_t p = blockIdx.y;
+    const int64_t k = blockIdx.x;
+    const int64_t half = (pieces_per_bucket + 1) / 2;
+    float *row = reinterpret_cast<float *>(a.codes + (int64_t)p * a.code_stride);
+    float *src = row + k * pieces_per_bucket;                  // this bucket's pieces
+    float *dst = row + (int64_t)a.nb * pieces_per_bucket + k * half;   // ... and its spare buffer
+    int64_t count = pieces_per_bucket;
+    while (count > 1) {
+        const int64_t pairs = (count + 1) / 2;
+        for (int64_t i = threadIdx.x; i < pairs; i += blockDim.x) {
+            const float lo = src[2 * i];
+            const float hi = 2 * i + 1 < count ? src[2 * i + 1] : 0.0f;
+            dst[i] = lo + hi;
+        }
+        __syncthreads();                                       // the block's writes, before its next reads
+        float *t = src;
+        src = dst;
+        dst = t;
+        count = pairs;
+    }
+    if (threadIdx.x == 0) a.scales[(int64_t)p * a.scale_stride + k] = __builtin_sqrtf(src[0]);
+}
+
 __global__ void __launch_bounds__(256) k_zero_scales(const Args a)
 {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1102,6 +1177,15 @@ static void launch_quantize_r(const Args &a, const Plan &plan, bool update, hipS
         launch_team<R>(a, plan, update, st);
     } else if (plan.path == 1) {
         launch_chunk<R>(a, plan.lanes_per_bucket, 256, update, st);
+    } else if (a.norm_l2) {
+        // (make_plan admits the l2 norm here only for buckets beyond 32768 elements; the pieces'
+        // sums and the spare buffer, 6 bytes per 8192 elements, fit the row of codes many times.)
+        const int64_t pieces = cdiv((int64_t)a.bucket, kSumPiece);
+        hipLaunchKernelGGL(k_bucket_sumsq, dim3((unsigned)(a.nb * pieces), (unsigned)a.workers), dim3(256), 0, st, a,
+                           pieces);
+        hipLaunchKernelGGL(k_bucket_sumsq_finish, dim3((unsigned)a.nb, (unsigned)a.workers), dim3(256), 0, st, a,
+                           pieces);
+        launch_chunk<R>(a, 0, 256, update, st);
     } else {
         hipLaunchKernelGGL(k_zero_scales, dim3(cdiv(a.nb, 256), (unsigned)a.workers), dim3(256), 0, st, a);
         if (a.bucket < 256) {

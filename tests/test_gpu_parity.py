@@ -212,6 +212,28 @@ def test_l2_norm_buckets(E, s, bucket):
     _free_run(E, wl, 3)
 
 
+@pytest.mark.parametrize("bucket,N,s", [(40_000, 140_003, 4), (65_536, 200_000, 1), (100_000, 350_001, 7),
+                                        (1 << 20, (1 << 20) + 8192 * 3 + 5, 4)])
+def test_l2_norm_long_buckets(E, bucket, N, s):
+    """l_2 scaling of buckets beyond 32768 elements: sums of squares of 8192-element pieces, then
+    the tree over the pieces (two passes); several buckets with a short last one."""
+    wl = synth.Workload("edge", P=2, N=N, bucket=bucket, s=s, alpha=0.2, beta=0.9, iters=2, kind="normal",
+                        data_seed=bucket + s, norm="l2")
+    _free_run(E, wl, 2)
+    _free_run(E, wl, 2, fused=False)
+
+
+@pytest.mark.parametrize("N", [5, 100, 200, 5000, 40_000, 700_001])
+@pytest.mark.parametrize("norm", ["linf", "l2"])
+def test_one_norm_per_row_any_length(E, N, norm):
+    """The bucket holds the whole row, for rows of every size class (the library then takes the
+    tightest bucket one of its mappings accepts); both norms; a bucket far beyond the row."""
+    for bucket in ((N + 7) // 8 * 8, 1 << 24):
+        wl = synth.Workload("edge", P=2, N=N, bucket=bucket, s=4, alpha=0.2, beta=0.9, iters=2, kind="normal",
+                            data_seed=N, norm=norm)
+        _free_run(E, wl, 2)
+
+
 def test_l2_geometry_invariance_and_unfused(E):
     wl = synth.Workload("edge", P=2, N=5 * 2048 + 1000, bucket=2048, s=4, alpha=0.2, beta=0.9, iters=2,
                         kind="normal", data_seed=77, norm="l2")
