@@ -55,7 +55,7 @@ typedef enum {
     ECQ_ERR_NULL = -1,    /* a required pointer is NULL                                   */
     ECQ_ERR_SHAPE = -2,   /* n <= 0, n > ECQ_MAX_N or workers <= 0 or workers > 65535      */
     ECQ_ERR_LEVELS = -3,  /* s outside 1..127                                             */
-    ECQ_ERR_BUCKET = -4,  /* bucket not a positive multiple of 8, or unsupported with l2  */
+    ECQ_ERR_BUCKET = -4,  /* bucket not a positive multiple of 8                           */
     ECQ_ERR_STRIDE = -5,  /* a row stride too small for its row or not suitably divisible */
     ECQ_ERR_ALIGN = -6,   /* a base pointer is not aligned as documented                  */
     ECQ_ERR_LAUNCH = -7,  /* the HIP runtime refused a launch                             */
@@ -69,10 +69,10 @@ typedef enum {
  *   ECQ_NORM_LINF  max |v_i| over the bucket (order-free).
  *   ECQ_NORM_L2    sqrt of the sum of fl(v_i^2), the sum taken over a balanced binary tree by
  *                  element index (the bucket padded with zeros to a power of two), then one
- *                  correctly rounded square root.  Needs a bucket that is a power of two in
- *                  8..128, any multiple of 8 from 256 on, or any bucket that holds the whole
- *                  row (n <= bucket: one norm per worker, Eq. (8) without buckets); other
- *                  buckets give ECQ_ERR_BUCKET.  Squares must stay inside the binary32 range.
+ *                  correctly rounded square root.  Squares must stay inside the binary32
+ *                  range.
+ * Either norm takes any bucket that is a positive multiple of 8, up to one that holds the whole
+ * row (n <= bucket: one norm per worker, Eq. (8) without buckets).
  * Buckets beyond 32768 elements take two passes over g and h (20 instead of 12 bytes per
  * element); with ECQ_NORM_L2 the first pass borrows a few bytes per 8192 elements of the
  * worker's row of `codes`, which the second pass then overwrites as documented. */

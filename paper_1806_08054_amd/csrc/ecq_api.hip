@@ -58,9 +58,9 @@ static void set_stream_key(Args &a, uint64_t seed, uint64_t step)
     a.step_hi = (uint32_t)(step >> 32);
 }
 
-// Chooses how a bucket is mapped to lanes.  Single pass when the bucket is a power of two of
-// 8..128 elements (a group of lanes inside one wave) or when 256 <= bucket <= 32768 (a team of
-// up to 16 waves holding up to 8 float4 per lane); two passes otherwise.
+// Chooses how a bucket is mapped to lanes.  Single pass when the bucket has fewer than 256
+// elements (a group of lanes inside one wave) or at most 32768 (a team of up to 16 waves holding
+// up to 8 float4 per lane); two passes beyond that.
 int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
 {
     Plan pl{};
@@ -75,13 +75,11 @@ int make_plan(const ecq_shape &sh, const ecq_tuning *tu, Plan *plan)
         if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8 && waves != 16) return ECQ_ERR_PARAM;
         if (threads != 0 && (threads < 64 || threads > 1024 || (threads & 63) != 0)) return ECQ_ERR_PARAM;
     }
-    const bool pow2 = (b & (b - 1)) == 0;
-    const bool small_ok = pow2 && b >= 8 && b <= 128;
+    const bool small_ok = b >= 8 && b < 256;
     const bool team_ok = b >= 256 && b <= 32768;
     // The l2 sum has a fixed tree order: the single-pass mappings reproduce it, and so does the
     // two-pass route for buckets beyond 32768 (sums of 8192-element pieces, then a tree over the
-    // pieces); other buckets below 256 do not fit the lanes' tree.
-    if (sh.norm == ECQ_NORM_L2 && !(small_ok || team_ok || b > 32768)) return ECQ_ERR_BUCKET;
+    // pieces), but not the two-pass route forced on a shorter bucket.
     if (sh.norm == ECQ_NORM_L2 && path == 2 && b <= 32768) return ECQ_ERR_PARAM;
     if (path == 0) path = (small_ok || team_ok) ? 1 : 2;
     if (path == 1 && !(small_ok || team_ok)) return ECQ_ERR_PARAM;
@@ -411,7 +409,7 @@ const char *ecq_status_string(int status)
     case ECQ_ERR_NULL: return "a required pointer is NULL";
     case ECQ_ERR_SHAPE: return "n or workers out of range";
     case ECQ_ERR_LEVELS: return "s must be in 1..127";
-    case ECQ_ERR_BUCKET: return "bucket must be a positive multiple of 8 (with l2: a power of two in 8..128 or 256..32768)";
+    case ECQ_ERR_BUCKET: return "bucket must be a positive multiple of 8";
     case ECQ_ERR_STRIDE: return "a row stride is too small or not suitably divisible";
     case ECQ_ERR_ALIGN: return "a base pointer is not aligned as documented";
     case ECQ_ERR_LAUNCH: return "the HIP runtime refused a launch";

@@ -36,7 +36,7 @@ struct Args {
 // Resolved launch plan for the quantise(+update) entry points.
 struct Plan {
     int path;              // 1 = bucket in registers, 2 = two-pass
-    int lanes_per_bucket;  // path 1, bucket < 256: lanes sharing a bucket (power of two)
+    int lanes_per_bucket;  // path 1, bucket < 256: lanes sharing a bucket (bucket / 4)
     int waves_per_bucket;  // path 1, bucket >= 256
     int vec_per_lane;      // path 1: float4 per lane (1, 2, 4, 8)
     int block_threads;

@@ -318,58 +318,64 @@ __global__ void __launch_bounds__(1024) k_fused_team(const Args a, const int w_s
 }
 
 // ---------------------------------------------------------------------------------------------
-// A wave owns two consecutive chunks of 256 elements, a lane one float4 of each (all loads are
-// issued before any is used).  Two uses:
-//   lanes_per_bucket > 0 : single pass for small power-of-two buckets (8..128 elements): the
-//                          norm is a max over aligned groups of lanes_per_bucket lanes;
-//   lanes_per_bucket == 0: second pass of the two-pass route: the norm is read from scales.
+// A lane owns one float4 of each of two consecutive chunks of its wave (all loads are issued
+// before any is used).  The 64 lanes of a wave form slots of `slot_lanes` lanes (a power of two)
+// and a slot covers `span` consecutive elements with its first span/4 lanes:
+//   single pass, buckets of 8..248 elements: a slot is one bucket (span = bucket); slot_lanes is
+//       the bucket's lane count rounded up to a power of two, so the norm is a max (or the
+//       index tree of squares, the idle lanes standing for the padding zeros) over the slot;
+//   second pass of the two-pass route: one slot of 64 lanes, span 256, norms read from scales.
+// A chunk is what the wave's slots cover together: (64 / slot_lanes) * span elements.
 // ---------------------------------------------------------------------------------------------
 template <int R, bool UPDATE>
-__global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int lanes_per_bucket)
+__global__ void __launch_bounds__(256) k_quant_chunk(const Args a, const int slot_lanes, const int span,
+                                                     const int read_norms)
 {
     __shared__ float xi_tab[256];
     if constexpr (R != 2) fill_sxi_table(xi_tab, a.s);
 
-    constexpr int J = kChunksPerWave;                          // consecutive chunks of 256 elements per wave
+    constexpr int J = kChunksPerWave;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int slots = 64 / slot_lanes;                         // per wave
+    const int64_t chunk_elems = (int64_t)slots * span;
     const int64_t chunk0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave) * J;
     const uint32_t p = blockIdx.y;
-    if (chunk0 * 256 >= a.n) return;                           // wave-uniform
+    if (chunk0 * chunk_elems >= a.n) return;                   // wave-uniform
 
+    const int slot = lane / slot_lanes, in_slot = lane & (slot_lanes - 1);
+    const bool used = in_slot * 4 < span;                      // (idle lanes read nothing and store nothing)
     const float *__restrict__ grow = a.g + (int64_t)p * a.gh_stride;
     float *__restrict__ hrow = a.h + (int64_t)p * a.gh_stride;
     float g[J][4], h[J][4], v[J][4];
     uint32_t mx[J];
+    int64_t elem[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) {                              // all loads first (nothing is read beyond n)
-        const int64_t elem = (chunk0 + j) * 256 + lane * 4;
-        load4(grow, elem, a.n, g[j]);
-        load4(hrow, elem, a.n, h[j]);
+        elem[j] = used ? ((chunk0 + j) * slots + slot) * span + in_slot * 4 : a.n;
+        load4(grow, elem[j], a.n, g[j]);
+        load4(hrow, elem[j], a.n, h[j]);
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) mx[j] = compensate4(g[j], h[j], a.alpha, v[j]);
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        if ((chunk0 + j) * 256 >= a.n) break;                  // wave-uniform
-        const int64_t elem = (chunk0 + j) * 256 + lane * 4;
-        const int64_t rest = a.n - elem;
-        const int valid = rest < 0 ? 0 : (rest > 4 ? 4 : (int)rest);
+        if ((chunk0 + j) * chunk_elems >= a.n) break;          // wave-uniform
+        const int64_t rest = a.n - elem[j];
+        const int valid = rest <= 0 ? 0 : (rest > 4 ? 4 : (int)rest);
         float scale;
-        const int64_t k = elem / a.bucket;
-        if (lanes_per_bucket > 0) {
-            scale = a.norm_l2 ? __builtin_sqrtf(group_sum_tree(sum_squares4(v[j]), lanes_per_bucket))
-                              : __uint_as_float(group_max(mx[j], lanes_per_bucket));
-            if (valid > 0 && (lane & (lanes_per_bucket - 1)) == 0)
-                a.scales[(int64_t)p * a.scale_stride + k] = scale;
+        if (!read_norms) {
+            scale = a.norm_l2 ? __builtin_sqrtf(group_sum_tree(sum_squares4(v[j]), slot_lanes))
+                              : __uint_as_float(group_max(mx[j], slot_lanes));
+            if (valid > 0 && in_slot == 0) a.scales[(int64_t)p * a.scale_stride + ((chunk0 + j) * slots + slot)] = scale;
         } else {
-            scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + k] : 0.0f;
+            scale = valid > 0 ? a.scales[(int64_t)p * a.scale_stride + elem[j] / a.bucket] : 0.0f;
         }
         const Rounder<R> rounder(scale, a.s, xi_tab);
-        const U4 words = philox4x32_10((uint32_t)(elem >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
+        const U4 words = philox4x32_10((uint32_t)(elem[j] >> 2), p, a.step_lo, a.step_hi, a.key0, a.key1);
         const uint32_t bits = quantize4<R, UPDATE>(g[j], h[j], v[j], valid, rounder, a.beta, words);
-        store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem, valid, bits, lane);
-        if (UPDATE) store4(hrow, elem, a.n, h[j]);
+        store_codes<R>(a.codes + (int64_t)p * a.code_stride, a.row_bytes, elem[j], valid, bits, lane);
+        if (UPDATE) store4(hrow, elem[j], a.n, h[j]);
     }
 }
 
@@ -1162,12 +1168,21 @@ static void launch_team(const Args &a, const Plan &plan, bool update, hipStream_
 template <int R>
 static void launch_chunk(const Args &a, int lanes_per_bucket, int block_threads, bool update, hipStream_t st)
 {
+    // lanes_per_bucket = 0: second pass of the two-pass route; else a bucket of 8..248 elements.
+    int slot_lanes = 64, span = 256;
+    if (lanes_per_bucket > 0) {
+        slot_lanes = 1;
+        while (slot_lanes < lanes_per_bucket) slot_lanes *= 2;
+        span = lanes_per_bucket * 4;
+    }
+    const int64_t chunk_elems = (int64_t)(64 / slot_lanes) * span;
     const int waves = block_threads / 64;
-    const dim3 grid(cdiv(cdiv(a.n, 256), waves * kChunksPerWave), (unsigned)a.workers);
+    const dim3 grid(cdiv(cdiv(a.n, chunk_elems), waves * kChunksPerWave), (unsigned)a.workers);
+    const int read_norms = lanes_per_bucket == 0;
     if (update)
-        hipLaunchKernelGGL((k_quant_chunk<R, true>), grid, dim3(block_threads), 0, st, a, lanes_per_bucket);
+        hipLaunchKernelGGL((k_quant_chunk<R, true>), grid, dim3(block_threads), 0, st, a, slot_lanes, span, read_norms);
     else
-        hipLaunchKernelGGL((k_quant_chunk<R, false>), grid, dim3(block_threads), 0, st, a, lanes_per_bucket);
+        hipLaunchKernelGGL((k_quant_chunk<R, false>), grid, dim3(block_threads), 0, st, a, slot_lanes, span, read_norms);
 }
 
 template <int R>

@@ -168,7 +168,7 @@ def test_levels_and_buckets(E, s, bucket):
 
 
 @pytest.mark.parametrize("bucket", [16, 24, 32, 40, 96, 128, 248, 256, 264, 2048, 4096, 8192, 16384, 32768, 40000,
-                                    65536, 100_000, 1 << 20])
+                                    65536, 100_000, 1 << 20, 56, 136, 200])
 def test_bucket_routes(E, bucket):
     """Every mapping of buckets to lanes: lane groups (powers of two up to 128), teams of waves
     (256 ... 32768), and the two-pass route with its two first passes (other buckets below 256;
@@ -203,7 +203,7 @@ def test_tiny_lengths(E, N, s):
 # ------------------------------------------------------------------ l_2 scaling ------------
 
 @pytest.mark.parametrize("s", [1, 4, 7])
-@pytest.mark.parametrize("bucket", [8, 32, 128, 256, 512, 1000, 1024, 4096, 8192, 16384, 32768])
+@pytest.mark.parametrize("bucket", [8, 24, 32, 40, 96, 128, 136, 248, 256, 512, 1000, 1024, 4096, 8192, 16384, 32768])
 def test_l2_norm_buckets(E, s, bucket):
     """l_2 scaling (tree sum of squares by index, one square root) on every single-pass route,
     ragged tails included; the paper's own setting is l_2 with s = 4 (Section 6)."""
