@@ -268,6 +268,10 @@ def test_launch_geometry_invariance(E):
     for path, waves, threads in [(1, 1, 64), (1, 1, 256), (1, 2, 256), (1, 4, 256), (1, 8, 512),
                                  (1, 8, 1024), (1, 16, 1024), (2, 0, 0)]:
         _free_run(E, wl, 2, tuning=E.Tuning(path, waves, threads, 0))
+    # The two-pass route on request for buckets below 256 elements (segmented wave maximum).
+    for bucket in (8, 40, 96, 248):
+        small = synth.scaled(wl, bucket=bucket)
+        _free_run(E, small, 2, tuning=E.Tuning(2, 0, 0, 0))
 
 
 def test_unfused_equals_fused(E):
