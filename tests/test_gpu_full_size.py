@@ -172,6 +172,23 @@ def test_resnet50_tight_rows(E):
     _run(E, wl, full_iters=2, full_rows=list(range(wl.P)), aligned=False)
 
 
+def test_resnet50_l2(E):
+    """Workload 3's shape with l_2 scaling, the setting of the paper's CNN experiments
+    (Section 6.2): 3 iterations, every element."""
+    wl = synth.scaled(synth.WORKLOADS["resnet50"], iters=3, norm="l2")
+    _run(E, wl, full_iters=3, full_rows=list(range(wl.P)), samples=8)
+
+
+@pytest.mark.parametrize("norm", ["linf", "l2"])
+def test_resnet50_one_norm_per_row(E, norm):
+    """Workload 3's rows quantised as Eq. (8) states it, without buckets: one norm per worker
+    (two passes over g and h; for l_2 the tree over 8192-element pieces): 2 iterations, every
+    element."""
+    wl = synth.WORKLOADS["resnet50"]
+    wl = synth.scaled(wl, iters=2, norm=norm, bucket=(wl.N + 7) // 8 * 8)
+    _run(E, wl, full_iters=2, full_rows=list(range(wl.P)), samples=1)
+
+
 def test_alexnet_full(E):
     """Workload 4: 10 free-running iterations; all 16 workers in full for the first 3,
     sampled buckets of all workers for all 10."""
