@@ -80,66 +80,65 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
 {
     __shared__ unsigned long long weight[512];
     __shared__ unsigned long long first_code[64];
+    __shared__ unsigned long long leaf_key[256];               // occupied levels in the order (weight, number)
     __shared__ unsigned int len_count[64];
     __shared__ short parent[512];
-    __shared__ unsigned char live[512];
     __shared__ unsigned char len_of[256];
 
     const int lane = threadIdx.x;
     const int64_t row = (int64_t)blockIdx.x * table_stride;
     for (int i = lane; i < 512; i += 64) {
-        const unsigned long long w = i < bins ? counts[row + i] : 0ull;
-        weight[i] = w;
+        weight[i] = i < bins ? counts[row + i] : 0ull;
         parent[i] = -1;
-        live[i] = w > 0 ? 1 : 0;
     }
     len_count[lane] = 0u;
     __syncthreads();
 
+    // A node's place in the order (weight, number) as one integer: weights stay below 2^35 (a
+    // row sums to at most 2^34), numbers below 2^9.
+    auto key_of = [&](int node) -> unsigned long long { return (weight[node] << 9) | (unsigned long long)node; };
+    // Sort the occupied levels by counting, for every one, the occupied levels before it.
     int alive = 0;
-    for (int i = lane; i < bins; i += 64) alive += live[i];
+    for (int i = lane; i < bins; i += 64) {
+        if (weight[i] == 0ull) continue;
+        ++alive;
+        const unsigned long long mine = key_of(i);
+        int rank = 0;
+        for (int j = 0; j < bins; ++j) rank += (weight[j] != 0ull && key_of(j) < mine) ? 1 : 0;
+        leaf_key[rank] = mine;
+    }
     for (int d = 1; d < 64; d <<= 1) alive += __shfl_xor(alive, d, 64);
     const bool single = alive == 1;
+    __syncthreads();
 
-    // alive - 1 merges; node numbers stay below bins + alive - 1 <= 509.
-    int nodes = bins;
-    while (alive > 1) {
-        int pick[2];
+    // The two nodes that come first in the order (weight, number) are merged into a node with
+    // the next free number, alive - 1 times (numbers stay below bins + alive - 1 <= 509).  The
+    // merged nodes come into being in that very order (their weights never decrease, their
+    // numbers grow), so the first of all live nodes is always the first leaf not yet taken or
+    // the first merged node not yet taken: one lane walks the two queues.
+    if (lane == 0) {
+        int next_leaf = 0, next_made = 0, made = 0;
+        for (int m = 0; m + 1 < alive; ++m) {
+            int pick[2];
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            // First live node in the order (weight, number): lanes scan their nodes in
-            // ascending number, so "<" keeps the lowest number among equal weights.
-            unsigned long long bw = ~0ull;
-            int bi = 0x7FFFFFFF;
-            for (int i = lane; i < nodes; i += 64)
-                if (live[i] && (bi == 0x7FFFFFFF || weight[i] < bw)) {
-                    bw = weight[i];
-                    bi = i;
-                }
-            for (int d = 1; d < 64; d <<= 1) {
-                const unsigned long long ow = __shfl_xor(bw, d, 64);
-                const int oi = __shfl_xor(bi, d, 64);
-                const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || ow < bw || (ow == bw && oi < bi));
-                if (take) {
-                    bw = ow;
-                    bi = oi;
+            for (int k = 0; k < 2; ++k) {
+                const unsigned long long lk = next_leaf < alive ? leaf_key[next_leaf] : ~0ull;
+                const unsigned long long mk = next_made < made ? key_of(bins + next_made) : ~0ull;
+                if (lk < mk) {
+                    pick[k] = (int)(lk & 511ull);
+                    ++next_leaf;
+                } else {
+                    pick[k] = bins + next_made;
+                    ++next_made;
                 }
             }
-            pick[k] = bi;                                      // the same in every lane
-            if (lane == 0 && bi < nodes) live[bi] = 0;
-            __syncthreads();
+            weight[bins + made] = weight[pick[0]] + weight[pick[1]];
+            parent[pick[0]] = (short)(bins + made);
+            parent[pick[1]] = (short)(bins + made);
+            ++made;
         }
-        if (pick[0] >= nodes || pick[1] >= nodes) break;       // cannot happen: alive counts the live nodes
-        if (lane == 0) {
-            weight[nodes] = weight[pick[0]] + weight[pick[1]];
-            parent[pick[0]] = (short)nodes;
-            parent[pick[1]] = (short)nodes;
-            live[nodes] = 1;
-        }
-        ++nodes;
-        --alive;
-        __syncthreads();
     }
+    __syncthreads();
 
     for (int c = lane; c < 256; c += 64) {
         int depth = 0;
