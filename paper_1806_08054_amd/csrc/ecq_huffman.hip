@@ -964,17 +964,39 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
                 res >>= (hit >> 8);
                 have -= (hit >> 8);
             } else {
-                // Longer than the table covers: walk the canonical code one bit at a time.
-                unsigned long long word = 0;
-                for (int l = 1; l <= kMaxLen; ++l) {
-                    if (have == 0u) refill();
-                    word = (word << 1) | (res & 1ull);
-                    res >>= 1;
-                    --have;
-                    const unsigned long long idx = word - tab.first_code[l];
-                    if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
+                // Longer than the table covers.  Up to 32 bits: the next 32 stream bits, first one
+                // on top, give the candidate codeword of every length by one shift; the canonical
+                // code says which length holds it.
+                if (have < 32u) refill();
+                const unsigned int top = __brev((unsigned int)res);
+                int l = kFastBits + 1;
+                bool found = false;
+                for (; l <= 32; ++l) {
+                    const unsigned long long cand = top >> (32 - l);
+                    const unsigned long long idx = cand - tab.first_code[l];
+                    if (tab.count[l] && cand >= tab.first_code[l] && idx < tab.count[l]) {
                         c = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
+                        res >>= l;
+                        have -= (unsigned int)l;
+                        found = true;
                         break;
+                    }
+                }
+                if (!found) {
+                    // Beyond 32 bits (levels rarer than one in 2^32): one bit at a time.
+                    unsigned long long word = top;
+                    res >>= 32;
+                    have -= 32u;
+                    for (l = 33; l <= kMaxLen; ++l) {
+                        if (have == 0u) refill();
+                        word = (word << 1) | (res & 1ull);
+                        res >>= 1;
+                        --have;
+                        const unsigned long long idx = word - tab.first_code[l];
+                        if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
+                            c = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
+                            break;
+                        }
                     }
                 }
             }
