@@ -154,6 +154,9 @@ def main():
     add_ms = timed(lambda: E.ecq_calib_add(cal_a, cal_b, cal_o, n_cal))
     copy_ms = timed(lambda: E.ecq_calib_copy(cal_a, cal_o, n_cal))
     del cal_o
+    # The aggregation's access pattern (P rows of codes read side by side, one float written per
+    # element) without its arithmetic.
+    gather_ms = timed(lambda: E.ecq_calib_gather(sh, codes, out))
 
     for t in range(args.warmup):
         step(t)
@@ -201,7 +204,9 @@ def main():
                               "bytes": deq_b},
         "calibration": {"add_2r1w_GBps": round(12 * n_cal / (add_ms * 1e-3) / 1e9, 1),
                         "copy_1r1w_GBps": round(8 * n_cal / (copy_ms * 1e-3) / 1e9, 1),
-                        "floats": n_cal},
+                        "floats": n_cal,
+                        "aggregate_pattern_GBps": round((P * E.row_bytes(N, wl.s) + 4 * N) / (gather_ms * 1e-3) / 1e9, 1),
+                        "aggregate_pattern_ms": round(gather_ms, 4)},
         "roofline": {"bound": "hbm", "kernel": "ecq_quantize_update (fused single pass)",
                      "achieved": round(fused_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(fused_gbps / HBM_PEAK_GBPS, 4), "traffic": None},

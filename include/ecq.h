@@ -283,6 +283,15 @@ int ecq_check_division(int per_divisor, uint32_t salt, uint64_t *mismatches, voi
 int ecq_calib_add(const float *a, const float *b, float *out, int64_t n, void *stream);
 int ecq_calib_copy(const float *a, float *out, int64_t n, void *stream);
 
+/*
+ * Calibration of the aggregation's access pattern, not part of the method: reads every
+ * worker's row of `codes` exactly as ecq_dequant_aggregate does (a wave takes 128*r contiguous
+ * bytes of each of the P rows for its 1024 outputs), adds the words up and writes n floats,
+ * with no decoding and no norms.  codes, out as for ecq_dequant_aggregate; only the whole runs
+ * of 1024 outputs are written.
+ */
+int ecq_calib_gather(const ecq_shape *shape, const uint8_t *codes, float *out, void *stream);
+
 /* Static, human-readable text for a status value. */
 const char *ecq_status_string(int status);
 

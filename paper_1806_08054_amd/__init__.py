@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     code_bits,
     ecq_calib_add,
     ecq_calib_copy,
+    ecq_calib_gather,
     ecq_check_division,
     ecq_dequant_aggregate,
     ecq_dequant_aggregate_sgd,

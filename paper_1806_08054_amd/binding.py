@@ -86,13 +86,14 @@ def lib() -> C.CDLL:
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
+        L.ecq_calib_gather.argtypes = [shp, vp, vp, vp]
         L.ecq_status_string.argtypes = [C.c_int]
         L.ecq_status_string.restype = C.c_char_p
         L.ecq_version.argtypes = []
         for name in ("ecq_code_bits", "ecq_row_bytes", "ecq_num_buckets", "ecq_check_shape", "ecq_quantize",
                      "ecq_error_update", "ecq_quantize_update", "ecq_quantize_update_ex",
                      "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits", "ecq_check_division",
-                     "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy", "ecq_huffman_num_tiles",
+                     "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy", "ecq_calib_gather", "ecq_huffman_num_tiles",
                      "ecq_huffman_build", "ecq_huffman_encode", "ecq_huffman_decode",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
@@ -227,3 +228,7 @@ def ecq_calib_add(a, b, out, n: int, stream=None) -> None:
 
 def ecq_calib_copy(a, out, n: int, stream=None) -> None:
     _check(lib().ecq_calib_copy(_ptr(a), _ptr(out), n, _stream(stream)), "ecq_calib_copy")
+
+
+def ecq_calib_gather(shape: Shape, codes, out, stream=None) -> None:
+    _check(lib().ecq_calib_gather(C.byref(shape), _ptr(codes), _ptr(out), _stream(stream)), "ecq_calib_gather")

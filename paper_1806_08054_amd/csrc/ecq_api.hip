@@ -402,6 +402,18 @@ int ecq_calib_copy(const float *a, float *out, int64_t n, void *stream)
     return ecq::launch_calib_copy(a, out, n, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
 }
 
+int ecq_calib_gather(const ecq_shape *shape, const uint8_t *codes, float *out, void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!codes || !out) return ECQ_ERR_NULL;
+    if (!ecq::aligned(out, 16) || !ecq::aligned(codes, 4)) return ECQ_ERR_ALIGN;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    a.out = out;
+    return ecq::launch_calib_gather(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ECQ_OK : ECQ_ERR_LAUNCH;
+}
+
 const char *ecq_status_string(int status)
 {
     switch (status) {

@@ -68,6 +68,7 @@ hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, u
 hipError_t launch_calib_add(const float *a, const float *b, float *out, int64_t n,
                             hipStream_t stream);
 hipError_t launch_calib_copy(const float *a, float *out, int64_t n, hipStream_t stream);
+hipError_t launch_calib_gather(const Args &a, hipStream_t stream);
 
 static inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
 

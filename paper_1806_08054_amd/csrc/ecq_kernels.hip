@@ -1302,6 +1302,50 @@ hipError_t launch_calib_add(const float *x, const float *y, float *out, int64_t 
     return hipGetLastError();
 }
 
+// The aggregation kernel's loads and stores without its arithmetic: four workers' code words
+// per lane in flight, their sum written as the lane's 16 outputs in the same float4 pattern.
+template <int R>
+__global__ void __launch_bounds__(256) k_calib_gather(const Args a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
+    if (base + kAggRun > a.n) return;
+    const uint8_t *__restrict__ cptr = a.codes + ((base * R) >> 3) + lane * (2 * R);
+    uint32_t sum = 0;
+    int p = 0;
+    for (; p + 4 <= a.workers; p += 4) {
+        Codes16<R> cd[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cd[u].load(cptr + (int64_t)(p + u) * a.code_stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < Codes16<R>::kWords; ++i) sum += cd[u].w[i];
+    }
+    for (; p < a.workers; ++p) {
+        Codes16<R> one;
+        one.load(cptr + (int64_t)p * a.code_stride);
+#pragma unroll
+        for (int i = 0; i < Codes16<R>::kWords; ++i) sum += one.w[i];
+    }
+    const float r = (float)sum;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f4 o;
+        o.x = r; o.y = r; o.z = r; o.w = r;
+        __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(a.out + base + 4 * (q * 64 + lane)));
+    }
+}
+
+hipError_t launch_calib_gather(const Args &a, hipStream_t stream)
+{
+    const dim3 grid(cdiv(cdiv(a.n, kAggRun), 4));
+#define CALL(RR) hipLaunchKernelGGL((k_calib_gather<RR>), grid, dim3(256), 0, stream, a)
+    ECQ_DISPATCH_R(a.r, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
 hipError_t launch_calib_copy(const float *x, float *out, int64_t n, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_calib_copy, dim3(cdiv(n, 1024)), dim3(256), 0, stream, x, out, n);

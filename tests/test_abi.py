@@ -83,6 +83,7 @@ def test_entry_points_reject_bad_arguments_before_any_launch(E):
     assert lib.ecq_dequant_aggregate(C.byref(sh), None, None, None, None) == -1
     assert lib.ecq_philox_words(1, 0, 0, 0, 16, None, None) == -1
     assert lib.ecq_calib_add(None, None, None, 16, None) == -1
+    assert lib.ecq_calib_gather(C.byref(sh), None, None, None) == -1
     fake = C.c_void_p(0x1000)
     assert lib.ecq_quantize_update(C.byref(sh), fake, fake, -1.0, 1.0, 1, 0, fake, fake, None) == -8
     assert lib.ecq_quantize_update(C.byref(sh), fake, fake, 1.0, 2.0, 1, 0, fake, fake, None) == -8

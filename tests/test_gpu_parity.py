@@ -357,6 +357,25 @@ def test_aggregate_many_workers_long_rows(E, P, s, bucket):
     assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
 
 
+def test_calibration_gather(E):
+    """The aggregation-pattern calibration kernel reads the rows it is given and nothing else:
+    every whole run of 1024 outputs holds the sum of the P rows' code words of its lane."""
+    P, N, s = 5, 3 * 1024 + 100, 7
+    sh = E.Shape.packed(N, P, 512, s)
+    rng = np.random.default_rng(1)
+    codes_np = rng.integers(0, 256, size=(P, sh.code_stride), dtype=np.uint8)
+    out = torch.full((N,), -3.0, device="cuda")
+    E.ecq_calib_gather(sh, _dev(codes_np), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    words = codes_np[:, : 3 * 1024 // 2].copy().view(np.uint32).reshape(P, 3, 64, 2)   # r = 4: 8 bytes per lane
+    want = words.astype(np.uint64).sum(axis=(0, 3)) & 0xFFFFFFFF                       # [run][lane]
+    for run in range(3):
+        block = got[run * 1024:(run + 1) * 1024].reshape(4, 64, 4)
+        assert np.array_equal(block, np.broadcast_to(want[run].astype(np.float32)[None, :, None], (4, 64, 4)))
+    assert np.all(got[3 * 1024:] == -3.0)
+
+
 # ------------------------------------------------------------------ model update -----------
 
 @pytest.mark.parametrize("s,bucket,N,P", [(1, 512, 5000, 4), (4, 1024, 3 * 1024 + 77, 3), (3, 24, 1000, 5),
