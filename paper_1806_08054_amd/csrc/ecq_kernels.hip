@@ -805,7 +805,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     // One worker's norms for the lane's first and second 8 outputs.
     auto norms_of = [&](const float *__restrict__ row, float &lo, float &hi) {
         lo = NORMS == 0 ? row[k_wave] : row[k_lane];
-        hi = NORMS == 2 ? row[k_half] : lo;
+        if constexpr (NORMS == 2) hi = row[k_half];            // (else `hi` is never read)
     };
 
     float acc[16];
@@ -833,18 +833,19 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
             for (int u = 0; u < U; ++u) {
                 cd[u] = cd_next[u];
                 lo[u] = lo_next[u];
-                hi[u] = hi_next[u];
+                if constexpr (NORMS == 2) hi[u] = hi_next[u];
             }
             if (b + 1 < batches) request(cd_next, lo_next, hi_next);
     #pragma unroll
-            for (int u = 0; u < U; ++u) agg_add16<R>(table, pair, lane_off, cd[u], lo[u], hi[u], acc);
+            for (int u = 0; u < U; ++u)
+                agg_add16<R>(table, pair, lane_off, cd[u], lo[u], NORMS == 2 ? hi[u] : lo[u], acc);
         }
         for (int p = batches * U; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
             one.load(cptr);
             norms_of(srow, one_lo, one_hi);
-            agg_add16<R>(table, pair, lane_off, one, one_lo, one_hi, acc);
+            agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
             srow += a.scale_stride;
         }
@@ -861,7 +862,8 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
                 norms_of(srow + u * a.scale_stride, lo[u], hi[u]);
             }
 #pragma unroll
-            for (int u = 0; u < V; ++u) agg_add16<R>(table, pair, lane_off, cd[u], lo[u], hi[u], acc);
+            for (int u = 0; u < V; ++u)
+                agg_add16<R>(table, pair, lane_off, cd[u], lo[u], NORMS == 2 ? hi[u] : lo[u], acc);
             cptr += V * a.code_stride;
             srow += V * a.scale_stride;
         }
@@ -870,7 +872,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
             float one_lo, one_hi;
             one.load(cptr);
             norms_of(srow, one_lo, one_hi);
-            agg_add16<R>(table, pair, lane_off, one, one_lo, one_hi, acc);
+            agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
             srow += a.scale_stride;
         }
