@@ -295,12 +295,13 @@ struct Codes16 {
 #pragma unroll
             for (int i = 0; i < R / 2; ++i) w[i] = reinterpret_cast<const uint32_t *>(src)[i];
         } else {
+            // 2*R bytes at a 2-byte aligned address: whole dwords (global loads need no natural
+            // alignment here), then one short.
 #pragma unroll
-            for (int i = 0; i < kWords; ++i) {
-                const uint32_t lo = reinterpret_cast<const uint16_t *>(src)[2 * i];
-                const uint32_t hi = (2 * i + 1 < R) ? reinterpret_cast<const uint16_t *>(src)[2 * i + 1] : 0u;
-                w[i] = lo | (hi << 16);
-            }
+            for (int i = 0; i < kWords - 1; ++i) __builtin_memcpy(&w[i], src + 4 * i, 4);
+            uint16_t last;
+            __builtin_memcpy(&last, src + 4 * (kWords - 1), 2);
+            w[kWords - 1] = last;
         }
     }
     // The same for a lane at the ragged end of a row: bytes at or beyond row_bytes read as 0.
