@@ -200,6 +200,37 @@ def test_tiny_lengths(E, N, s):
     _free_run(E, wl, 2)
 
 
+def _random_workloads(count, seed):
+    rng = np.random.default_rng(seed)
+    levels = [1, 1, 1, 2, 3, 4, 4, 7, 8, 15, 16, 31, 40, 127]
+    out = []
+    for i in range(count):
+        N = int(rng.choice([rng.integers(1, 300), rng.integers(300, 9000), rng.integers(9000, 90_000)]))
+        kind = rng.integers(4)
+        if kind == 0:
+            bucket = 8 * int(rng.integers(1, 32))                       # lane groups
+        elif kind == 1:
+            bucket = 8 * int(rng.integers(32, 4097))                    # teams of waves
+        elif kind == 2:
+            bucket = 8 * int(rng.integers(4097, 12_000))                # two passes
+        else:
+            bucket = (N + 7) // 8 * 8 + 8 * int(rng.integers(0, 3))     # one norm per row
+        out.append(synth.Workload(f"random{i}", P=int(rng.integers(1, 10)), N=N, bucket=bucket,
+                                  s=int(rng.choice(levels)), alpha=float(np.float32(rng.uniform(0, 1.2))),
+                                  beta=float(np.float32(rng.uniform(0, 1))), iters=2,
+                                  kind=str(rng.choice(["normal", "student_t"])), data_seed=1000 + i,
+                                  norm=str(rng.choice(["linf", "l2"]))))
+    return out
+
+
+@pytest.mark.parametrize("wl", _random_workloads(48, seed=2024), ids=lambda w: f"{w.name}-P{w.P}-N{w.N}-b{w.bucket}-s{w.s}-{w.norm}")
+def test_random_shapes(E, wl):
+    """Seeded random corners of the configuration space: worker counts, lengths, every class of
+    bucket size, levels, both norms, alpha and beta; fused and unfused entry points."""
+    _free_run(E, wl, 2, pad=int(wl.N % 3))
+    _free_run(E, wl, 2, fused=False)
+
+
 # ------------------------------------------------------------------ l_2 scaling ------------
 
 @pytest.mark.parametrize("s", [1, 4, 7])
