@@ -581,6 +581,29 @@ def test_huffman_matches_oracle(E, s, bucket, N, P, kind):
     assert bits < P * N * E.code_bits(s)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_huffman_random_messages(E, case):
+    """Seeded random messages: level distributions from nearly flat to one dominant level, any
+    number of unused levels, lengths around tile, step and run boundaries."""
+    rng = np.random.default_rng(7000 + case)
+    s = int(rng.choice([1, 1, 2, 3, 4, 7, 8, 15, 16, 31, 63, 127]))
+    P = int(rng.integers(1, 4))
+    N = int(rng.choice([rng.integers(1, 2000), rng.integers(2000, 20_000), 16_384 * int(rng.integers(1, 4)) + int(rng.integers(-3, 4)),
+                        rng.integers(20_000, 150_000)]))
+    q = np.zeros((P, N), np.int8)
+    for p in range(P):
+        w = rng.random(2 * s + 1) ** float(rng.choice([1.0, 4.0, 16.0, 64.0]))
+        w[rng.random(2 * s + 1) < 0.3] = 0.0                    # unused levels
+        w[s] += float(rng.choice([0.0, 1.0, 20.0]))             # level 0 often dominates
+        if w.sum() == 0.0:
+            w[s] = 1.0
+        q[p] = rng.choice(np.arange(-s, s + 1), size=N, p=w / w.sum()).astype(np.int8)
+    sh = E.Shape.packed(N, P, 512, s)
+    packed = oracle.pack_rows(q, s)
+    codes = _dev(np.pad(packed, ((0, 0), (0, sh.code_stride - packed.shape[1]))))
+    _huffman_roundtrip(E, sh, P, N, s, codes, q)
+
+
 def test_huffman_degenerate_rows(E):
     """A message with a single occupied level (all-zero gradient: every level 0) costs one bit
     per element; a two-level message costs one bit per element too."""
