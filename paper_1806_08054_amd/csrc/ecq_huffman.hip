@@ -27,7 +27,7 @@ constexpr int kMaxLen = 63;                                    // longest codewo
 constexpr int kFastBits = 10;                                  // decode: direct table on 10 stream bits
 constexpr int kRunTiles = 16;                                  // encoder: consecutive tiles (one "run") per wave
 constexpr int kRunElems = kRunTiles * ECQ_HUFFMAN_TILE;
-constexpr int kDecodeThreads = 128;                            // decode: tiles (lanes) per block
+constexpr int kDecodeThreads = 256;                            // decode: tiles (lanes) per block
 constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
 constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
 
