@@ -69,8 +69,10 @@ typedef enum {
  *   ECQ_NORM_LINF  max |v_i| over the bucket (order-free).
  *   ECQ_NORM_L2    sqrt of the sum of fl(v_i^2), the sum taken over a balanced binary tree by
  *                  element index (the bucket padded with zeros to a power of two), then one
- *                  correctly rounded square root.  Squares must stay inside the binary32
- *                  range.
+ *                  correctly rounded square root.  Squares must not overflow binary32.  Squares
+ *                  that underflow are handled as Eq. (8)-(9) read: a computed norm of 0 gives
+ *                  level 0 everywhere, and an element that exceeds the computed norm (possible
+ *                  when its square is denormal) takes level s, the end of the grid.
  * Either norm takes any bucket that is a positive multiple of 8, up to one that holds the whole
  * row (n <= bucket: one norm per worker, Eq. (8) without buckets).
  * Buckets beyond 32768 elements take two passes over g and h (20 instead of 12 bytes per
@@ -130,7 +132,8 @@ int ecq_quantize(const ecq_shape *shape, const float *g, const float *h, float a
  * Eq. (6): h <- beta*h + (g - g~), with g~ decoded from (codes, scales) as
  * scales[p][i/b] * fl(|q|/s) carrying the sign of q = code - s (Eq. (8)).
  *   g      in      device, [P][gh_stride] float32, 16-byte aligned.
- *   codes, scales  in, as written by ecq_quantize.
+ *   codes, scales  in, as written by ecq_quantize.  A code beyond 2s (no message written by
+ *                  this library holds one) decodes as level 0 here and in the aggregation.
  *   beta   in      time-decaying factor, 0 <= beta <= 1.
  *   h      in/out  device, [P][gh_stride] float32, 16-byte aligned, updated in place.
  */
@@ -269,7 +272,8 @@ int ecq_philox_words(uint64_t seed, uint64_t step, uint32_t p, uint64_t i0, int6
  * reciprocal instead of one full division per element.  This call compares that routine with
  * the plain correctly rounded binary32 division for every divisor significand (2^23 of them,
  * exponents drawn over the whole normal range from `salt`) and `per_divisor` numerators each
- * (same binade, far smaller, denormal, equal), in both of the forms the kernels use, and adds
+ * (same binade, far smaller, denormal, equal, up to an eighth larger), in both of the forms the
+ * kernels use, and adds
  * the number of differing results to *mismatches (device, uint64, zeroed by the call).
  * Expected: 0.
  */

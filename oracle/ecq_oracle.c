@@ -29,7 +29,9 @@
  *     other choice the paper names, and the one its Lemma 1 covers) is sqrt of the sum of the
  *     squares fl(v_i*v_i), the sum taken over a balanced binary tree by element index (the
  *     bucket padded with zeros to a power of two), then one correctly rounded square root.
- *     (The computed l_2 norm is never below max|v_i|, so the ratio stays <= 1 here too.)
+ *     (While the squares are normal numbers the computed l_2 norm is never below max|v_i| and
+ *     the ratio stays <= 1; a square that underflows can leave the norm below the element, or
+ *     at 0: the level is then s, the end of the grid of Eq. (8), or 0 for a zero norm.)
  *   - ||v|| = 0: every level 0, scale 0.
  *   - |v_i| = ||v|| (outside every half-open interval of Eq. (9)): l = s, never rounds up.
  *   - sgn: level is negated iff v_i < 0; level 0 has no sign.
@@ -115,7 +117,7 @@ float ecq_oracle_compensate(float g, float alpha, float h)
     return g + ah;
 }
 
-/* l_inf norm of one bucket. */
+/* l_inf norm of one bucket: the largest |v_i| (0 for an empty or all-zero bucket). */
 float ecq_oracle_bucket_scale(const float *v, int64_t len)
 {
     float m = 0.0f;
@@ -238,23 +240,15 @@ void ecq_oracle_bucket_step(const float *g, float *h, int64_t len, uint64_t i0, 
                             int s, float alpha, float beta, uint64_t seed, uint64_t step,
                             int update_h, int8_t *q, float *scale_out, float *gt, int norm_l2)
 {
-    float scale = 0.0f;
-    if (norm_l2) {
-        float *v = (float *)calloc((size_t)(len > 0 ? len : 1), sizeof(float));
-        for (int64_t i = 0; i < len; ++i) v[i] = ecq_oracle_compensate(g[i], alpha, h[i]);
-        scale = ecq_oracle_bucket_scale_l2(v, len);
-        free(v);
-    } else {
-        for (int64_t i = 0; i < len; ++i) {
-            float a = fabsf(ecq_oracle_compensate(g[i], alpha, h[i]));
-            if (a > scale) scale = a;
-        }
-    }
+    float *v = (float *)calloc((size_t)(len > 0 ? len : 1), sizeof(float));
+    for (int64_t i = 0; i < len; ++i) v[i] = ecq_oracle_compensate(g[i], alpha, h[i]);
+    float scale = norm_l2 ? ecq_oracle_bucket_scale_l2(v, len) : ecq_oracle_bucket_scale(v, len);
+    free(v);
     *scale_out = scale;
     for (int64_t i = 0; i < len; ++i) {
-        float v = ecq_oracle_compensate(g[i], alpha, h[i]);
+        float vi = ecq_oracle_compensate(g[i], alpha, h[i]);
         uint32_t w = ecq_oracle_word(seed, step, p, i0 + (uint64_t)i);
-        int qi = ecq_oracle_round(v, scale, s, w);
+        int qi = ecq_oracle_round(vi, scale, s, w);
         float gti = ecq_oracle_dequant(qi, scale, s);
         q[i] = (int8_t)qi;
         if (gt) gt[i] = gti;

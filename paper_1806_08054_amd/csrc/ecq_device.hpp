@@ -74,9 +74,9 @@ __device__ __forceinline__ float error_update(float beta, float h, float g, floa
 // division instead.  With SCALE24 the quotient comes out multiplied by 2^24 (an exact
 // scaling folded into the per-bucket constants).
 struct Ratio {
-    float d;        // divisor: the norm, or 1 for an all-zero bucket
+    float d;        // divisor: the norm, or 1 when the norm is 0
     float neg_d;    // -d            (* 2^-24 with SCALE24)
-    float y;        // ~ 1/d         (* 2^24 with SCALE24)
+    float y;        // ~ 1/d         (* 2^24 with SCALE24); 0 when the norm is 0
     float tiny;     // numerators in (0, tiny) use the plain division
     bool fast;      // divisor inside the safe window
 };
@@ -93,6 +93,13 @@ __device__ __forceinline__ Ratio make_ratio(float norm)
     rt.y = SCALE24 ? r * 0x1p24f : r;
     rt.neg_d = SCALE24 ? -rt.d * 0x1p-24f : -rt.d;
     rt.tiny = (rt.d > 1.0f ? rt.d : 1.0f) * 0x1p-100f;
+    // ||v|| = 0: every level is 0, whatever the elements are (with the l2 norm the squares of
+    // tiny elements can all round to 0).  A zero reciprocal makes every quotient 0 on the
+    // fast route, and the smallest denormal as `tiny` keeps every numerator on it.
+    if (!(norm > 0.0f)) {
+        rt.y = 0.0f;
+        rt.tiny = __uint_as_float(1u);
+    }
     return rt;
 }
 
@@ -136,8 +143,10 @@ __device__ __forceinline__ Quantized quantize_ternary(float v, float norm, const
 }
 
 // General s.  sxi_tab[c] = +-fl(|c - s|/s), indexed by the code c = level + s, so the sign of
-// the dequantised value comes with the table entry.  The quotient never exceeds 1, so the
-// level never exceeds s; x >= 0, so truncation is floor and x - floor(x) is exact.
+// the dequantised value comes with the table entry.  x >= 0, so truncation is floor and
+// x - floor(x) is exact.  With the l_inf norm the quotient never exceeds 1; the computed l2
+// norm can fall below |v_i| when fl(v_i^2) is denormal (a quotient up to about 1.12), so the
+// level is capped at s, the end of the grid of Eq. (8).
 __device__ __forceinline__ Quantized quantize_levels(float v, float norm, const Ratio &rt, int s, float sf,
                                                      const float *sxi_tab, uint32_t word)
 {
@@ -145,7 +154,8 @@ __device__ __forceinline__ Quantized quantize_levels(float v, float norm, const 
     const float x = a * sf;
     const float frac = __builtin_amdgcn_fractf(x);
     const float u = (float)(word >> 8) * 0x1p-24f;
-    const int m = (int)x + ((u < frac) ? 1 : 0);
+    int m = (int)x + ((u < frac) ? 1 : 0);
+    m = m < s ? m : s;
     const int smask = (int)__float_as_uint(v) >> 31;          // 0, or -1 for negative v
     const int c = s + ((m ^ smask) - smask);                   // s - m for negative v, s + m otherwise
     Quantized out;

@@ -156,12 +156,6 @@ __device__ __forceinline__ void store_codes(uint8_t *__restrict__ crow, int64_t 
     }
 }
 
-__device__ __forceinline__ void fill_xi_table(float *xi_tab, int s)
-{
-    for (int t = threadIdx.x; t <= s; t += blockDim.x) xi_tab[t] = (float)t / (float)s;
-    __syncthreads();
-}
-
 // Signed table of the rounding step, indexed by the code c = level + s: +-fl(|level|/s).
 __device__ __forceinline__ void fill_sxi_table(float *sxi_tab, int s)
 {
@@ -543,17 +537,34 @@ __global__ void __launch_bounds__(256) k_zero_scales(const Args a)
 // Decode side.
 // ---------------------------------------------------------------------------------------------
 
-// Eq. (8) from a code: scale * fl(|q|/s), negated iff q < 0.
+// Decode table of the decoding kernels for r > 2, in LDS: sxi[c] = +-fl(|c-s|/s) for the codes
+// 0..2s and 0 beyond, so that g~ = norm * sxi[c] (Eq. 8).  r = 2 needs no table.
 template <int R>
-__device__ __forceinline__ float decode_one(uint64_t bits, int e, int s, float scale,
-                                            const float *xi_tab)
+__device__ __forceinline__ void fill_agg_table(float *table, int s)
 {
-    const int c = (int)((bits >> (R * e)) & ((1u << R) - 1u));
-    const int q = c - s;
-    const int m = q < 0 ? -q : q;
-    const float xi = (R == 2) ? (float)m : xi_tab[m];
-    const float gt = scale * xi;
-    return q < 0 ? -gt : gt;
+    if constexpr (R != 2) {
+        for (int c = threadIdx.x; c < 256; c += blockDim.x) {
+            const int q = c - s;
+            const int m = q < 0 ? -q : q;
+            const float xi = (m <= s) ? (float)m / (float)s : 0.0f;
+            table[c] = q < 0 ? -xi : xi;
+        }
+        __syncthreads();
+    }
+}
+
+// Eq. (8) from a code c = level + s: scale * sxi[c], sxi[c] = +-fl(|c - s|/s).  Codes beyond 2s
+// (no message of this library holds one) decode as level 0, here as in the aggregation kernel.
+template <int R>
+__device__ __forceinline__ float decode_one(uint64_t bits, int e, float scale, const float *sxi)
+{
+    const uint32_t c = (uint32_t)(bits >> (R * e)) & ((1u << R) - 1u);
+    if constexpr (R == 2) {
+        const float level = c == 0u ? -1.0f : (c == 2u ? 1.0f : 0.0f);
+        return scale * level;
+    } else {
+        return scale * sxi[c];
+    }
 }
 
 // The 4*R code bits of the 4 elements starting at `elem` (a multiple of 4).  They start at bit
@@ -587,8 +598,8 @@ __device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ crow
 template <int R>
 __global__ void __launch_bounds__(256) k_error_update(const Args a, const int bucket_shift)
 {
-    __shared__ float xi_tab[128];
-    if constexpr (R != 2) fill_xi_table(xi_tab, a.s);
+    __shared__ float sxi[R == 2 ? 1 : 256];
+    fill_agg_table<R>(sxi, a.s);
     constexpr int J = 2;
     const int lane = threadIdx.x & 63;
     const uint32_t p = blockIdx.y;
@@ -623,45 +634,23 @@ __global__ void __launch_bounds__(256) k_error_update(const Args a, const int bu
         if (elem >= a.n) continue;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            h[j][e] = error_update(a.beta, h[j][e], g[j][e], decode_one<R>(bits[j], e, a.s, scale[j], xi_tab));
+            h[j][e] = error_update(a.beta, h[j][e], g[j][e], decode_one<R>(bits[j], e, scale[j], sxi));
         store4(hrow, elem, a.n, h[j]);
     }
 }
 
-// Decode table of the aggregation kernel for r > 2, in LDS: sxi[c] = +-fl(|c-s|/s), so that
-// g~ = norm * sxi[c] (Eq. 8).  r = 2 needs no table (see agg_add).
-template <int R>
-__device__ __forceinline__ void fill_agg_table(float *table, int s)
-{
-    if constexpr (R != 2) {
-        for (int c = threadIdx.x; c < 256; c += blockDim.x) {
-            const int q = c - s;
-            const int m = q < 0 ? -q : q;
-            const float xi = (m <= s) ? (float)m / (float)s : 0.0f;
-            table[c] = q < 0 ? -xi : xi;
-        }
-        __syncthreads();
-    }
-}
-
 // sum += one worker's dequantised values for a lane's 4 elements.
-//   r = 2: c ^ 1 is the two's complement of -level (level -1 -> 01, 0 -> 00, +1 -> 11), so a
-//          signed field extract gives -level, and sum = fma(-norm, -level, sum) equals
-//          sum + norm * level because that product is exact.
+//   r = 2: sum = fma(norm, level, sum) equals sum + norm * level because that product is exact.
 template <int R>
 __device__ __forceinline__ void agg_add(const float *table, uint32_t bits, float norm, float (&sum)[4])
 {
-    if constexpr (R == 2) {
-        const uint32_t t = bits ^ 0x55u;
-        const float nn = -norm;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int minus_level = (int)(t << (30 - 2 * e)) >> 30;
-            sum[e] = __builtin_fmaf(nn, (float)minus_level, sum[e]);
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < 4; ++e) {
+        if constexpr (R == 2) {
+            const uint32_t c = (bits >> (2 * e)) & 3u;
+            const float level = c == 0u ? -1.0f : (c == 2u ? 1.0f : 0.0f);
+            sum[e] = __builtin_fmaf(norm, level, sum[e]);
+        } else {
             const float gt = norm * table[(bits >> (R * e)) & ((1u << R) - 1u)];
             sum[e] = sum[e] + gt;
         }
@@ -1054,7 +1043,8 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x)
 }
 
 // Division self-check: thread t owns the divisor with significand t (all 2^23) and an exponent
-// drawn from `salt`; numerators never exceed the divisor, as in the kernels.
+// drawn from `salt`; numerators stay at or below the divisor, or up to an eighth above it (the
+// computed l2 norm of a bucket can fall that far below its largest element), as in the kernels.
 template <bool SCALE24>
 __global__ void __launch_bounds__(256) k_check_division(unsigned long long *mismatches, int per_divisor,
                                                        int wide_exponents, uint32_t salt)
@@ -1076,10 +1066,12 @@ __global__ void __launch_bounds__(256) k_check_division(unsigned long long *mism
             av = __uint_as_float(((uint32_t)ee << 23) | (mix32(r + 1u) & 0x7FFFFFu));
         } else if (mode == 6u) {                               // tiny, denormals included
             av = __uint_as_float(mix32(r) & 0x00FFFFFFu);
-        } else {
+        } else if (r & 8u) {
             av = d;
+        } else {                                               // up to 2^20 units in the last place above
+            av = __uint_as_float(__float_as_uint(d) + (mix32(r + 2u) & 0xFFFFFu));
         }
-        if (!(av <= d)) av = d;
+        if (mode != 7u && !(av <= d)) av = d;
         float want = av / d;
         if (SCALE24) want = want * 0x1p24f;
         bad += __float_as_uint(ratio<SCALE24>(av, rt)) != __float_as_uint(want);

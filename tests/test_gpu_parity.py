@@ -119,6 +119,7 @@ def _free_run(E, wl, iters, tuning=None, pad=0, fused=True, gens=None):
         st.g[:, : wl.N] = _dev(g_np)
         codes_ref, scales_ref = _compare_step(st, g_np, h_ref, wl.alpha, wl.beta, t, tuning, fused)
         _aggregate_check(st, codes_ref, scales_ref)
+        st.oracle_message = (codes_ref, scales_ref)         # the oracle's own, last iteration
     return st
 
 
@@ -298,6 +299,70 @@ def test_l2_degenerate(E):
         _free_run(E, wl, 3, gens=gens)
 
 
+@pytest.mark.parametrize("bucket", [16, 96, 512, 2048, 16384, 65536])
+def test_l2_squares_that_underflow(E, bucket):
+    """l_2 scaling where fl(v_i^2) is denormal or 0: buckets whose only non-zero element lies in
+    1e-23..1e-19 (the computed norm can fall below the element: level s, the end of the grid),
+    a few tiny neighbours, and buckets whose squares all round to 0 (norm 0: every level 0).
+    Every bucket route, s = 1, 4, 127."""
+    P = 3
+    N = max(4 * bucket + 40, 4096)
+    rng = np.random.default_rng(bucket)
+
+    def gens(t):
+        g = np.zeros((P, N), np.float32)
+        for k in range(0, N, bucket):
+            width = min(bucket, N - k)
+            g[0, k + int(rng.integers(width))] = np.float32(rng.choice([-1.0, 1.0]) * 10.0 ** rng.uniform(-23, -19))
+            at = k + rng.integers(width, size=4)
+            g[1, at] = (10.0 ** rng.uniform(-24, -19, 4)).astype(np.float32)
+        g[2] = (rng.standard_normal(N) * 1e-30).astype(np.float32)      # every square rounds to 0
+        g[2, : N // 2] = rng.standard_normal(N // 2).astype(np.float32) * np.float32(1e-21)
+        return g
+
+    for s in (1, 4, 127):
+        wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=2,
+                            kind="normal", norm="l2")
+        _free_run(E, wl, 2, gens=gens)
+        _free_run(E, wl, 1, gens=gens, fused=False)
+
+
+@pytest.mark.parametrize("s", [1, 2, 5, 6, 100])
+def test_codes_beyond_the_grid_decode_as_level_zero(E, s):
+    """A message that holds codes above 2s (none written by the library does): the error update
+    and the aggregation both read them as level 0, i.e. as the same message with those codes
+    replaced by s, which the oracle decodes."""
+    P, N, bucket = 3, 3 * 1024 + 72, 256
+    r = E.code_bits(s)
+    if (1 << r) == 2 * s + 1:
+        pytest.skip("every r-bit code is on the grid")
+    rng = np.random.default_rng(s)
+    st = GpuState(E, P, N, bucket, s)
+    c = rng.integers(0, 1 << r, (P, N))
+    clean = np.where(c > 2 * s, s, c)
+    g_np = rng.standard_normal((P, N)).astype(np.float32)
+    h_np = rng.standard_normal((P, N)).astype(np.float32)
+    scales = np.abs(rng.standard_normal((P, st.nb))).astype(np.float32)
+    # (codes beyond the grid are not levels the oracle's packer takes: lay the fields out as the
+    # little-endian big integer they are)
+    from tests import exact_ref as X
+    dirty_bytes = np.stack([np.frombuffer(X.pack([int(v) - s for v in row], s), np.uint8) for row in c])
+    clean_bytes = oracle.pack_rows((clean - s).astype(np.int8), s)
+    st.g[:, :N] = _dev(g_np)
+    st.h[:, :N] = _dev(h_np)
+    st.codes[:, : st.rb] = _dev(dirty_bytes)
+    st.scales[:, : st.nb] = _dev(scales)
+    E.ecq_error_update(st.sh, st.g, st.codes, st.scales, 0.9, st.h)
+    E.ecq_dequant_aggregate(st.sh, st.codes, st.scales, st.out)
+    torch.cuda.synchronize()
+    h_ref = h_np.copy()
+    for p in range(P):
+        oracle.error_update_row(g_np[p], clean_bytes[p], scales[p], bucket, s, 0.9, h_ref[p])
+    assert np.array_equal(st.h.cpu().numpy()[:, :N].view(np.uint32), h_ref.view(np.uint32))
+    ref = oracle.aggregate(clean_bytes, scales, N, bucket, s)
+    assert np.array_equal(st.out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 def test_launch_geometry_invariance(E):
     """Same bits for every mapping of buckets to lanes."""
     wl = synth.Workload("edge", P=2, N=5 * 2048 + 1000, bucket=2048, s=3, alpha=1.0, beta=0.9, iters=2,
@@ -381,9 +446,7 @@ def test_aggregate_many_workers_long_rows(E, P, s, bucket):
     wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="student_t",
                         data_seed=P + s)
     st = _free_run(E, wl, 1)
-    codes_ref = st.codes.cpu().numpy()[:, : st.rb]
-    scales_ref = st.scales.cpu().numpy()[:, : st.nb]
-    # (both were just compared bit for bit with the oracle's by _free_run)
+    codes_ref, scales_ref = st.oracle_message
     gavg = oracle.aggregate(codes_ref, scales_ref, N, bucket, s)
     w0 = np.random.default_rng(P).standard_normal(N).astype(np.float32)
     eta = float(np.float32(0.05))

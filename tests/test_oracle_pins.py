@@ -518,9 +518,10 @@ def test_l2_norm_value_and_order():
 
 
 def test_l2_norm_dominates_every_element():
-    """fl(sqrt(fl(x^2))) = |x| in binary32 and sums of non-negative terms are monotone under
-    rounding, so the computed l_2 norm is never below max|v_i|: the ratio stays <= 1 and the
-    element of a one-element bucket is reproduced exactly, as with l_inf."""
+    """fl(sqrt(fl(x^2))) = |x| in binary32 while x^2 is a normal number, and sums of
+    non-negative terms are monotone under rounding, so the computed l_2 norm is then never below
+    max|v_i|: the ratio stays <= 1 and the element of a one-element bucket is reproduced
+    exactly, as with l_inf."""
     rng = np.random.default_rng(13)
     for x in rng.uniform(1.0, 2.0, 2000).astype(np.float32):
         assert float(oracle.bucket_scale_l2(np.array([x], np.float32))) == float(x)
@@ -531,6 +532,68 @@ def test_l2_norm_dominates_every_element():
     q, sc, gt, _ = oracle.bucket_step(np.array([-1.7], np.float32), np.zeros(1, np.float32), 0, 0, 3, 1.0, 1.0,
                                       1, 0, norm="l2")
     assert int(q[0]) == -3 and float(gt[0]) == float(np.float32(-1.7))
+
+
+@pytest.mark.parametrize("s", [1, 4, 127])
+def test_l2_squares_that_underflow(s):
+    """Where fl(v_i^2) is a denormal number the computed l_2 norm can fall below |v_i| (the
+    quotient of Eq. (9) then exceeds 1 and the level is s, the end of the grid of Eq. (8)), and
+    where every square rounds to 0 the norm is 0 and every level is 0 with h' = beta*h + g
+    (Eq. (6) with g~ = 0).  Against the exact-rational model, plus the two facts themselves."""
+    rng = np.random.default_rng([21, s])
+    alpha, beta = f32(0.2), f32(0.9)
+    above = 0
+    for trial in range(40):
+        n = int(rng.integers(1, 24))
+        g = np.zeros(n, np.float32)
+        h = np.zeros(n, np.float32)
+        at = int(rng.integers(n))
+        g[at] = F32(rng.choice([-1.0, 1.0]) * 10.0 ** rng.uniform(-23.0, -19.0))
+        if trial % 3 == 0:                           # a few more tiny neighbours
+            g[rng.integers(n, size=3)] = F32(10.0 ** rng.uniform(-24.0, -20.0))
+        q, scale, gt, hn = oracle.bucket_step(g, h, 8 * trial, 2, s, alpha, beta, 5, trial, norm="l2")
+        eq, escale, egt, ehn = X.bucket_step([float(x) for x in g], [float(x) for x in h], 8 * trial, 2, s,
+                                             alpha, beta, 5, trial, norm="l2")
+        assert Fraction(float(scale)) == escale
+        assert [int(x) for x in q] == eq
+        assert [Fraction(float(x)) for x in gt] == egt
+        assert [Fraction(float(x)) for x in hn] == ehn
+        assert all(-s <= int(x) <= s for x in q)
+        big = int(np.abs(g).argmax())
+        if float(scale) == 0.0:                      # every square rounded to 0
+            assert not q.any()
+        elif float(scale) < abs(float(g[big])):      # the norm fell below its largest element
+            above += 1
+            assert abs(int(q[big])) == s
+    assert above > 0
+    # every square underflows to 0
+    g = (rng.standard_normal(16) * 1e-30).astype(np.float32)
+    h = (rng.standard_normal(16) * 1e-30).astype(np.float32)
+    q, scale, gt, hn = oracle.bucket_step(g, h, 0, 0, s, alpha, beta, 5, 0, norm="l2")
+    assert float(scale) == 0.0 and not q.any() and not gt.any()
+    want = [X.rn32(X.rn32(Fraction(float(beta)) * Fraction(float(b))) + Fraction(float(a))) for a, b in zip(g, h)]
+    assert [Fraction(float(x)) for x in hn] == want
+
+
+def test_linf_scale_is_the_largest_magnitude():
+    """The l_inf norm of a bucket (text after Eq. (8)) against numpy's norm(., inf): order-free,
+    sign-free, exact (one of the |v_i| themselves), denormals kept, 0 for an all-zero bucket."""
+    rng = np.random.default_rng(31)
+    for n in (1, 2, 7, 64, 1000):
+        for scale in (1.0, 1e-41, 1e30):
+            v = (rng.standard_normal(n) * scale).astype(np.float32)
+            got = float(oracle.bucket_scale(v))
+            assert got == float(np.linalg.norm(v.astype(np.float64), np.inf))
+            assert got == float(oracle.bucket_scale(-v[::-1].copy()))
+            assert got in set(np.abs(v).tolist())
+    assert float(oracle.bucket_scale(np.array([0.0, -0.0, 0.0], np.float32))) == 0.0
+    assert float(oracle.bucket_scale(np.array([-3.5, 2.0, 3.25], np.float32))) == 3.5
+    # the bucket step takes its scale from this function
+    g = rng.standard_normal(24).astype(np.float32)
+    h = rng.standard_normal(24).astype(np.float32)
+    _, sc, _, _ = oracle.bucket_step(g, h, 0, 0, 3, f32(0.5), f32(0.9), 1, 0)
+    v = np.array([oracle.compensate(float(a), f32(0.5), float(b)) for a, b in zip(g, h)], np.float32)
+    assert float(sc) == float(oracle.bucket_scale(v))
 
 
 def test_l2_lemma1_unbiased_and_variance_bound():
