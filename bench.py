@@ -14,6 +14,7 @@ timed on a bounded sample of the same workload on this machine's host cores.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -35,6 +36,36 @@ def algorithmic_bytes(P, N, bucket, s, E):
     return fused, dequant
 
 
+def kernel_sources_sha():
+    """Hash of the HIP sources the library is built from: every profile summary under profiles/
+    is stamped with it, and a figure taken from a summary is only reported while it matches."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1806_08054_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic(workload):
+    """(bytes per launch of the fused kernel, source) from the committed FETCH_SIZE / WRITE_SIZE
+    summary of this workload, or (None, reason) when there is none for the current sources."""
+    path = os.path.join(ROOT, "profiles", f"fused_{workload}_pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None, "no profiles/ summary for this workload"
+    stamp, value = None, None
+    for line in open(path):
+        if line.startswith("kernel_sources_sha:"):
+            stamp = line.split(":")[1].strip()
+        if line.startswith("hbm_bytes_per_launch:"):
+            value = int(line.split(":")[1])
+    rel = os.path.relpath(path, ROOT)
+    if stamp != kernel_sources_sha():
+        return None, f"{rel} was taken on other kernel sources ({stamp}); not reported"
+    return value, f"{rel} (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the copy kernel; kernel sources {stamp})"
+
+
 def cpu_baseline(wl, sample_n, g_sample, steps=3):
     """The oracle as it stands on a prefix of every worker's gradient (whole buckets), `steps`
     free-running steps: about 10-30 s of CPU work at the default sizes."""
@@ -46,7 +77,8 @@ def cpu_baseline(wl, sample_n, g_sample, steps=3):
     threads = oracle.max_threads()
     t0 = time.perf_counter()
     for t in range(steps):
-        q, scales, _ = oracle.batch_step(g, h, wl.bucket, wl.s, wl.alpha, wl.beta, 1, t, threads=threads)
+        q, scales, _ = oracle.batch_step(g, h, wl.bucket, wl.s, wl.alpha, wl.beta, 1, t, threads=threads,
+                                         norm=wl.norm)
         codes = oracle.pack_rows(q, wl.s)
         oracle.aggregate(codes, scales, sample_n, wl.bucket, wl.s)
     dt = (time.perf_counter() - t0) / steps
@@ -92,7 +124,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50", choices=["tiny", "linear", "resnet50", "alexnet", "vgg16"])
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["tiny", "linear", "resnet50", "alexnet", "vgg16", "paper_cnn", "paper_linear"],
+                    help="resnet50 is the metric workload; paper_cnn / paper_linear are the paper's own "
+                         "quantiser settings (Sections 6.2 / 6.1) on the same gradient")
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-entropy-coding", action="store_true",
@@ -112,7 +147,7 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     P, N = wl.P, wl.N
-    sh = E.Shape.aligned(N, P, wl.bucket, wl.s)      # rows start on 128-byte lines
+    sh = E.Shape.aligned(N, P, wl.bucket, wl.s, norm={"linf": 0, "l2": 1}[wl.norm])   # rows start on 128-byte lines
     pool = [synth.gradients(wl, t, device="cuda",
                             out=torch.zeros(P, sh.gh_stride, dtype=torch.float32, device="cuda"))
             for t in range(max(1, args.pool))]
@@ -178,6 +213,7 @@ def main():
 
     value = (fused_b + deq_b) / (ms_per_step * 1e-3) / 1e9
     fused_gbps = fused_b / (fused_ms * 1e-3) / 1e9
+    traffic, traffic_source = profiled_traffic(wl.name)
     result = {
         "metric": "ECQ quantize+error-update GB/s (% HBM peak), 25M-elem grad, P=8",
         "value": round(value, 1),
@@ -192,15 +228,21 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: P={P} workers x N={N} fp32, bucket {wl.bucket}, s={wl.s} "
-                               f"({E.code_bits(wl.s)}-bit codes), alpha={wl.alpha}, beta={wl.beta}; "
+                               f"({E.code_bits(wl.s)}-bit codes), {wl.norm} norm, alpha={wl.alpha}, beta={wl.beta}; "
                                "step = fused quantise+error-update over all workers, then dequantise+average",
-                   "workers": P, "n": N, "bucket": wl.bucket, "s": wl.s},
+                   "workers": P, "n": N, "bucket": wl.bucket, "s": wl.s, "norm": wl.norm},
+        # `value` is the whole step; the kernel the metric's name refers to is reported beside it.
+        "value_is": "whole step: algorithmic bytes of fused quantise+error-update plus dequantise+average / step time",
+        "whole_step_GBps": round(value, 1),
+        "fused_quantize_update_GBps": round(fused_gbps, 1),
+        "fused_quantize_update_pct_hbm_peak": round(100 * fused_gbps / HBM_PEAK_GBPS, 2),
         "step_bytes": fused_b + deq_b,
         "gelem_per_s": round(P * N / (ms_per_step * 1e-3) / 1e9, 2),
         "fused": {"ms": round(fused_ms, 4), "GBps": round(fused_gbps, 1),
                   "pct_hbm_peak": round(100 * fused_gbps / HBM_PEAK_GBPS, 2),
                   "gelem_per_s": round(P * N / (fused_ms * 1e-3) / 1e9, 2), "bytes": fused_b},
         "dequant_aggregate": {"ms": round(deq_ms, 4), "GBps": round(deq_b / (deq_ms * 1e-3) / 1e9, 1),
+                              "pct_hbm_peak": round(100 * deq_b / (deq_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
                               "bytes": deq_b},
         "calibration": {"add_2r1w_GBps": round(12 * n_cal / (add_ms * 1e-3) / 1e9, 1),
                         "copy_1r1w_GBps": round(8 * n_cal / (copy_ms * 1e-3) / 1e9, 1),
@@ -209,15 +251,12 @@ def main():
                         "aggregate_pattern_ms": round(gather_ms, 4)},
         "roofline": {"bound": "hbm", "kernel": "ecq_quantize_update (fused single pass)",
                      "achieved": round(fused_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(fused_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "frac": round(fused_gbps / HBM_PEAK_GBPS, 4),
+                     # HBM bytes per launch from a separate rocprofv3 counter run on the same kernel
+                     # sources (not measured in this run); null when no such summary is committed.
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes": fused_b},
     }
-    # HBM bytes per launch of the fused kernel as measured with rocprofv3 FETCH_SIZE / WRITE_SIZE
-    # (scaled by the copy kernel); the committed summary holds the figure and how it was made.
-    traffic_file = os.path.join(ROOT, "profiles", "fused_team_resnet50_pmc_traffic.txt")
-    if os.path.exists(traffic_file) and args.workload == "resnet50":
-        for line in open(traffic_file):
-            if line.startswith("hbm_bytes_per_launch:"):
-                result["roofline"]["traffic"] = int(line.split(":")[1])
     if not args.no_entropy_coding:
         result["entropy_coding"] = entropy_coding(E, torch, sh, wl, codes, timed)
     if not args.no_cpu_baseline:

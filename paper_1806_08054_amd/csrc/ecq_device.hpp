@@ -299,19 +299,29 @@ template <int R>
 struct Codes16 {
     static constexpr int kWords = (R + 1) / 2;
     uint32_t w[kWords];
+    // NT: non-temporal loads, for codes that are read once and should not take room in (or evict
+    // dirty lines from) the last-level cache.
+    template <bool NT = false>
     __device__ __forceinline__ void load(const uint8_t *__restrict__ src)
     {
         if constexpr ((R & 1) == 0) {
 #pragma unroll
-            for (int i = 0; i < R / 2; ++i) w[i] = reinterpret_cast<const uint32_t *>(src)[i];
+            for (int i = 0; i < R / 2; ++i) {
+                const uint32_t *at = reinterpret_cast<const uint32_t *>(src) + i;
+                w[i] = NT ? __builtin_nontemporal_load(at) : *at;
+            }
         } else {
             // 2*R bytes at a 2-byte aligned address: whole dwords (global loads need no natural
             // alignment here), then one short.
+            typedef uint32_t u32_unaligned __attribute__((aligned(2)));
+            typedef uint16_t u16_aligned __attribute__((aligned(2)));
 #pragma unroll
-            for (int i = 0; i < kWords - 1; ++i) __builtin_memcpy(&w[i], src + 4 * i, 4);
-            uint16_t last;
-            __builtin_memcpy(&last, src + 4 * (kWords - 1), 2);
-            w[kWords - 1] = last;
+            for (int i = 0; i < kWords - 1; ++i) {
+                const u32_unaligned *at = reinterpret_cast<const u32_unaligned *>(src + 4 * i);
+                w[i] = NT ? __builtin_nontemporal_load(at) : *at;
+            }
+            const u16_aligned *last = reinterpret_cast<const u16_aligned *>(src + 4 * (kWords - 1));
+            w[kWords - 1] = NT ? __builtin_nontemporal_load(last) : *last;
         }
     }
     // The same for a lane at the ragged end of a row: bytes at or beyond row_bytes read as 0.

@@ -710,9 +710,34 @@ __device__ __forceinline__ void fill_pair_table(f2 *pair, int)
     __syncthreads();
 }
 
+// Byte table of the r = 4 fast path: one code byte (two codes) -> their signed grid points
+// +-fl(|c - s|/s) as a float2, shared by all lanes: half the address arithmetic of one lookup
+// per code.  The entry of byte t sits in slot t ^ (t >> 4): the bytes that occur together in a
+// message mostly differ from the most frequent one (both levels 0) in one nibble, and this
+// spreads them over different banks whichever nibble it is (lanes that read the same entry
+// are served together).
+__device__ __forceinline__ void fill_byte_table(f2 *tab, int s)
+{
+    for (int t = threadIdx.x; t < 256; t += blockDim.x) {
+        float xi[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int c = (t >> (4 * k)) & 15, q = c - s, m = q < 0 ? -q : q;
+            const float v = (m <= s) ? (float)m / (float)s : 0.0f;
+            xi[k] = q < 0 ? -v : v;
+        }
+        f2 e;
+        e.x = xi[0];
+        e.y = xi[1];
+        tab[t ^ (t >> 4)] = e;
+    }
+    __syncthreads();
+}
+
 // acc += one worker's dequantised values for a lane's 16 elements (Eq. 8).
 //   r = 2: levels from the pair table; acc = fma(norm, level, acc) equals acc + norm * level
 //          because that product is exact.
+//   r = 4: two grid points per lookup from the byte table, g~ = norm * sxi[c], then acc + g~.
 //   else : g~ = norm * sxi[c], then acc + g~, as in agg_add.
 template <int R>
 __device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint32_t lane_off, const Codes16<R> &cd,
@@ -733,6 +758,21 @@ __device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint
             acc[2 * j] = __builtin_fmaf(norm, lv.x, acc[2 * j]);
             acc[2 * j + 1] = __builtin_fmaf(norm, lv.y, acc[2 * j + 1]);
         }
+    } else if constexpr (R == 4) {
+        // `pair` is the byte table here: g~ = norm * sxi[c] for the byte's two codes, then acc + g~.
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float norm = i == 0 ? norm_lo : norm_hi;
+            const uint32_t x = cd.w[i], y = x ^ ((x >> 4) & 0x0F0F0F0Fu);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t off = ((y >> (8 * k)) & 0xFFu) << 3;
+                const f2 xi = *reinterpret_cast<const f2 *>(reinterpret_cast<const char *>(pair) + off);
+                const float g0 = norm * xi.x, g1 = norm * xi.y;
+                acc[8 * i + 2 * k] = acc[8 * i + 2 * k] + g0;
+                acc[8 * i + 2 * k + 1] = acc[8 * i + 2 * k + 1] + g1;
+            }
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -750,8 +790,12 @@ constexpr int kAggStageStride = 20;    // floats between lanes in the transposit
 // lane one aligned load of 2*R code bytes (a wave reads 128*R contiguous bytes per worker) and
 // its norms: NORMS = 0 when the bucket is a multiple of 1024 (one norm per wave, a scalar
 // load), 1 when it is a multiple of 16 (one per lane), 2 otherwise (buckets are multiples of 8,
-// so the lane's two halves of 8 outputs may lie in two buckets: one norm each).  Four workers'
-// codes and norms are in flight together.  The 16 sums of a lane are then transposed through
+// so the lane's two halves of 8 outputs may lie in two buckets: one norm each).  Eight workers'
+// codes and norms are requested together (r = 2: the next eight while the current ones are
+// added).  Codes are read once, with non-temporal loads: a regular load would take a line of the
+// last-level cache and push out a dirty line the pass before left there (its code stores), and
+// the write-back of up to 256 MB of such lines is charged to this kernel (+14-20 % measured
+// at 16 and 32 workers).  The 16 sums of a lane are then transposed through
 // LDS so the wave stores (and, for the model update, loads) whole contiguous kilobytes as
 // float4 per lane.  The ragged last run of a row goes through agg_run_guarded.
 // bucket_shift >= 0 when the bucket is a power of two.
@@ -760,8 +804,9 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
 {
     // One LDS object with the pair table first: its byte offsets are then LDS addresses, and a
     // lookup address is a single AND-OR of the shifted codes with the lane's copy offset.
+    // (r = 4: `pair` holds the byte table, 256 entries.)
     struct Lds {
-        f2 pair[R == 2 ? 16 * 32 : 1];
+        f2 pair[R == 2 ? 16 * 32 : (R == 4 ? 256 : 1)];
         float table[R == 2 ? 1 : 256];
         __attribute__((aligned(16))) float stage[4][64 * kAggStageStride];
     };
@@ -770,8 +815,9 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     const f2 *pair = lds.pair;
     fill_agg_table<R>(lds.table, a.s);
     if constexpr (R == 2) fill_pair_table(lds.pair, 0);
+    if constexpr (R == 4) fill_byte_table(lds.pair, a.s);
 
-    constexpr int U = 4;                                       // workers per batch
+    constexpr int U = 8;                                       // r = 2: workers per batch
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
     base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
@@ -810,7 +856,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         auto request = [&](Codes16<R> (&c)[U], float (&nl)[U], float (&nh)[U]) {
     #pragma unroll
             for (int u = 0; u < U; ++u) {
-                c[u].load(cptr + u * a.code_stride);
+                c[u].template load<true>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, nl[u], nh[u]);
             }
             cptr += U * a.code_stride;
@@ -832,22 +878,23 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (int p = batches * U; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            one.load(cptr);
+            one.template load<true>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
             srow += a.scale_stride;
         }
     } else {
-        // r > 2: the table lookups want the compiler's unrolled schedule; two workers per step.
-        constexpr int V = 2;
+        // r > 2: the table lookups want the compiler's unrolled schedule: V workers per step (a
+        // software pipeline like the one above measured 15-20 % slower at r = 4).
+        constexpr int V = R == 4 ? 8 : 2;
         int p = 0;
         for (; p + V <= a.workers; p += V) {
             Codes16<R> cd[V];
             float lo[V], hi[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
-                cd[u].load(cptr + u * a.code_stride);
+                cd[u].template load<true>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, lo[u], hi[u]);
             }
 #pragma unroll
@@ -859,7 +906,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            one.load(cptr);
+            one.template load<true>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
@@ -1235,13 +1282,13 @@ hipError_t launch_error_update(const Args &a, hipStream_t stream)
 
 hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
 {
-    const dim3 grid(cdiv(cdiv(a.n, kAggRun), 4));
     int bucket_shift = -1;
     if ((a.bucket & (a.bucket - 1)) == 0)
         for (bucket_shift = 0; (1 << bucket_shift) < a.bucket; ++bucket_shift) {}
     const int norms = (a.bucket % kAggRun) == 0 ? 0 : ((a.bucket % 16) == 0 ? 1 : 2);
     // Dividing by a power of two and multiplying by its reciprocal round identically.
     const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
+    const dim3 grid(cdiv(cdiv(a.n, kAggRun), 4));
 #define CALL(RR)                                                                                              \
     if (norms == 0)                                                                                           \
         hipLaunchKernelGGL((k_dequant_aggregate<RR, 0>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p); \
@@ -1296,29 +1343,31 @@ hipError_t launch_calib_add(const float *x, const float *y, float *out, int64_t 
     return hipGetLastError();
 }
 
-// The aggregation kernel's loads and stores without its arithmetic: four workers' code words
-// per lane in flight, their sum written as the lane's 16 outputs in the same float4 pattern.
+// The aggregation kernel's loads and stores without its arithmetic: eight workers' code words per
+// lane in flight (non-temporal loads), their sum written as the lane's 16 outputs in the same
+// float4 pattern.
 template <int R>
 __global__ void __launch_bounds__(256) k_calib_gather(const Args a)
 {
+    constexpr int U = 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
     if (base + kAggRun > a.n) return;
     const uint8_t *__restrict__ cptr = a.codes + ((base * R) >> 3) + lane * (2 * R);
     uint32_t sum = 0;
     int p = 0;
-    for (; p + 4 <= a.workers; p += 4) {
-        Codes16<R> cd[4];
+    for (; p + U <= a.workers; p += U) {
+        Codes16<R> cd[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) cd[u].load(cptr + (int64_t)(p + u) * a.code_stride);
+        for (int u = 0; u < U; ++u) cd[u].template load<true>(cptr + (int64_t)(p + u) * a.code_stride);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < Codes16<R>::kWords; ++i) sum += cd[u].w[i];
     }
     for (; p < a.workers; ++p) {
         Codes16<R> one;
-        one.load(cptr + (int64_t)p * a.code_stride);
+        one.template load<true>(cptr + (int64_t)p * a.code_stride);
 #pragma unroll
         for (int i = 0; i < Codes16<R>::kWords; ++i) sum += one.w[i];
     }

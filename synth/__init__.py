@@ -51,6 +51,21 @@ WORKLOADS = {
                       iters=5, kind="outliers"),
 }
 
+# The quantiser settings the paper itself reports, on the metric workload's gradient (same
+# P, N and value distribution as "resnet50"):
+#   paper_cnn     Section 6.2 (CNN experiments): bucket 4096, l_2 scaling, s = 4, alpha = 0.01,
+#                 beta = 1.0;
+#   paper_linear  Section 6.1 (linear models): l_2 scaling, s = 4, alpha = 0.2, beta = 0.9; the
+#                 paper scales the whole d-vector there (d <= 1024 features), which a bucket of
+#                 1024 elements reproduces on a long flat gradient.
+PAPER_SETTINGS = {
+    "paper_cnn": Workload("paper_cnn", P=8, N=25_557_032, bucket=4096, s=4, alpha=0.01, beta=1.0,
+                          iters=3, kind="layered", norm="l2"),
+    "paper_linear": Workload("paper_linear", P=8, N=25_557_032, bucket=1024, s=4, alpha=0.2, beta=0.9,
+                             iters=3, kind="layered", norm="l2"),
+}
+WORKLOADS.update(PAPER_SETTINGS)
+
 
 def _gen(device, *seed_parts: int) -> torch.Generator:
     g = torch.Generator(device=device)

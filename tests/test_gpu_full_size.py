@@ -165,6 +165,15 @@ def test_resnet50_one_norm_per_row(E, norm):
     _run(E, wl)
 
 
+@pytest.mark.parametrize("name", ["paper_cnn", "paper_linear"])
+def test_paper_settings_full(E, name):
+    """The paper's own quantiser settings on the metric workload's gradient (P = 8,
+    N = 25,557,032): Section 6.2's (bucket 4096, l_2 scaling, s = 4, alpha = 0.01, beta = 1.0) and
+    Section 6.1's (l_2, s = 4, alpha = 0.2, beta = 0.9, 1024-element vectors): 3 free-running
+    iterations, every element."""
+    _run(E, synth.WORKLOADS[name])
+
+
 def test_alexnet_full(E):
     """Workload 4: 10 free-running iterations, all 16 workers and the average in full at every
     iteration."""
