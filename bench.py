@@ -37,14 +37,14 @@ def algorithmic_bytes(P, N, bucket, s, E):
 
 
 def kernel_sources_sha():
-    """Hash of the HIP sources the library is built from: every profile summary under profiles/
-    is stamped with it, and a figure taken from a summary is only reported while it matches."""
+    """Hash of the sources of the fused and aggregation kernels: the counter summaries under
+    profiles/ are stamped with it, and a figure taken from one is only reported while it
+    matches."""
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_1806_08054_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".hpp")):
-            h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    for name in ("ecq_device.hpp", "ecq_kernels.hip"):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
 
 

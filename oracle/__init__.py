@@ -48,6 +48,7 @@ _f32p = np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")
 _i8p = np.ctypeslib.ndpointer(np.int8, flags="C_CONTIGUOUS")
 _u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
 _u32p = np.ctypeslib.ndpointer(np.uint32, flags="C_CONTIGUOUS")
+_u64p = np.ctypeslib.ndpointer(np.uint64, flags="C_CONTIGUOUS")
 
 
 def _declare(L):
@@ -99,7 +100,6 @@ def _declare(L):
     L.ecq_oracle_aggregate.restype = None
     L.ecq_oracle_sgd_step.argtypes = [_f32p, _f32p, C.c_float, C.c_int64]
     L.ecq_oracle_sgd_step.restype = None
-    _u64p = np.ctypeslib.ndpointer(np.uint64, flags="C_CONTIGUOUS")
     L.ecq_oracle_level_histogram.argtypes = [_i8p, C.c_int64, C.c_int, _u64p]
     L.ecq_oracle_level_histogram.restype = None
     L.ecq_oracle_entropy_bound_bits.argtypes = [_u64p, C.c_int]
@@ -112,6 +112,21 @@ def _declare(L):
     L.ecq_oracle_huffman_encode.restype = C.c_int64
     L.ecq_oracle_huffman_decode.argtypes = [_u8p, C.c_uint64, C.c_int64, C.c_int, _u8p, _u64p, _i8p]
     L.ecq_oracle_huffman_decode.restype = None
+    L.ecq_oracle_zrun_max_run.argtypes = [C.c_int]
+    L.ecq_oracle_zrun_max_run.restype = C.c_int
+    L.ecq_oracle_zrun_symbols.argtypes = [C.c_int]
+    L.ecq_oracle_zrun_symbols.restype = C.c_int
+    L.ecq_oracle_zrun_tokens.argtypes = [_i8p, C.c_int64, C.c_int, _u8p]
+    L.ecq_oracle_zrun_tokens.restype = C.c_int64
+    L.ecq_oracle_zrun_histogram.argtypes = [_i8p, C.c_int64, C.c_int, C.c_int64, _u64p]
+    L.ecq_oracle_zrun_histogram.restype = None
+    L.ecq_oracle_zrun_max_bytes.argtypes = [C.c_int64, C.c_int, C.c_int64]
+    L.ecq_oracle_zrun_max_bytes.restype = C.c_int64
+    L.ecq_oracle_zrun_encode.argtypes = [_i8p, C.c_int64, C.c_int, _u8p, _u64p, _u8p, C.c_int64, C.c_int64,
+                                         C.c_int64, _u32p, _u64p]
+    L.ecq_oracle_zrun_encode.restype = C.c_int64
+    L.ecq_oracle_zrun_decode.argtypes = [_u8p, C.c_uint64, C.c_int64, C.c_int, _u8p, _u64p, _i8p]
+    L.ecq_oracle_zrun_decode.restype = None
 
 
 # ------------------------------------------------------------------ scalar steps ------------
@@ -322,6 +337,65 @@ def huffman_decode(stream: np.ndarray, start: int, n: int, s: int, lengths: np.n
     lib().ecq_oracle_huffman_decode(np.ascontiguousarray(stream, np.uint8), start, n, s,
                                     np.ascontiguousarray(lengths, np.uint8),
                                     np.ascontiguousarray(codes, np.uint64), q)
+    return q
+
+
+ZRUN_TILE = 4096        # elements per independently decodable tile of the zero-run code
+ZRUN_GROUP = 64         # tiles per group (one 64-bit stream offset per group)
+
+
+def zrun_max_run(s: int) -> int:
+    """Z = floor(127/s): the longest zero run one token completes."""
+    return int(lib().ecq_oracle_zrun_max_run(s))
+
+
+def zrun_symbols(s: int) -> int:
+    """Size of the token alphabet, 2sZ + 1."""
+    return int(lib().ecq_oracle_zrun_symbols(s))
+
+
+def zrun_tokens(q: np.ndarray, s: int) -> np.ndarray:
+    """Tokens of ONE tile of levels (Section 4, cost paragraph; zero runs joined with the level
+    that ends them)."""
+    q = np.ascontiguousarray(q, np.int8).reshape(-1)
+    out = np.zeros(q.size + 1, np.uint8)
+    count = lib().ecq_oracle_zrun_tokens(q, q.size, s, out)
+    return out[:count].copy()
+
+
+def zrun_histogram(q: np.ndarray, s: int, tile: int = ZRUN_TILE) -> np.ndarray:
+    """Token counts of one worker row."""
+    q = np.ascontiguousarray(q, np.int8).reshape(-1)
+    counts = np.zeros(zrun_symbols(s), np.uint64)
+    lib().ecq_oracle_zrun_histogram(q, q.size, s, tile, counts)
+    return counts
+
+
+def zrun_max_bytes(n: int, s: int, tile: int = ZRUN_TILE) -> int:
+    return int(lib().ecq_oracle_zrun_max_bytes(n, s, tile))
+
+
+def zrun_encode(q: np.ndarray, s: int, lengths: np.ndarray, codes: np.ndarray, tile: int = ZRUN_TILE,
+                group: int = ZRUN_GROUP):
+    """One worker row -> (stream bytes, bits of every tile, group bit offsets incl. the total,
+    total bits)."""
+    q = np.ascontiguousarray(q, np.int8).reshape(-1)
+    tiles = (q.size + tile - 1) // tile
+    out = np.zeros(max(zrun_max_bytes(q.size, s, tile), 4), np.uint8)
+    tile_bits = np.zeros(max(tiles, 1), np.uint32)
+    group_offsets = np.zeros((tiles + group - 1) // group + 1, np.uint64)
+    bits = lib().ecq_oracle_zrun_encode(q, q.size, s, np.ascontiguousarray(lengths, np.uint8),
+                                        np.ascontiguousarray(codes, np.uint64), out, out.size, tile, group,
+                                        tile_bits, group_offsets)
+    return out, tile_bits[:tiles], group_offsets, int(bits)
+
+
+def zrun_decode(stream: np.ndarray, start: int, n: int, s: int, lengths: np.ndarray, codes: np.ndarray):
+    """One tile of n levels from the stream bit `start`."""
+    q = np.full(n, -128, np.int8)
+    lib().ecq_oracle_zrun_decode(np.ascontiguousarray(stream, np.uint8), start, n, s,
+                                 np.ascontiguousarray(lengths, np.uint8),
+                                 np.ascontiguousarray(codes, np.uint64), q)
     return q
 
 

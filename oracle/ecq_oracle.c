@@ -475,3 +475,141 @@ void ecq_oracle_huffman_decode(const uint8_t *stream, uint64_t start, int64_t n,
         q[i] = (int8_t)(found - s);
     }
 }
+
+/* ---------------------------------------------------------------- zero-run Huffman coding - */
+/* Section 4's cost paragraph bounds the entropy-coded length of a message by
+ * sum_k d_k log2(d/d_k) bits.  A Huffman code over single levels never spends less than one bit
+ * per element, and quantised gradients are mostly zeros (the bound is often far below one bit),
+ * so the Huffman code is taken over TOKENS instead: a run of zero levels together with the
+ * non-zero level that ends it (the classic run-length source extension; Huffman, 1952, over
+ * the extended alphabet).
+ *
+ * Conventions of this repository (the paper fixes none of them):
+ *  - Z = floor(127 / s) is the longest run a token completes.  Tokens are numbered
+ *      z * 2s + j   for a run of z zeros (0 <= z < Z) ended by the non-zero level with rank j,
+ *                   j = 0..2s-1 in increasing level order (-s..-1, then 1..s);
+ *      2s * Z       for Z zeros and no level after them,
+ *    2sZ + 1 <= 255 symbols in all.
+ *  - A row is cut into tiles of `tile` elements that are tokenised on their own: levels are
+ *    taken in order, a zero extends the run, the Z-th zero of a run sends the token "Z zeros"
+ *    and restarts the run, a non-zero level sends (run, level) and restarts the run.  A run
+ *    still open at the end of the tile is sent as one "Z zeros" token; the decoder knows the
+ *    tile's length and drops the zeros beyond it.
+ *  - One Huffman code per worker row from the row's token counts, built and made canonical
+ *    exactly as the per-level code above; the bit stream has the same layout (LSB-first,
+ *    codewords most significant bit first, tiles back to back without padding).
+ *  - Kept beside the stream: the number of bits of every tile (32 bits each) and, for every
+ *    group of `group` tiles, the stream bit at which the group starts (64 bits each), the
+ *    last entry being the row's total.  Tiles then decode independently.
+ */
+
+int ecq_oracle_zrun_max_run(int s) { return (s >= 1 && s <= 127) ? 127 / s : -1; }
+
+int ecq_oracle_zrun_symbols(int s)
+{
+    int z = ecq_oracle_zrun_max_run(s);
+    return z < 0 ? -1 : 2 * s * z + 1;
+}
+
+/* Tokens of one tile of len levels; `tokens` must hold len + 1 entries.  Returns their number. */
+int64_t ecq_oracle_zrun_tokens(const int8_t *q, int64_t len, int s, uint8_t *tokens)
+{
+    int Z = ecq_oracle_zrun_max_run(s);
+    int64_t count = 0;
+    int run = 0;
+    for (int64_t i = 0; i < len; ++i) {
+        if (q[i] == 0) {
+            if (++run == Z) {
+                tokens[count++] = (uint8_t)(2 * s * Z);
+                run = 0;
+            }
+        } else {
+            int rank = q[i] < 0 ? (int)q[i] + s : (int)q[i] + s - 1;
+            tokens[count++] = (uint8_t)(run * 2 * s + rank);
+            run = 0;
+        }
+    }
+    if (run > 0) tokens[count++] = (uint8_t)(2 * s * Z);
+    return count;
+}
+
+/* Token counts of one worker row (all its tiles). */
+void ecq_oracle_zrun_histogram(const int8_t *q, int64_t n, int s, int64_t tile, uint64_t *counts)
+{
+    int A = ecq_oracle_zrun_symbols(s);
+    uint8_t *tokens = (uint8_t *)malloc((size_t)tile + 1);
+    for (int a = 0; a < A; ++a) counts[a] = 0;
+    for (int64_t e0 = 0; e0 < n; e0 += tile) {
+        int64_t len = n - e0 < tile ? n - e0 : tile;
+        int64_t count = ecq_oracle_zrun_tokens(q + e0, len, s, tokens);
+        for (int64_t k = 0; k < count; ++k) counts[tokens[k]] += 1;
+    }
+    free(tokens);
+}
+
+/* A stream row never needs more than this many bytes when the code was built from the row's
+ * own token counts: the lengths r*(z+1) for (z, level) and r*Z for "Z zeros" satisfy Kraft's
+ * inequality and cost r bits per element covered, and only the one closing token a tile may
+ * have covers fewer elements than it is charged for. */
+int64_t ecq_oracle_zrun_max_bytes(int64_t n, int s, int64_t tile)
+{
+    int64_t r = ecq_oracle_code_bits(s), Z = ecq_oracle_zrun_max_run(s);
+    int64_t tiles = (n + tile - 1) / tile;
+    return ((n * r + tiles * r * Z + 7) / 8 + 3) / 4 * 4;
+}
+
+/* Encodes one worker row; returns the total number of bits.  out is zeroed up to out_bytes
+ * first and must hold the stream; tile_bits gets ceil(n/tile) entries, group_offsets
+ * ceil(tiles/group) + 1. */
+int64_t ecq_oracle_zrun_encode(const int8_t *q, int64_t n, int s, const uint8_t *lengths,
+                               const uint64_t *codes, uint8_t *out, int64_t out_bytes, int64_t tile,
+                               int64_t group, uint32_t *tile_bits, uint64_t *group_offsets)
+{
+    uint8_t *tokens = (uint8_t *)malloc((size_t)tile + 1);
+    memset(out, 0, (size_t)out_bytes);
+    int64_t pos = 0, t = 0;
+    for (int64_t e0 = 0; e0 < n; e0 += tile, ++t) {
+        int64_t len = n - e0 < tile ? n - e0 : tile;
+        if (t % group == 0) group_offsets[t / group] = (uint64_t)pos;
+        int64_t begin = pos;
+        int64_t count = ecq_oracle_zrun_tokens(q + e0, len, s, tokens);
+        for (int64_t k = 0; k < count; ++k) {
+            int a = tokens[k];
+            for (int b = lengths[a] - 1; b >= 0; --b) {        /* most significant bit first */
+                if ((codes[a] >> b) & 1u) out[pos >> 3] |= (uint8_t)(1u << (pos & 7));
+                ++pos;
+            }
+        }
+        tile_bits[t] = (uint32_t)(pos - begin);
+    }
+    group_offsets[(t + group - 1) / group] = (uint64_t)pos;
+    free(tokens);
+    return pos;
+}
+
+/* Decodes one tile of len levels whose tokens start at stream bit `start`. */
+void ecq_oracle_zrun_decode(const uint8_t *stream, uint64_t start, int64_t len, int s,
+                            const uint8_t *lengths, const uint64_t *codes, int8_t *q)
+{
+    int Z = ecq_oracle_zrun_max_run(s), A = ecq_oracle_zrun_symbols(s);
+    uint64_t pos = start;
+    int64_t i = 0;
+    while (i < len) {
+        uint64_t word = 0;
+        int bits = 0, found = -1;
+        while (found < 0 && bits < 64) {
+            word = (word << 1) | (uint64_t)((stream[pos >> 3] >> (pos & 7)) & 1u);
+            ++pos;
+            ++bits;
+            for (int a = 0; a < A; ++a)
+                if (lengths[a] == bits && codes[a] == word) found = a;
+        }
+        if (found < 0) break;                                   /* not a stream of this code */
+        int zeros = found == 2 * s * Z ? Z : found / (2 * s);
+        for (int k = 0; k < zeros && i < len; ++k) q[i++] = 0;
+        if (found != 2 * s * Z && i < len) {
+            int rank = found % (2 * s);
+            q[i++] = (int8_t)(rank < s ? rank - s : rank - s + 1);
+        }
+    }
+}

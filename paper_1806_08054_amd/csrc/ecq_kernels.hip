@@ -790,17 +790,18 @@ constexpr int kAggStageStride = 20;    // floats between lanes in the transposit
 // lane one aligned load of 2*R code bytes (a wave reads 128*R contiguous bytes per worker) and
 // its norms: NORMS = 0 when the bucket is a multiple of 1024 (one norm per wave, a scalar
 // load), 1 when it is a multiple of 16 (one per lane), 2 otherwise (buckets are multiples of 8,
-// so the lane's two halves of 8 outputs may lie in two buckets: one norm each).  Eight workers'
-// codes and norms are requested together (r = 2: the next eight while the current ones are
-// added).  Codes are read once, with non-temporal loads: a regular load would take a line of the
+// so the lane's two halves of 8 outputs may lie in two buckets: one norm each).  r = 2: U
+// workers' codes and norms are requested together, the next U while the current ones are added
+// (U = 8 from 16 workers on, else 4: -3 % at 32 workers, +7 % at 8); r = 4: eight at a time.  Codes are read once, with non-temporal loads: a regular load would take a line of the
 // last-level cache and push out a dirty line the pass before left there (its code stores), and
 // the write-back of up to 256 MB of such lines is charged to this kernel (+14-20 % measured
 // at 16 and 32 workers).  The 16 sums of a lane are then transposed through
 // LDS so the wave stores (and, for the model update, loads) whole contiguous kilobytes as
 // float4 per lane.  The ragged last run of a row goes through agg_run_guarded.
 // bucket_shift >= 0 when the bucket is a power of two.
-template <int R, int NORMS>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift, const float inv_p)
+template <int R, int NORMS, int U>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift, const float inv_p,
+                                                           const int stream_codes)
 {
     // One LDS object with the pair table first: its byte offsets are then LDS addresses, and a
     // lookup address is a single AND-OR of the shifted codes with the lane's copy offset.
@@ -817,7 +818,6 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
     if constexpr (R == 2) fill_pair_table(lds.pair, 0);
     if constexpr (R == 4) fill_byte_table(lds.pair, a.s);
 
-    constexpr int U = 8;                                       // r = 2: workers per batch
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t base = ((int64_t)blockIdx.x * 4 + wave) * kAggRun;
     base = ((int64_t)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
@@ -856,7 +856,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         auto request = [&](Codes16<R> (&c)[U], float (&nl)[U], float (&nh)[U]) {
     #pragma unroll
             for (int u = 0; u < U; ++u) {
-                c[u].template load<true>(cptr + u * a.code_stride);
+                if (stream_codes) c[u].template load<true>(cptr + u * a.code_stride); else c[u].template load<false>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, nl[u], nh[u]);
             }
             cptr += U * a.code_stride;
@@ -878,7 +878,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (int p = batches * U; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            one.template load<true>(cptr);
+            if (stream_codes) one.template load<true>(cptr); else one.template load<false>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
@@ -894,7 +894,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
             float lo[V], hi[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
-                cd[u].template load<true>(cptr + u * a.code_stride);
+                if (stream_codes) cd[u].template load<true>(cptr + u * a.code_stride); else cd[u].template load<false>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, lo[u], hi[u]);
             }
 #pragma unroll
@@ -906,7 +906,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            one.template load<true>(cptr);
+            if (stream_codes) one.template load<true>(cptr); else one.template load<false>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
@@ -1289,15 +1289,27 @@ hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
     // Dividing by a power of two and multiplying by its reciprocal round identically.
     const float inv_p = (a.workers & (a.workers - 1)) == 0 ? 1.0f / (float)a.workers : 0.0f;
     const dim3 grid(cdiv(cdiv(a.n, kAggRun), 4));
-#define CALL(RR)                                                                                              \
-    if (norms == 0)                                                                                           \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, 0>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p); \
-    else if (norms == 1)                                                                                      \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, 1>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p); \
-    else                                                                                                      \
-        hipLaunchKernelGGL((k_dequant_aggregate<RR, 2>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p)
+    const bool wide = a.r == 2 && a.workers >= 16;             // r = 2: workers per batch (other widths ignore it)
+    // Messages of up to 96 MB in all are most likely still in the 256 MB last-level cache, where
+    // the encoding pass left them; larger ones are streamed past it.
+    const int stream_codes = (int64_t)a.workers * a.row_bytes > ((int64_t)96 << 20);
+#define LAUNCH(RR, NN, UU) \
+    hipLaunchKernelGGL((k_dequant_aggregate<RR, NN, UU>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p, \
+                       stream_codes)
+#define CALL(RR)                                      \
+    if (norms == 0) {                                 \
+        if (RR == 2 && wide) LAUNCH(RR, 0, (RR == 2 ? 8 : 4)); \
+        else LAUNCH(RR, 0, 4);                        \
+    } else if (norms == 1) {                          \
+        if (RR == 2 && wide) LAUNCH(RR, 1, (RR == 2 ? 8 : 4)); \
+        else LAUNCH(RR, 1, 4);                        \
+    } else {                                          \
+        if (RR == 2 && wide) LAUNCH(RR, 2, (RR == 2 ? 8 : 4)); \
+        else LAUNCH(RR, 2, 4);                        \
+    }
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
+#undef LAUNCH
     return hipGetLastError();
 }
 

@@ -812,3 +812,160 @@ def test_huffman_stream_round_trip_and_tiles(s):
         cnt = min(T, n - t * T)
         assert np.array_equal(oracle.huffman_decode(stream, int(offs[t]), cnt, s, lengths, codes), q[t * T:t * T + cnt])
     assert bits < n * oracle.code_bits(s)
+
+
+# ------------------------------------------------------------------ zero-run Huffman coding --
+
+def _zrun_tokens_by_runs(levels, s):
+    """Second implementation of the tokeniser, from the runs of the tile instead of a scan:
+    every maximal run of zeros gives floor(run / Z) "Z zeros" tokens, the rest joins the level
+    that follows it; a rest at the end of the tile gives one closing token."""
+    import itertools
+    Z = 127 // s
+    tokens, pending = [], 0
+    for is_zero, grp in itertools.groupby(levels, key=lambda v: v == 0):
+        grp = list(grp)
+        if is_zero:
+            tokens += [2 * s * Z] * (len(grp) // Z)
+            pending = len(grp) % Z
+        else:
+            for v in grp:
+                rank = sorted(set(range(-s, s + 1)) - {0}).index(v)
+                tokens.append(pending * 2 * s + rank)
+                pending = 0
+    if pending:
+        tokens.append(2 * s * Z)
+    return tokens
+
+
+def _zrun_expand(tokens, s, n):
+    Z = 127 // s
+    ranks = [v for v in range(-s, s + 1) if v != 0]
+    out = []
+    for t in tokens:
+        if t == 2 * s * Z:
+            out += [0] * Z
+        else:
+            out += [0] * (t // (2 * s)) + [ranks[t % (2 * s)]]
+    assert len(out) >= n and not any(out[n:])                  # only zeros are dropped at the tile's end
+    return out[:n]
+
+
+def _random_levels(rng, n, s, p_nonzero):
+    q = rng.integers(1, s + 1, n) * rng.choice([-1, 1], n)
+    return np.where(rng.random(n) < p_nonzero, q, 0).astype(np.int8)
+
+
+def test_zrun_alphabet():
+    """Z = floor(127/s) and 2sZ + 1 <= 255 tokens for every s the codec takes."""
+    for s in range(1, 128):
+        Z, A = oracle.zrun_max_run(s), oracle.zrun_symbols(s)
+        assert Z == 127 // s and Z >= 1
+        assert A == 2 * s * Z + 1 and A <= 255 and A % 2 == 1
+        assert 2 * s * (Z + 1) + 1 > 255                      # Z is the largest run that fits a byte of tokens
+    assert [oracle.zrun_max_run(s) for s in (1, 3, 4, 7, 127)] == [127, 42, 31, 18, 1]
+
+
+def test_zrun_tokens_hand_worked():
+    """Tokens of small tiles written out by hand (run * 2s + rank; 2sZ for "Z zeros")."""
+    tok = lambda q, s: oracle.zrun_tokens(np.array(q, np.int8), s).tolist()
+    # s = 1: ranks -1 -> 0, +1 -> 1; Z = 127, "Z zeros" = 254
+    assert tok([0, 0, 1, 0, -1, 0, 0], 1) == [2 * 2 + 1, 1 * 2 + 0, 254]
+    assert tok([1, 1, -1], 1) == [1, 1, 0]
+    assert tok([0] * 127, 1) == [254]                          # exactly Z zeros: one token, nothing pending
+    assert tok([0] * 128, 1) == [254, 254]                     # ... one more: a closing token
+    assert tok([0] * 127 + [1], 1) == [254, 1]
+    assert tok([0] * 126 + [-1], 1) == [126 * 2 + 0]
+    assert tok([], 1) == []
+    # s = 3: ranks -3,-2,-1,1,2,3 -> 0..5; Z = 42, "Z zeros" = 252
+    assert tok([-3, 0, 2, 0, 0, 0, 1], 3) == [0, 1 * 6 + 4, 3 * 6 + 3]
+    # s = 63: Z = 2, 126 ranks, "Z zeros" = 252
+    assert tok([0, 0, 5], 63) == [252, 5 + 63 - 1]
+    assert tok([0, 0, 0, 5], 63) == [252, 126 + 67]
+    assert tok([0] * 5, 63) == [252, 252, 252]
+    # s = 127: Z = 1, every zero is a token of its own
+    assert tok([0, -127, 0, 0, 127], 127) == [254, 0, 254, 254, 253]
+
+
+@pytest.mark.parametrize("s", [1, 3, 4, 7, 20, 63, 127])
+def test_zrun_tokens_against_run_based_implementation(s):
+    """The scan in the oracle against a tokeniser written from the tile's runs; tokens expand
+    back to the levels; the histogram is the count of the tiles' tokens."""
+    rng = np.random.default_rng([41, s])
+    Z = 127 // s
+    for p_nz in (0.0, 0.01, 0.2, 0.9, 1.0):
+        for n in (1, Z, Z + 1, 3 * Z + 2, 257, 1000):
+            q = _random_levels(rng, n, s, p_nz)
+            got = oracle.zrun_tokens(q, s).tolist()
+            assert got == _zrun_tokens_by_runs(q.tolist(), s)
+            assert _zrun_expand(got, s, n) == q.tolist()
+    q = _random_levels(rng, 5000, s, 0.1)
+    tile = 512
+    want = np.zeros(oracle.zrun_symbols(s), np.uint64)
+    for e0 in range(0, q.size, tile):
+        for t in _zrun_tokens_by_runs(q[e0:e0 + tile].tolist(), s):
+            want[t] += 1
+    assert np.array_equal(oracle.zrun_histogram(q, s, tile=tile), want)
+
+
+@pytest.mark.parametrize("s,n,tile,group", [(1, 10000, 4096, 64), (1, 8192, 4096, 1), (3, 5000, 512, 4), (7, 3000, 256, 3),
+                                            (127, 900, 128, 2), (4, 100, 4096, 64)])
+def test_zrun_stream_is_the_big_integer_model_and_decodes_by_tile(s, n, tile, group):
+    """The stream against a big-integer model (token codewords first bit first, LSB-first
+    stream, tiles back to back); per-tile bit counts and per-group offsets; every tile decodes
+    on its own from its offset."""
+    rng = np.random.default_rng([43, s, n])
+    q = _random_levels(rng, n, s, 0.15)
+    counts = oracle.zrun_histogram(q, s, tile=tile)
+    lengths = oracle.huffman_lengths(counts)
+    codes = oracle.huffman_codes(lengths)
+    assert lengths.tolist() == X.huffman_lengths([int(c) for c in counts])
+    stream, tile_bits, group_offsets, bits = oracle.zrun_encode(q, s, lengths, codes, tile=tile, group=group)
+    big, pos, want_bits = 0, 0, []
+    for e0 in range(0, n, tile):
+        begin = pos
+        for t in _zrun_tokens_by_runs(q[e0:e0 + tile].tolist(), s):
+            for b in range(int(lengths[t]) - 1, -1, -1):
+                big |= ((int(codes[t]) >> b) & 1) << pos
+                pos += 1
+        want_bits.append(pos - begin)
+    assert bits == pos and tile_bits.tolist() == want_bits
+    nbytes = (bits + 7) // 8
+    assert bytes(stream[:nbytes]) == big.to_bytes(nbytes, "little") and not stream[nbytes:].any()
+    starts = np.concatenate([[0], np.cumsum(tile_bits.astype(np.int64))])
+    assert group_offsets.tolist() == [int(starts[j]) for j in range(0, len(tile_bits), group)] + [bits]
+    assert bits <= 8 * oracle.zrun_max_bytes(n, s, tile)
+    for t, e0 in enumerate(range(0, n, tile)):
+        length = min(tile, n - e0)
+        assert np.array_equal(oracle.zrun_decode(stream, int(starts[t]), length, s, lengths, codes), q[e0:e0 + length])
+
+
+def test_zrun_length_against_the_entropy_bound():
+    """Section 4's bound sum_k d_k log2(d/d_k) for memoryless levels: the token code stays within
+    2 % of it while at most a third of the levels are non-zero (a per-level code cannot go below
+    one bit per element) and within 6 % for dense messages, never exceeds the Huffman guarantee
+    (token entropy + one bit per token), and never the capacity the library reserves."""
+    rng = np.random.default_rng(47)
+    n = 1 << 18
+    for s, p_nz in [(1, 0.005), (1, 0.04), (1, 0.3), (1, 0.66), (4, 0.05), (7, 0.3), (127, 0.5)]:
+        q = _random_levels(rng, n, s, p_nz)
+        bound = oracle.entropy_bound_bits(oracle.level_histogram(q, s))
+        counts = oracle.zrun_histogram(q, s)
+        lengths = oracle.huffman_lengths(counts)
+        _, tile_bits, _, bits = oracle.zrun_encode(q, s, lengths, oracle.huffman_codes(lengths))
+        assert bits == int(tile_bits.astype(np.int64).sum())
+        tokens = int(counts.sum())
+        token_entropy = oracle.entropy_bound_bits(counts)
+        assert token_entropy - 1e-6 <= bits < token_entropy + tokens
+        assert bits <= 8 * oracle.zrun_max_bytes(n, s)
+        if s < 127:
+            assert bits <= (1.02 if p_nz <= 0.34 else 1.06) * bound, (s, p_nz, bits / n, bound / n)
+        else:                                                  # Z = 1: a per-level Huffman code in effect
+            assert bits < bound + n
+    # the adversary of the capacity bound: alternating long runs and rare levels
+    q = np.zeros(n, np.int8)
+    q[::4097] = 1
+    counts = oracle.zrun_histogram(q, 1)
+    lengths = oracle.huffman_lengths(counts)
+    _, _, _, bits = oracle.zrun_encode(q, 1, lengths, oracle.huffman_codes(lengths))
+    assert bits <= 8 * oracle.zrun_max_bytes(n, 1)
