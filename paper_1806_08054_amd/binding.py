@@ -83,6 +83,13 @@ def lib() -> C.CDLL:
         L.ecq_huffman_build.argtypes = [C.c_int, C.c_int, vp, i64, vp, vp, vp]
         L.ecq_huffman_encode.argtypes = [shp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
         L.ecq_huffman_decode.argtypes = [shp, vp, i64, vp, i64, vp, vp, i64, vp, vp]
+        L.ecq_zrun_symbols.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.ecq_zrun_num_tiles.argtypes = [i64, C.POINTER(i64), C.POINTER(i64)]
+        L.ecq_zrun_stream_bytes.argtypes = [i64, C.c_int, C.POINTER(i64)]
+        L.ecq_zrun_histogram.argtypes = [shp, vp, vp, i64, vp]
+        L.ecq_zrun_build.argtypes = [C.c_int, C.c_int, vp, i64, vp, vp, vp]
+        L.ecq_zrun_encode.argtypes = [shp, vp, vp, vp, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.ecq_zrun_decode.argtypes = [shp, vp, i64, vp, i64, vp, i64, vp, vp, i64, vp, vp]
         L.ecq_philox_words.argtypes = [u64, u64, C.c_uint32, u64, i64, vp, vp]
         L.ecq_calib_add.argtypes = [vp, vp, vp, i64, vp]
         L.ecq_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -95,6 +102,8 @@ def lib() -> C.CDLL:
                      "ecq_dequant_aggregate", "ecq_dequant_aggregate_sgd", "ecq_level_histogram", "ecq_entropy_bound_bits", "ecq_check_division",
                      "ecq_philox_words", "ecq_calib_add", "ecq_calib_copy", "ecq_calib_gather", "ecq_huffman_num_tiles",
                      "ecq_huffman_build", "ecq_huffman_encode", "ecq_huffman_decode",
+                     "ecq_zrun_symbols", "ecq_zrun_num_tiles", "ecq_zrun_stream_bytes", "ecq_zrun_histogram",
+                     "ecq_zrun_build", "ecq_zrun_encode", "ecq_zrun_decode",
                      "ecq_version"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -212,6 +221,54 @@ def ecq_huffman_decode(shape: Shape, streams, stream_stride: int, tile_offsets, 
     _check(lib().ecq_huffman_decode(C.byref(shape), _ptr(streams), stream_stride, _ptr(tile_offsets),
                                     offset_stride, _ptr(lengths), _ptr(codewords), table_stride, _ptr(codes),
                                     _stream(stream)), "ecq_huffman_decode")
+
+
+ZRUN_TILE = 4096        # ECQ_ZRUN_TILE
+ZRUN_GROUP = 64         # ECQ_ZRUN_GROUP
+
+
+def zrun_symbols(s: int) -> tuple[int, int]:
+    """(Z, number of tokens) of the zero-run code for s levels."""
+    z, a = C.c_int(0), C.c_int(0)
+    _check(lib().ecq_zrun_symbols(s, C.byref(z), C.byref(a)), "ecq_zrun_symbols")
+    return z.value, a.value
+
+
+def zrun_num_tiles(n: int) -> tuple[int, int]:
+    """(tiles, groups) of a row of n elements."""
+    t, g = C.c_int64(0), C.c_int64(0)
+    _check(lib().ecq_zrun_num_tiles(n, C.byref(t), C.byref(g)), "ecq_zrun_num_tiles")
+    return t.value, g.value
+
+
+def zrun_stream_bytes(n: int, s: int) -> int:
+    out = C.c_int64(0)
+    _check(lib().ecq_zrun_stream_bytes(n, s, C.byref(out)), "ecq_zrun_stream_bytes")
+    return out.value
+
+
+def ecq_zrun_histogram(shape: Shape, codes, counts, count_stride: int, stream=None) -> None:
+    _check(lib().ecq_zrun_histogram(C.byref(shape), _ptr(codes), _ptr(counts), count_stride, _stream(stream)),
+           "ecq_zrun_histogram")
+
+
+def ecq_zrun_build(workers: int, s: int, counts, table_stride: int, lengths, codewords, stream=None) -> None:
+    _check(lib().ecq_zrun_build(workers, s, _ptr(counts), table_stride, _ptr(lengths), _ptr(codewords),
+                                _stream(stream)), "ecq_zrun_build")
+
+
+def ecq_zrun_encode(shape: Shape, codes, lengths, codewords, table_stride: int, streams, stream_stride: int,
+                    tile_bits, tile_stride: int, group_offsets, group_stride: int, stream=None) -> None:
+    _check(lib().ecq_zrun_encode(C.byref(shape), _ptr(codes), _ptr(lengths), _ptr(codewords), table_stride,
+                                 _ptr(streams), stream_stride, _ptr(tile_bits), tile_stride, _ptr(group_offsets),
+                                 group_stride, _stream(stream)), "ecq_zrun_encode")
+
+
+def ecq_zrun_decode(shape: Shape, streams, stream_stride: int, tile_bits, tile_stride: int, group_offsets,
+                    group_stride: int, lengths, codewords, table_stride: int, codes, stream=None) -> None:
+    _check(lib().ecq_zrun_decode(C.byref(shape), _ptr(streams), stream_stride, _ptr(tile_bits), tile_stride,
+                                 _ptr(group_offsets), group_stride, _ptr(lengths), _ptr(codewords), table_stride,
+                                 _ptr(codes), _stream(stream)), "ecq_zrun_decode")
 
 
 def ecq_check_division(per_divisor: int, salt: int, mismatches, stream=None) -> None:

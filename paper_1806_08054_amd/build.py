@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libecq.so")
-SOURCES = ["ecq_api.hip", "ecq_kernels.hip", "ecq_huffman.hip"]
+SOURCES = ["ecq_api.hip", "ecq_kernels.hip", "ecq_huffman.hip", "ecq_zrun.hip"]
 
 # -ffp-contract=off: every binary32 operation of the codec rounds on its own.
 # packed-fp32-ops off: no v_pk_*_f32 instructions are generated.

@@ -362,6 +362,126 @@ int ecq_huffman_decode(const ecq_shape *shape, const uint8_t *streams, int64_t s
                : ECQ_ERR_LAUNCH;
 }
 
+namespace ecq {
+static int64_t zrun_stream_bytes(int64_t n, int s)
+{
+    const int64_t r = code_bits(s), Z = 127 / s;
+    const int64_t tiles = (n + ECQ_ZRUN_TILE - 1) / ECQ_ZRUN_TILE;
+    return ((n * r + tiles * r * Z + 7) / 8 + 3) / 4 * 4;
+}
+
+// Checks shared by the two zero-run stream entry points.
+static int check_zrun(const ecq_shape *sh, const void *codes, const void *lengths, const void *codewords,
+                      int64_t table_stride, const void *streams, int64_t stream_stride, const void *tile_bits,
+                      int64_t tile_stride, const void *group_offsets, int64_t group_stride)
+{
+    const int st = check_shape(sh);
+    if (st != ECQ_OK) return st;
+    if (!codes || !lengths || !codewords || !streams || !tile_bits || !group_offsets) return ECQ_ERR_NULL;
+    const int64_t tiles = (sh->n + ECQ_ZRUN_TILE - 1) / ECQ_ZRUN_TILE;
+    const int64_t groups = (tiles + ECQ_ZRUN_GROUP - 1) / ECQ_ZRUN_GROUP;
+    if (table_stride < 2 * (int64_t)sh->s * (127 / sh->s) + 1) return ECQ_ERR_STRIDE;
+    if ((stream_stride & 3) != 0 || stream_stride < zrun_stream_bytes(sh->n, sh->s)) return ECQ_ERR_STRIDE;
+    if (tile_stride < tiles || group_stride < groups + 1) return ECQ_ERR_STRIDE;
+    if (!aligned(codes, 4) || !aligned(streams, 4) || !aligned(tile_bits, 4) || !aligned(group_offsets, 8) ||
+        !aligned(codewords, 8))
+        return ECQ_ERR_ALIGN;
+    return ECQ_OK;
+}
+}  // namespace ecq
+
+int ecq_zrun_symbols(int s, int *max_run, int *symbols)
+{
+    if (s < 1 || s > 127) return ECQ_ERR_LEVELS;
+    if (max_run) *max_run = 127 / s;
+    if (symbols) *symbols = 2 * s * (127 / s) + 1;
+    return ECQ_OK;
+}
+
+int ecq_zrun_num_tiles(int64_t n, int64_t *tiles, int64_t *groups)
+{
+    if (n < 0 || n > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    const int64_t t = (n + ECQ_ZRUN_TILE - 1) / ECQ_ZRUN_TILE;
+    if (tiles) *tiles = t;
+    if (groups) *groups = (t + ECQ_ZRUN_GROUP - 1) / ECQ_ZRUN_GROUP;
+    return ECQ_OK;
+}
+
+int ecq_zrun_stream_bytes(int64_t n, int s, int64_t *bytes)
+{
+    if (!bytes) return ECQ_ERR_NULL;
+    if (s < 1 || s > 127) return ECQ_ERR_LEVELS;
+    if (n < 0 || n > ECQ_MAX_N) return ECQ_ERR_SHAPE;
+    *bytes = ecq::zrun_stream_bytes(n, s);
+    return ECQ_OK;
+}
+
+int ecq_zrun_histogram(const ecq_shape *shape, const uint8_t *codes, uint64_t *counts, int64_t count_stride,
+                       void *stream)
+{
+    const int st = ecq::check_shape(shape);
+    if (st != ECQ_OK) return st;
+    if (!codes || !counts) return ECQ_ERR_NULL;
+    if (count_stride < 2 * (int64_t)shape->s * (127 / shape->s) + 1) return ECQ_ERR_STRIDE;
+    if (!ecq::aligned(codes, 4) || !ecq::aligned(counts, 8)) return ECQ_ERR_ALIGN;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    return ecq::launch_zrun_histogram(a, reinterpret_cast<unsigned long long *>(counts), count_stride,
+                                      static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_zrun_build(int workers, int s, const uint64_t *counts, int64_t table_stride, uint8_t *lengths,
+                   uint64_t *codewords, void *stream)
+{
+    if (workers <= 0 || workers > 65535) return ECQ_ERR_SHAPE;
+    if (s < 1 || s > 127) return ECQ_ERR_LEVELS;
+    if (!counts || !lengths || !codewords) return ECQ_ERR_NULL;
+    const int symbols = 2 * s * (127 / s) + 1;
+    if (table_stride < symbols) return ECQ_ERR_STRIDE;
+    if (!ecq::aligned(counts, 8) || !ecq::aligned(codewords, 8)) return ECQ_ERR_ALIGN;
+    return ecq::launch_huffman_build(workers, symbols, reinterpret_cast<const unsigned long long *>(counts),
+                                     table_stride, lengths, reinterpret_cast<unsigned long long *>(codewords),
+                                     static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_zrun_encode(const ecq_shape *shape, const uint8_t *codes, const uint8_t *lengths, const uint64_t *codewords,
+                    int64_t table_stride, uint8_t *streams, int64_t stream_stride, uint32_t *tile_bits,
+                    int64_t tile_stride, uint64_t *group_offsets, int64_t group_stride, void *stream)
+{
+    const int st = ecq::check_zrun(shape, codes, lengths, codewords, table_stride, streams, stream_stride, tile_bits,
+                                   tile_stride, group_offsets, group_stride);
+    if (st != ECQ_OK) return st;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = const_cast<uint8_t *>(codes);
+    return ecq::launch_zrun_encode(a, lengths, reinterpret_cast<const unsigned long long *>(codewords), table_stride,
+                                   reinterpret_cast<uint32_t *>(streams), stream_stride / 4, tile_bits, tile_stride,
+                                   reinterpret_cast<unsigned long long *>(group_offsets), group_stride,
+                                   static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
+int ecq_zrun_decode(const ecq_shape *shape, const uint8_t *streams, int64_t stream_stride, const uint32_t *tile_bits,
+                    int64_t tile_stride, const uint64_t *group_offsets, int64_t group_stride, const uint8_t *lengths,
+                    const uint64_t *codewords, int64_t table_stride, uint8_t *codes, void *stream)
+{
+    const int st = ecq::check_zrun(shape, codes, lengths, codewords, table_stride, streams, stream_stride, tile_bits,
+                                   tile_stride, group_offsets, group_stride);
+    if (st != ECQ_OK) return st;
+    ecq::Args a = ecq::make_args(*shape);
+    a.codes = codes;
+    return ecq::launch_zrun_decode(a, lengths, reinterpret_cast<const unsigned long long *>(codewords), table_stride,
+                                   reinterpret_cast<const uint32_t *>(streams), stream_stride / 4, tile_bits,
+                                   tile_stride, reinterpret_cast<const unsigned long long *>(group_offsets),
+                                   group_stride, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ECQ_OK
+               : ECQ_ERR_LAUNCH;
+}
+
 int ecq_check_division(int per_divisor, uint32_t salt, uint64_t *mismatches, void *stream)
 {
     if (!mismatches) return ECQ_ERR_NULL;

@@ -208,6 +208,31 @@ __device__ __forceinline__ uint32_t group_max(uint32_t x, int lanes)
     return x;
 }
 
+// ---- wave-level synchronisation and prefix sums (entropy coders) ------------------------------
+
+// Orders a wave's LDS writes before its later LDS reads of other lanes' data.  Only that wave
+// touches the memory in question, and a wave's LDS operations complete in order.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave: four shifts inside each row of 16 lanes,
+// then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.  Lanes without
+// a source add 0.
+__device__ __forceinline__ unsigned int wave_inclusive_scan(unsigned int x)
+{
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, false);   // row_shr:1
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, false);   // row_shr:2
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false);   // row_shr:4
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, false);   // row_shr:8
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false);   // row_bcast:15
+    x += (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false);   // row_bcast:31
+    return x;
+}
+
 // ---- l2 norm: sum of squares over a balanced binary tree by element index --------------------
 //
 // a + b == b + a in IEEE arithmetic, so a butterfly in which both partners add leaves the same

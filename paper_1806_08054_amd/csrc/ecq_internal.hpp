@@ -60,6 +60,16 @@ hipError_t launch_huffman_encode(const Args &a, const uint8_t *lengths, const un
 hipError_t launch_huffman_decode(const Args &a, const uint8_t *lengths, const unsigned long long *codewords,
                                  int64_t table_stride, const uint32_t *streams, int64_t stream_stride_words,
                                  const unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream);
+// Zero-run Huffman coder (ecq_zrun.hip).  a.codes = the fixed-length message.
+hipError_t launch_zrun_histogram(const Args &a, unsigned long long *counts, int64_t count_stride, hipStream_t stream);
+hipError_t launch_zrun_encode(const Args &a, const uint8_t *lengths, const unsigned long long *codewords,
+                              int64_t table_stride, uint32_t *streams, int64_t stream_stride_words,
+                              uint32_t *tile_bits, int64_t tile_stride, unsigned long long *group_offsets,
+                              int64_t group_stride, hipStream_t stream);
+hipError_t launch_zrun_decode(const Args &a, const uint8_t *lengths, const unsigned long long *codewords,
+                              int64_t table_stride, const uint32_t *streams, int64_t stream_stride_words,
+                              const uint32_t *tile_bits, int64_t tile_stride, const unsigned long long *group_offsets,
+                              int64_t group_stride, hipStream_t stream);
 hipError_t launch_check_division(int per_divisor, uint32_t salt, unsigned long long *mismatches,
                                  hipStream_t stream);
 hipError_t launch_philox_words(uint32_t key0, uint32_t key1, uint32_t step_lo, uint32_t step_hi,

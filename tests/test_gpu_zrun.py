@@ -1,0 +1,269 @@
+"""GPU parity of the zero-run Huffman coder (Section 4, cost paragraph: entropy coding of the
+quantised levels) against the CPU oracle: token counts, code, per-tile bit counts, group
+offsets and stream bit-exact; decode(encode(message)) = message; the library decodes a stream
+the oracle wrote.  Every oracle input is a seeded level array or the oracle's own output.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from tests.test_gpu_parity import SEED, GpuState, _dev
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_1806_08054_amd as E
+    return E
+
+
+def _levels(rng, P, n, s, p_nonzero):
+    q = rng.integers(1, s + 1, (P, n)) * rng.choice([-1, 1], (P, n))
+    return np.where(rng.random((P, n)) < p_nonzero, q, 0).astype(np.int8)
+
+
+class ZrunBuffers:
+    def __init__(self, E, P, N, s, pad=0):
+        self.Z, self.symbols = E.zrun_symbols(s)
+        self.tiles, self.groups = E.zrun_num_tiles(N)
+        self.table_stride = self.symbols + pad
+        self.stream_stride = E.zrun_stream_bytes(N, s) + 4 * pad
+        self.tile_stride = self.tiles + pad
+        self.group_stride = self.groups + 1 + pad
+        dev = "cuda"
+        self.counts = torch.full((P, self.table_stride), -1, dtype=torch.int64, device=dev)
+        self.lengths = torch.full((P, self.table_stride), 0xEE, dtype=torch.uint8, device=dev)
+        self.codewords = torch.full((P, self.table_stride), -1, dtype=torch.int64, device=dev)
+        self.streams = torch.full((P, self.stream_stride), 0xEE, dtype=torch.uint8, device=dev)
+        self.tile_bits = torch.full((P, self.tile_stride), -1, dtype=torch.int32, device=dev)
+        self.group_offsets = torch.full((P, self.group_stride), -1, dtype=torch.int64, device=dev)
+
+
+def _roundtrip(E, q, s, bucket=512, pad=0):
+    """q: [P, N] int8 levels.  Encodes their fixed-length message on the GPU and compares every
+    product with the oracle's."""
+    P, N = q.shape
+    st = GpuState(E, P, N, bucket, s, pad=pad)
+    codes_ref = oracle.pack_rows(q, s)
+    st.codes[:, : st.rb] = _dev(codes_ref)
+    zb = ZrunBuffers(E, P, N, s, pad=pad)
+    E.ecq_zrun_histogram(st.sh, st.codes, zb.counts, zb.table_stride)
+    E.ecq_zrun_build(P, s, zb.counts, zb.table_stride, zb.lengths, zb.codewords)
+    E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                      zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+    back = torch.full_like(st.codes, 0xEE)
+    E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                      zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, back)
+    torch.cuda.synchronize()
+    A = zb.symbols
+    counts = zb.counts.cpu().numpy()
+    lengths = zb.lengths.cpu().numpy()
+    codewords = zb.codewords.cpu().numpy().view(np.uint64)
+    streams = zb.streams.cpu().numpy()
+    tile_bits = zb.tile_bits.cpu().numpy().view(np.uint32)
+    group_offsets = zb.group_offsets.cpu().numpy().view(np.uint64)
+    total_bits = 0
+    for p in range(P):
+        ref_counts = oracle.zrun_histogram(q[p], s)
+        assert np.array_equal(counts[p, :A].astype(np.uint64), ref_counts), f"token counts differ, row {p}"
+        ref_len = oracle.huffman_lengths(ref_counts)
+        ref_cw = oracle.huffman_codes(ref_len)
+        assert np.array_equal(lengths[p, :A], ref_len), f"codeword lengths differ, row {p}"
+        assert np.array_equal(codewords[p, :A], ref_cw), f"codewords differ, row {p}"
+        ref_stream, ref_bits, ref_groups, bits = oracle.zrun_encode(q[p], s, ref_len, ref_cw)
+        assert np.array_equal(tile_bits[p, : zb.tiles], ref_bits), f"tile sizes differ, row {p}"
+        assert np.array_equal(group_offsets[p, : zb.groups + 1], ref_groups), f"group offsets differ, row {p}"
+        nbytes = (bits + 31) // 32 * 4
+        assert np.array_equal(streams[p, :nbytes], ref_stream[:nbytes]), f"stream differs, row {p}"
+        assert np.all(streams[p, nbytes:] == 0xEE), "bytes beyond the stream were written"
+        total_bits += bits
+    # nothing outside the documented extents is touched
+    assert np.all(counts[:, A:] == -1) and np.all(lengths[:, A:] == 0xEE)
+    assert np.all(zb.tile_bits.cpu().numpy()[:, zb.tiles:] == -1)
+    assert np.all(zb.group_offsets.cpu().numpy()[:, zb.groups + 1:] == -1)
+    assert torch.equal(back[:, : st.rb].cpu(), torch.from_numpy(codes_ref)), "decode(encode(message)) differs"
+    assert bool((back[:, st.rb:] == 0xEE).all())
+    return total_bits
+
+
+@pytest.mark.parametrize("s,p_nz", [(1, 0.04), (1, 0.33), (1, 0.0), (1, 1.0), (3, 0.1), (4, 0.06), (7, 0.3),
+                                    (20, 0.2), (63, 0.5), (127, 0.5), (2, 0.002)])
+def test_zrun_matches_oracle(E, s, p_nz):
+    """Several groups of 64 tiles, whole tiles and a ragged tail, from all zeros to all
+    non-zero, every code width."""
+    rng = np.random.default_rng([s, int(p_nz * 1000)])
+    N = 2 * 64 * 4096 + 5 * 4096 + 777
+    _roundtrip(E, _levels(rng, 2, N, s, p_nz), s)
+
+
+@pytest.mark.parametrize("N", [1, 7, 16, 127, 128, 1023, 1024, 1025, 4095, 4096, 4097, 8192, 64 * 4096, 64 * 4096 + 1])
+def test_zrun_lengths_around_tile_and_group_boundaries(E, N):
+    rng = np.random.default_rng(N)
+    for s, p_nz in ((1, 0.1), (5, 0.3)):
+        _roundtrip(E, _levels(rng, 3, N, s, p_nz), s, bucket=8, pad=3)
+
+
+def test_zrun_runs_around_the_longest_run(E):
+    """Runs of exactly Z - 1, Z, Z + 1 and multiples of Z zeros, at the start, in the middle and
+    at the end of tiles, and across step (1024) and tile (4096) boundaries."""
+    for s in (1, 4, 31, 127):
+        Z = 127 // s
+        rng = np.random.default_rng(s)
+        q = np.zeros((2, 5 * 4096 + 300), np.int8)
+        at = 0
+        for run in [Z - 1, Z, Z + 1, 2 * Z, 2 * Z + 1, 0, 0, 1, 1023, 1024, 4095, 4096, 3 * Z - 1, 5]:
+            at += max(run, 0)
+            if at >= q.shape[1]:
+                break
+            q[0, at] = rng.integers(1, s + 1) * rng.choice([-1, 1])
+            at += 1
+        q[1, 4095] = 1                                       # a tile that ends with its only level
+        q[1, 4096] = -1                                      # ... and one that starts with it
+        q[1, 2 * 4096 + 1023: 2 * 4096 + 1025] = 1           # both sides of a step boundary
+        _roundtrip(E, q, s)
+
+
+def test_zrun_long_codewords(E):
+    """Token counts that fall off like Fibonacci numbers give codewords beyond 24 and beyond 32
+    bits: the encoder's long path and the decoder's canonical walk."""
+    s = 1
+    fib = [1, 1]
+    while len(fib) < 40:
+        fib.append(fib[-1] + fib[-2])
+    # token (z, +1) for z = 0..39 occurs fib[z] times: a message made of such tokens in random order
+    rng = np.random.default_rng(5)
+    reps = np.repeat(np.arange(28), [fib[z] for z in range(28)])      # about 830 k tokens
+    rng.shuffle(reps)
+    total = int((reps + 1).sum())
+    q = np.zeros((1, total), np.int8)
+    ends = np.cumsum(reps + 1) - 1
+    q[0, ends] = 1
+    _roundtrip(E, q, s)
+
+
+def test_zrun_decodes_an_oracle_stream(E):
+    """The library's decoder on a stream, index and tables written by the oracle."""
+    s, P, N = 3, 2, 64 * 4096 + 3000
+    rng = np.random.default_rng(77)
+    q = _levels(rng, P, N, s, 0.08)
+    st = GpuState(E, P, N, 512, s)
+    zb = ZrunBuffers(E, P, N, s)
+    zb.streams.zero_()
+    for p in range(P):
+        counts = oracle.zrun_histogram(q[p], s)
+        lengths = oracle.huffman_lengths(counts)
+        cw = oracle.huffman_codes(lengths)
+        stream, tile_bits, groups, bits = oracle.zrun_encode(q[p], s, lengths, cw)
+        zb.lengths[p, : zb.symbols] = _dev(lengths)
+        zb.codewords[p, : zb.symbols] = _dev(cw.view(np.int64))
+        zb.streams[p, : stream.size] = _dev(stream)
+        zb.tile_bits[p, : zb.tiles] = _dev(tile_bits.view(np.int32))
+        zb.group_offsets[p, : zb.groups + 1] = _dev(groups.view(np.int64))
+    E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                      zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, st.codes)
+    torch.cuda.synchronize()
+    assert np.array_equal(st.codes.cpu().numpy()[:, : st.rb], oracle.pack_rows(q, s))
+
+
+def test_zrun_foreign_tables_stay_in_bounds(E):
+    """Tables that do not belong to the message (all lengths 63, or all 0) give a meaningless
+    stream, never an access outside the documented extents."""
+    s, P, N = 1, 2, 3 * 4096 + 100
+    rng = np.random.default_rng(9)
+    q = _levels(rng, P, N, s, 0.5)
+    st = GpuState(E, P, N, 512, s)
+    st.codes[:, : st.rb] = _dev(oracle.pack_rows(q, s))
+    for fill in (63, 0, 200):
+        zb = ZrunBuffers(E, P, N, s, pad=2)
+        zb.lengths.fill_(fill)
+        zb.codewords.fill_(-1)
+        E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                          zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+        back = torch.full_like(st.codes, 0xEE)
+        E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                          zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, back)
+        torch.cuda.synchronize()
+        assert bool((back[:, st.rb:] == 0xEE).all())
+        assert bool((zb.tile_bits[:, zb.tiles:] == -1).all()) and bool((zb.group_offsets[:, zb.groups + 1:] == -1).all())
+
+
+def test_zrun_argument_errors(E):
+    s, P, N = 1, 2, 10000
+    st = GpuState(E, P, N, 512, s)
+    zb = ZrunBuffers(E, P, N, s)
+    enc = lambda **kw: E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, kw.get("ts", zb.table_stride),
+                                         zb.streams, kw.get("ss", zb.stream_stride), zb.tile_bits,
+                                         kw.get("tl", zb.tile_stride), zb.group_offsets, kw.get("gs", zb.group_stride))
+    for kw in ({"ts": zb.symbols - 1}, {"ss": zb.stream_stride - 4}, {"ss": zb.stream_stride + 2},
+               {"tl": zb.tiles - 1}, {"gs": zb.groups}):
+        with pytest.raises(E.EcqError) as err:
+            enc(**kw)
+        assert err.value.status == -5
+    with pytest.raises(E.EcqError) as err:
+        E.ecq_zrun_histogram(st.sh, st.codes, zb.counts, zb.symbols - 1)
+    assert err.value.status == -5
+    with pytest.raises(E.EcqError) as err:
+        E.ecq_zrun_build(P, 0, zb.counts, zb.table_stride, zb.lengths, zb.codewords)
+    assert err.value.status == -3
+    torch.cuda.synchronize()
+    assert bool((zb.streams == 0xEE).all()) and bool((zb.tile_bits == -1).all())
+
+
+@pytest.mark.parametrize("name,rows", [("resnet50", [0, 7]), ("alexnet", [5]), ("vgg16", [31]), ("paper_cnn", [3])])
+def test_zrun_full_size(E, name, rows):
+    """The zero-run coder on one iteration's messages at the benchmark's sizes: every row
+    decodes back to its fixed-length message; the rows in `rows` are compared in full (token
+    counts, code, tile sizes, group offsets, stream) with the oracle, whose levels come from its
+    own quantiser run on the seeded gradients; every row's length stays below the paper's bound
+    sum_k d_k log2(d/d_k) plus 3 % (index excluded)."""
+    wl = synth.WORKLOADS[name]
+    st = GpuState(E, wl.P, wl.N, wl.bucket, wl.s, aligned=True, norm=wl.norm)
+    synth.gradients(wl, 0, device="cuda", out=st.g)
+    E.ecq_quantize_update(st.sh, st.g, st.h, wl.alpha, wl.beta, SEED, 0, st.codes, st.scales)
+    P, N, s = wl.P, wl.N, wl.s
+    q_rows = {}
+    for p in rows:
+        g_row = st.g[p, :N].cpu().numpy()[None, :]
+        q_rows[p] = oracle.batch_step(g_row, np.zeros_like(g_row), wl.bucket, s, wl.alpha, wl.beta, SEED, 0,
+                                      worker0=p, norm=wl.norm)[0][0]
+    del st.g, st.h
+    zb = ZrunBuffers(E, P, N, s)
+    bins = 2 * s + 1
+    level_counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    E.ecq_level_histogram(st.sh, st.codes, level_counts, bins)
+    E.ecq_zrun_histogram(st.sh, st.codes, zb.counts, zb.table_stride)
+    E.ecq_zrun_build(P, s, zb.counts, zb.table_stride, zb.lengths, zb.codewords)
+    E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                      zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+    back = torch.zeros_like(st.codes)
+    E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                      zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, back)
+    torch.cuda.synchronize()
+    assert torch.equal(back[:, : st.rb], st.codes[:, : st.rb]), "decode(encode(message)) differs from the message"
+    total = zb.group_offsets[:, zb.groups].cpu().numpy()
+    lc = level_counts.cpu().numpy().astype(np.uint64)
+    for p in range(P):
+        bound = oracle.entropy_bound_bits(lc[p])
+        assert int(total[p]) <= 1.03 * bound + 64, (p, int(total[p]) / N, bound / N)
+        assert int(total[p]) == int(zb.tile_bits[p, : zb.tiles].to(torch.int64).sum().item())
+    for p in rows:
+        q = q_rows[p]
+        ref_counts = oracle.zrun_histogram(q, s)
+        assert np.array_equal(zb.counts[p, : zb.symbols].cpu().numpy().astype(np.uint64), ref_counts)
+        ref_len = oracle.huffman_lengths(ref_counts)
+        ref_cw = oracle.huffman_codes(ref_len)
+        assert np.array_equal(zb.lengths[p, : zb.symbols].cpu().numpy(), ref_len)
+        assert np.array_equal(zb.codewords[p, : zb.symbols].cpu().numpy().view(np.uint64), ref_cw)
+        ref_stream, ref_bits, ref_groups, bits = oracle.zrun_encode(q, s, ref_len, ref_cw)
+        assert np.array_equal(zb.tile_bits[p, : zb.tiles].cpu().numpy().view(np.uint32), ref_bits)
+        assert np.array_equal(zb.group_offsets[p, : zb.groups + 1].cpu().numpy().view(np.uint64), ref_groups)
+        nbytes = (bits + 7) // 8
+        assert np.array_equal(zb.streams[p, :nbytes].cpu().numpy(), ref_stream[:nbytes]), f"stream differs, worker {p}"
+        bound = oracle.entropy_bound_bits(oracle.level_histogram(q, s))
+        print(f"{name}: worker {p}: {bits / N:.4f} bits per element, bound {bound / N:.4f}, "
+              f"fixed length {E.code_bits(s)}", flush=True)
