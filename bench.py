@@ -92,8 +92,11 @@ def cpu_baseline(wl, sample_n, g_sample, steps=3):
 
 
 def entropy_coding(E, torch, sh, wl, codes, timed):
-    """Outside the timed region: the Huffman coding of the last step's messages that the
-    paper's communication-cost figures assume (Section 4, cost paragraph), leg by leg."""
+    """Outside the timed region: the entropy coding of the last step's messages that the paper's
+    communication-cost figures assume (Section 4, cost paragraph), leg by leg, for the per-level
+    Huffman code and for the zero-run Huffman code.  bits_per_element counts everything that has
+    to travel besides the bucket scales: stream, per-tile sizes, group offsets, code lengths;
+    compression_vs_fp32 also counts the 32-bit scale of every bucket."""
     P, N, s = wl.P, wl.N, wl.s
     bins, tiles = 2 * s + 1, E.huffman_num_tiles(N)
     counts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
@@ -112,11 +115,44 @@ def entropy_coding(E, torch, sh, wl, codes, timed):
     ok = bool(torch.equal(back[:, :rb], codes[:, :rb]))
     bits = int(offs[:, tiles].sum().item())
     bound = sum(E.ecq_entropy_bound_bits(row) for row in counts.cpu().tolist())
-    return {"bits_per_element": round(bits / (P * N), 4), "entropy_bound_bits_per_element": round(bound / (P * N), 4),
-            "fixed_length_bits_per_element": E.code_bits(s), "histogram_ms": round(hist_ms, 4),
-            "build_ms": round(build_ms, 4), "encode_ms": round(enc_ms, 4), "decode_ms": round(dec_ms, 4),
-            "encode_gelem_per_s": round(P * N / (enc_ms * 1e-3) / 1e9, 1),
-            "decode_gelem_per_s": round(P * N / (dec_ms * 1e-3) / 1e9, 1), "round_trip_ok": ok}
+    per_level = {"bits_per_element": round(bits / (P * N), 4), "histogram_ms": round(hist_ms, 4),
+                 "build_ms": round(build_ms, 4), "encode_ms": round(enc_ms, 4), "decode_ms": round(dec_ms, 4),
+                 "encode_gelem_per_s": round(P * N / (enc_ms * 1e-3) / 1e9, 1),
+                 "decode_gelem_per_s": round(P * N / (dec_ms * 1e-3) / 1e9, 1), "round_trip_ok": ok}
+    del streams, offs
+    # The zero-run code (tokens = a run of zeros with the level that ends it): the one that can
+    # reach the paper's bound when it lies below one bit per element.
+    _, symbols = E.zrun_symbols(s)
+    ztiles, zgroups = E.zrun_num_tiles(N)
+    zstride = E.zrun_stream_bytes(N, s)
+    zcounts = torch.zeros(P, symbols, dtype=torch.int64, device="cuda")
+    zlengths = torch.zeros(P, symbols, dtype=torch.uint8, device="cuda")
+    zwords = torch.zeros(P, symbols, dtype=torch.int64, device="cuda")
+    zstreams = torch.zeros(P, zstride, dtype=torch.uint8, device="cuda")
+    tile_bits = torch.zeros(P, ztiles, dtype=torch.int32, device="cuda")
+    group_offs = torch.zeros(P, zgroups + 1, dtype=torch.int64, device="cuda")
+    back.zero_()
+    zhist_ms = timed(lambda: E.ecq_zrun_histogram(sh, codes, zcounts, symbols))
+    zbuild_ms = timed(lambda: E.ecq_zrun_build(P, s, zcounts, symbols, zlengths, zwords))
+    zenc_ms = timed(lambda: E.ecq_zrun_encode(sh, codes, zlengths, zwords, symbols, zstreams, zstride, tile_bits, ztiles,
+                                              group_offs, zgroups + 1))
+    zdec_ms = timed(lambda: E.ecq_zrun_decode(sh, zstreams, zstride, tile_bits, ztiles, group_offs, zgroups + 1,
+                                              zlengths, zwords, symbols, back))
+    zok = bool(torch.equal(back[:, :rb], codes[:, :rb]))
+    zbits = int(group_offs[:, zgroups].sum().item())
+    index_bits = P * (32 * ztiles + 64 * (zgroups + 1) + 8 * symbols)      # tile sizes, group offsets, code lengths
+    zero_run = {"stream_bits_per_element": round(zbits / (P * N), 4),
+                "index_bits_per_element": round(index_bits / (P * N), 4),
+                "bits_per_element": round((zbits + index_bits) / (P * N), 4),
+                "over_entropy_bound_pct": round(100 * ((zbits + index_bits) / bound - 1), 2) if bound > 0 else None,
+                "histogram_ms": round(zhist_ms, 4), "build_ms": round(zbuild_ms, 4), "encode_ms": round(zenc_ms, 4),
+                "decode_ms": round(zdec_ms, 4), "encode_gelem_per_s": round(P * N / (zenc_ms * 1e-3) / 1e9, 1),
+                "decode_gelem_per_s": round(P * N / (zdec_ms * 1e-3) / 1e9, 1), "round_trip_ok": zok}
+    return {"entropy_bound_bits_per_element": round(bound / (P * N), 4),
+            "fixed_length_bits_per_element": E.code_bits(s),
+            "bits_per_element": zero_run["bits_per_element"],
+            "compression_vs_fp32": round(32 * P * N / (zbits + index_bits + 32 * P * wl.nb), 2),
+            "zero_run_huffman": zero_run, "per_level_huffman": per_level}
 
 
 def main():
