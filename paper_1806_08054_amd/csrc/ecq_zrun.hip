@@ -26,10 +26,12 @@
 namespace ecq {
 
 constexpr int kZTile = ECQ_ZRUN_TILE;                          // elements per tile
-constexpr int kZGroup = ECQ_ZRUN_GROUP;                        // tiles per group = per block of the coders
+constexpr int kZGroup = ECQ_ZRUN_GROUP;                        // tiles per group (one stream offset each)
+constexpr int kZBlockTiles = 16;                               // consecutive tiles per block of the coders
 constexpr int kZStep = 1024;                                   // elements a wave takes at a time (16 per lane)
 constexpr int kZSteps = kZTile / kZStep;
-constexpr int kZWaveTiles = kZGroup / 4;                       // consecutive tiles per wave
+constexpr int kZWaveTiles = kZBlockTiles / 4;                  // consecutive tiles per wave
+constexpr int kZWaveSteps = kZWaveTiles * kZSteps;
 constexpr int kZMaxLen = 63;                                   // longest codeword handled
 constexpr int kZFastBits = 10;                                 // decode: direct table on 10 stream bits
 constexpr int kZRingWords = 16;                                // decode: words a lane collects before storing
@@ -39,10 +41,11 @@ constexpr int kZRingStride = 20;                               // ... and the di
 // that aligns the buffer with the stream's words.
 constexpr int kZBufWords = ((kZStep + 1) * kZMaxLen + 31 + 31) / 32 + 1;
 
-static_assert(kZTile == 4096 && kZGroup == 64, "a block of four waves takes one group, a wave 16 tiles");
+static_assert(kZTile == 4096 && kZGroup == 64 && kZGroup % kZBlockTiles == 0, "a wave scans one group's 64 tile sizes");
 
 struct ZrunShape {
     int s, two_s, Z, zz;                                       // zz = 2sZ: the token "Z zeros"
+    unsigned int magic;                                        // x / Z = (x * magic) >> 20 for x < 8192
 };
 
 __device__ __forceinline__ ZrunShape zrun_shape(int s)
@@ -52,6 +55,7 @@ __device__ __forceinline__ ZrunShape zrun_shape(int s)
     z.two_s = 2 * s;
     z.Z = 127 / s;
     z.zz = 2 * s * z.Z;
+    z.magic = (1u << 20) / (unsigned int)z.Z + 1u;
     return z;
 }
 
@@ -146,18 +150,21 @@ __device__ __forceinline__ int lane_run_in(const Codes16<R> &cd, int valid, int 
     uint32_t mask = NonZero<R>::mask(cd, z.s);
     if (valid < 16) mask &= (1u << (valid * kStride)) - 1u;
     const int last = mask ? lane * 16 + (31 - __builtin_clz(mask)) / kStride : -1;
+    // Inclusive maximum scan over the wave (lanes without a source take -1), then one lane down.
     int incl = last;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int below = __shfl_up(incl, d, 64);
-        if (lane >= d) incl = below > incl ? below : incl;
-    }
-    int before = __shfl_up(incl, 1, 64);
-    if (lane == 0) before = -1;
+    auto step_max = [&](int other) { incl = other > incl ? other : incl; };
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x111, 0xF, 0xF, false));   // row_shr:1
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x112, 0xF, 0xF, false));   // row_shr:2
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x114, 0xF, 0xF, false));   // row_shr:4
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x118, 0xF, 0xF, false));   // row_shr:8
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x142, 0xA, 0xF, false));   // row_bcast:15
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x143, 0xC, 0xF, false));   // row_bcast:31
+    const int before = __builtin_amdgcn_update_dpp(-1, incl, 0x138, 0xF, 0xF, false);   // wave_shr:1
     const int zeros = before >= 0 ? lane * 16 - before - 1 : since + lane * 16;
     const int wave_last = __builtin_amdgcn_readlane(incl, 63);
     since = wave_last >= 0 ? step_valid - wave_last - 1 : since + step_valid;
-    return zeros % z.Z;
+    // zeros < 4096 + 1024: the multiplication by the reciprocal is exact there.
+    return zeros - (int)(((unsigned int)zeros * z.magic) >> 20) * z.Z;
 }
 
 // The fixed-length codes of the 16 elements a lane owns in a step; returns how many exist.
@@ -193,12 +200,12 @@ __device__ __forceinline__ bool closes_tile(int64_t n, int64_t tile, int64_t ele
 }
 
 // ---------------------------------------------------------------------------------------------
-// Token counts of every worker row.  A block walks groups of 64 tiles of one row (a wave 16
+// Token counts of every worker row.  A block walks units of 16 tiles of one row (a wave 4
 // consecutive tiles of each), counts into one LDS histogram per wave and adds its totals to the
-// row's counters once: few, long-lived blocks, because all blocks of a row end in the same
-// global counters.
+// row's counters once: long-lived blocks, because all blocks of a row end in the same global
+// counters.
 // ---------------------------------------------------------------------------------------------
-constexpr int kZHistBlocks = 768;                              // target for the whole grid: three per CU
+constexpr int kZHistBlocks = 2048;                             // target for the whole grid: eight per CU
 
 template <int R>
 __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int64_t tiles,
@@ -214,26 +221,28 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     unsigned int *__restrict__ mine = hist[wave];
-    const int64_t groups = (tiles + kZGroup - 1) / kZGroup;
-    for (int64_t group = blockIdx.x; group < groups; group += gridDim.x) {
-        const int64_t first = group * kZGroup + wave * kZWaveTiles;
+    const int64_t units = (tiles + kZBlockTiles - 1) / kZBlockTiles;
+    for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
+        const int64_t first = unit * kZBlockTiles + wave * kZWaveTiles;
+        if (first >= tiles) break;                             // wave-uniform
+        // The wave's steps one after the other, the next step's codes requested a step ahead.
+        Codes16<R> cd, cd_next;
+        int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
+        int since = 0;
 #pragma unroll 1
-        for (int t = 0; t < kZWaveTiles; ++t) {
-            const int64_t tile = first + t;
-            if (tile >= tiles) break;                          // wave-uniform
-            int since = 0;
-#pragma unroll 1
-            for (int step = 0; step < kZSteps; ++step) {
-                const int64_t step_first = tile * kZTile + (int64_t)step * kZStep;
-                const int step_valid = step_elements(a.n, step_first);
-                if (step_valid == 0) break;                    // wave-uniform
-                const int64_t elem = step_first + lane * 16;
-                Codes16<R> cd;
-                const int valid = load_step_codes<R>(crow, a.row_bytes, a.n, elem, cd);
-                const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
-                lane_tokens<R>(cd, valid, run, closes_tile(a.n, tile, elem, valid), z,
-                               [&](int token) { atomicAdd(&mine[token & 255], 1u); });
-            }
+        for (int i = 0; i < kZWaveSteps; ++i) {
+            const int64_t tile = first + (i / kZSteps);
+            const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
+            const int step_valid = step_elements(a.n, step_first);
+            if (step_valid == 0 || tile >= tiles) break;       // wave-uniform
+            cd = cd_next;
+            valid = valid_next;
+            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
+            if ((i % kZSteps) == 0) since = 0;
+            const int64_t elem = step_first + lane * 16;
+            const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
+            lane_tokens<R>(cd, valid, run, closes_tile(a.n, tile, elem, valid), z,
+                           [&](int token) { atomicAdd(&mine[token & 255], 1u); });
         }
     }
     __syncthreads();
@@ -245,8 +254,8 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
 }
 
 // ---------------------------------------------------------------------------------------------
-// Encoder, pass 1: the number of stream bits of every tile.  One block per group of 64 tiles, a
-// wave 16 consecutive tiles.
+// Encoder, pass 1: the number of stream bits of every tile.  One block per 16 tiles, a wave 4
+// consecutive tiles, the next step's codes requested a step ahead.
 // ---------------------------------------------------------------------------------------------
 template <int R>
 __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint8_t *__restrict__ lengths,
@@ -264,34 +273,39 @@ __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
-    const int64_t first = (int64_t)blockIdx.x * kZGroup + wave * kZWaveTiles;
+    const int64_t first = (int64_t)blockIdx.x * kZBlockTiles + wave * kZWaveTiles;
+    if (first >= tiles) return;                                // wave-uniform; no barrier follows
+    Codes16<R> cd, cd_next;
+    int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
+    int since = 0;
+    unsigned int bits = 0;
 #pragma unroll 1
-    for (int t = 0; t < kZWaveTiles; ++t) {
-        const int64_t tile = first + t;
-        if (tile >= tiles) break;                              // wave-uniform
-        int since = 0;
-        unsigned int bits = 0;
-#pragma unroll 1
-        for (int step = 0; step < kZSteps; ++step) {
-            const int64_t step_first = tile * kZTile + (int64_t)step * kZStep;
-            const int step_valid = step_elements(a.n, step_first);
-            if (step_valid == 0) break;                        // wave-uniform
+    for (int i = 0; i < kZWaveSteps; ++i) {
+        const int64_t tile = first + (i / kZSteps);
+        const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
+        const int step_valid = step_elements(a.n, step_first);
+        if (tile < tiles && step_valid > 0) {                  // wave-uniform
+            cd = cd_next;
+            valid = valid_next;
+            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
+            if ((i % kZSteps) == 0) since = 0;
             const int64_t elem = step_first + lane * 16;
-            Codes16<R> cd;
-            const int valid = load_step_codes<R>(crow, a.row_bytes, a.n, elem, cd);
             const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
             lane_tokens<R>(cd, valid, run, closes_tile(a.n, tile, elem, valid), z,
                            [&](int token) { bits += len[token & 255]; });
         }
-        const unsigned int incl = wave_inclusive_scan(bits);   // a tile has fewer than 2^32 bits
-        if (lane == 63) tile_bits[(int64_t)p * tile_stride + tile] = incl;
+        if ((i % kZSteps) == kZSteps - 1 && tile < tiles) {    // the tile's last step: its size
+            const unsigned int incl = wave_inclusive_scan(bits);   // a tile has fewer than 2^32 bits
+            if (lane == 63) tile_bits[(int64_t)p * tile_stride + tile] = incl;
+            bits = 0;
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Encoder, pass 2: one block per row walks the tile sizes and leaves the stream bit at which
 // every group of 64 tiles starts (entry `groups`: the row's total).  It also clears the 32-bit
-// stream word in which every wave of pass 3 starts (every 16th tile) and the one that holds the
+// stream word in which every wave of pass 3 starts (every 4th tile) and the one that holds the
 // end of the row: those are the words two waves may share, and they fill them with atomic ORs.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024) k_zrun_scan(const uint32_t *__restrict__ tile_bits, const int64_t tile_stride,
@@ -337,8 +351,8 @@ __global__ void __launch_bounds__(1024) k_zrun_scan(const uint32_t *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Encoder, pass 3: one block per group of 64 tiles, a wave 16 consecutive tiles, taken in steps
-// of 1024 elements.  Per step a lane walks its tokens twice: once for the sum of their codeword
+// Encoder, pass 3: one block per 16 tiles, a wave 4 consecutive tiles, taken in steps of 1024
+// elements (the next step's codes requested a step ahead).  Per step a lane walks its tokens twice: once for the sum of their codeword
 // lengths (a wave prefix sum then places every lane), once to put the codewords into the wave's
 // LDS buffer, which is aligned with the 32-bit words of the stream.  Whole words leave with
 // plain coalesced stores; a partial last word is carried into the next step; only the first
@@ -386,8 +400,8 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     const uint32_t p = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t group = blockIdx.x;
-    const int64_t first = group * kZGroup + wave * kZWaveTiles;
+    const int64_t first = (int64_t)blockIdx.x * kZBlockTiles + wave * kZWaveTiles;
+    const int64_t group = ((int64_t)blockIdx.x * kZBlockTiles) / kZGroup;
     unsigned int *__restrict__ mine = step_buf[wave];
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     uint32_t *__restrict__ out = streams + (int64_t)p * stream_stride_words;
@@ -395,12 +409,14 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     const int64_t my_tile = group * kZGroup + lane;
     const unsigned int my_bits = my_tile < tiles ? tile_bits[(int64_t)p * tile_stride + my_tile] : 0u;
     const unsigned long long group_start = group_offsets[(int64_t)p * group_stride + group];
+    Codes16<R> cd, cd_next;
+    int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
     fill_zencode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z.zz + 1);
     if (first >= tiles) return;                                // wave-uniform; no block barrier follows
     const unsigned int incl = wave_inclusive_scan(my_bits);
     const unsigned int excl_tile = incl - my_bits;
     const unsigned long long range_start =
-        group_start + (unsigned int)__builtin_amdgcn_readlane((int)excl_tile, wave * kZWaveTiles);
+        group_start + (unsigned int)__builtin_amdgcn_readlane((int)excl_tile, (int)(first - group * kZGroup));
     for (int j = lane; j < kZBufWords; j += 64) mine[j] = 0u;
     wave_lds_sync();
 
@@ -408,17 +424,20 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     unsigned int carry = 0;                                    // partial last word of the step before
     int64_t last_tile = first + kZWaveTiles - 1;
     if (last_tile > tiles - 1) last_tile = tiles - 1;
+    int since = 0;
 #pragma unroll 1
-    for (int64_t tile = first; tile <= last_tile; ++tile) {
-        int since = 0;
-#pragma unroll 1
-        for (int step = 0; step < kZSteps; ++step) {
-            const int64_t step_first = tile * kZTile + (int64_t)step * kZStep;
+    for (int i = 0; i < kZWaveSteps; ++i) {
+        {
+            const int64_t tile = first + (i / kZSteps);
+            const int step = i % kZSteps;
+            const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
             const int step_valid = step_elements(a.n, step_first);
-            if (step_valid == 0) break;                        // wave-uniform
+            if (tile > last_tile || step_valid == 0) break;    // wave-uniform
+            cd = cd_next;
+            valid = valid_next;
+            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
+            if (step == 0) since = 0;
             const int64_t elem = step_first + lane * 16;
-            Codes16<R> cd;
-            const int valid = load_step_codes<R>(crow, a.row_bytes, a.n, elem, cd);
             const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
             const bool close = closes_tile(a.n, tile, elem, valid);
             unsigned int nbits = 0;
@@ -498,19 +517,27 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 // ---------------------------------------------------------------------------------------------
 // Decoder: one lane per tile, a wave per group of 64 tiles, four groups per block.
 // ---------------------------------------------------------------------------------------------
-// `fast` maps the next 10 stream bits to the token whose codeword they begin with (length in
-// the high byte; 0 = longer than 10 bits); longer codewords are found by the canonical
-// first-code / count test on the next 32 stream bits, and one bit at a time beyond that.
+// Decoding a tile is a chain (a token's position is known only once the one before it has been
+// decoded), so the work per token is kept small:
+//  - `fast` maps the next 10 stream bits to the token whose codeword they begin with, together
+//    with what the token stands for: (length << 16) | (zeros << 8) | code, code 255 = no level;
+//    0 = the codeword is longer than 10 bits, found by the canonical first-code / count test
+//    on the next 32 stream bits (one bit at a time beyond that);
+//  - the output is a window of 16 words per lane in LDS that starts out as codes of level 0
+//    (a message is mostly zeros); a token moves the output position past its zeros and XORs
+//    its level's code into the window, which leaves 64 bytes at a time.
 struct ZDecodeTable {
     unsigned long long first_code[64];       // canonical: first codeword of each length
+    unsigned int fast[1 << kZFastBits];
     unsigned int count[64];                  // codewords of each length
+    unsigned int zero_words[8];              // the output's words when every level is 0 (they repeat
+                                             // after R / gcd(R, 32) words)
     unsigned short base[64];                 // index into sorted[] of the first one
-    unsigned short fast[1 << kZFastBits];    // (length << 8) | token
+    unsigned short info[256];                // token -> (zeros << 8) | code
     unsigned char sorted[256];               // tokens in the order (length, token)
-    unsigned char zeros[256];                // zeros a token stands for
-    unsigned char code[256];                 // the code (level + s) that follows them; 255: none
 };
 
+template <int R>
 __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint8_t *__restrict__ lengths,
                                                    const unsigned long long *__restrict__ codewords,
                                                    const ZrunShape &z)
@@ -521,17 +548,23 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
         tab.count[l] = 0;
         tab.first_code[l] = 0ull;
     }
-    for (int i = tid; i < (1 << kZFastBits); i += blockDim.x) tab.fast[i] = 0;
+    for (int i = tid; i < (1 << kZFastBits); i += blockDim.x) tab.fast[i] = 0u;
     for (int c = tid; c < 256; c += blockDim.x) {
         tab.sorted[c] = (unsigned char)z.zz;
         if (c >= z.zz) {                                       // "Z zeros" (entries beyond it are never reached)
-            tab.zeros[c] = (unsigned char)z.Z;
-            tab.code[c] = 255;
+            tab.info[c] = (unsigned short)((z.Z << 8) | 255);
         } else {
             const int rank = c % z.two_s;
-            tab.zeros[c] = (unsigned char)(c / z.two_s);
-            tab.code[c] = (unsigned char)(rank < z.s ? rank : rank + 1);
+            tab.info[c] = (unsigned short)(((c / z.two_s) << 8) | (rank < z.s ? rank : rank + 1));
         }
+    }
+    if (tid < 8) {                                             // bits [32 tid, 32 tid + 32) of the all-zero-level stream
+        unsigned int word = 0;
+        for (int k = (32 * tid) / R; k * R < 32 * tid + 32; ++k) {
+            const int at = k * R - 32 * tid;                   // where field k starts, relative to the word
+            word |= at >= 0 ? (unsigned int)z.s << at : (unsigned int)z.s >> -at;
+        }
+        tab.zero_words[tid] = word;
     }
     __syncthreads();
     for (int c = tid; c < symbols; c += blockDim.x) {
@@ -561,8 +594,8 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
         if (!l || l > kZFastBits) continue;                    // block-uniform
         const unsigned long long cw = codewords[c] & ((1ull << l) - 1ull);
         const unsigned int rev = (unsigned int)(__brevll(cw) >> (64 - l));
-        for (unsigned int hi = tid; hi < (1u << (kZFastBits - l)); hi += blockDim.x)
-            tab.fast[rev | (hi << l)] = (unsigned short)((l << 8) | c);
+        const unsigned int entry = ((unsigned int)l << 16) | tab.info[c];
+        for (unsigned int hi = tid; hi < (1u << (kZFastBits - l)); hi += blockDim.x) tab.fast[rev | (hi << l)] = entry;
     }
     __syncthreads();
 }
@@ -576,11 +609,12 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                                                     const int64_t group_stride, const uint32_t *__restrict__ streams,
                                                     const int64_t stream_words, const int64_t stream_stride_words)
 {
+    constexpr int kPeriod = R == 2 || R == 4 || R == 8 ? 1 : (R == 6 ? 3 : R);   // words after which zero_words repeat
     __shared__ ZDecodeTable tab;
     __shared__ __attribute__((aligned(16))) unsigned int out_ring[256 * kZRingStride];
     const ZrunShape z = zrun_shape(a.s);
     const uint32_t p = blockIdx.y;
-    fill_zdecode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
+    fill_zdecode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t group = (int64_t)blockIdx.x * 4 + wave;
@@ -591,7 +625,8 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     const unsigned long long start = group_offsets[(int64_t)p * group_stride + group] + (incl - my_bits);
     if (tile >= tiles) return;
     const int64_t elem0 = tile * kZTile;
-    int remaining = (int)((a.n - elem0) < kZTile ? (a.n - elem0) : (int64_t)kZTile);
+    const int tile_elems = (int)((a.n - elem0) < kZTile ? (a.n - elem0) : (int64_t)kZTile);
+    int remaining = tile_elems;
     const uint32_t *__restrict__ in = streams + (int64_t)p * stream_stride_words;
     uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     int64_t out_byte = (elem0 >> 3) * R;                       // a multiple of 512*R: 4-byte aligned in the row
@@ -638,13 +673,14 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         have -= skip;
     }
 
-    // Decoded codes collect in a 64-bit accumulator, whole words go to a per-lane LDS ring and
-    // leave 64 bytes at a time.
-    unsigned long long out_acc = 0;
-    unsigned int out_held = 0;
+    // The output window: words [window, window + 16) of the tile's part of the row.
     unsigned int *__restrict__ ring = out_ring + threadIdx.x * kZRingStride;
-    int ring_at = 0;
-    auto flush_ring = [&](int count) {
+    int window = 0;
+    auto fill_window = [&]() {
+#pragma unroll
+        for (int k = 0; k < kZRingWords; ++k) ring[k] = tab.zero_words[kPeriod == 1 ? 0 : (window + k) % kPeriod];
+    };
+    auto store_window = [&](int count) {                       // the window's first `count` words leave
         if (count == kZRingWords && out_byte + 4 * kZRingWords <= a.row_bytes) {
 #pragma unroll
             for (int q = 0; q < kZRingWords / 4; ++q) {
@@ -658,36 +694,27 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         }
         out_byte += 4 * count;
     };
-    auto push_words = [&]() {                                  // move whole words of out_acc to the ring
-        while (out_held >= 32u) {
-            ring[ring_at++] = (unsigned int)out_acc;
-            out_acc >>= 32;
-            out_held -= 32u;
-            if (ring_at == kZRingWords) {
-                flush_ring(kZRingWords);
-                ring_at = 0;
-            }
+    auto advance_to = [&](int word) {                          // make `word` part of the window
+        while (word >= window + kZRingWords) {
+            store_window(kZRingWords);
+            window += kZRingWords;
+            fill_window();
         }
     };
-    // A 64-bit word full of codes of level 0 (c = s in every R-bit field that fits whole).
-    constexpr int kFieldsPerWord = 32 / R;                     // zeros appended per round: they fit 32 bits
-    unsigned int zero_fields = 0;
-#pragma unroll
-    for (int k = 0; k < kFieldsPerWord; ++k) zero_fields |= (unsigned int)a.s << (R * k);
+    fill_window();
 
+    int at = 0;                                                // elements decoded so far
     while (remaining > 0) {
         refill();
-        unsigned int token;
-        const unsigned int hit = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
-        if (hit) {
-            token = hit & 0xFFu;
-            res >>= (hit >> 8);
-            have -= (hit >> 8);
+        unsigned int entry = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
+        if (entry) {
+            res >>= (entry >> 16);
+            have -= (entry >> 16);
         } else {
             // Longer than the table covers.  Up to 32 bits: the next 32 stream bits, first one on
             // top, give the candidate codeword of every length by one shift; the canonical code
             // says which length holds it.
-            token = (unsigned int)z.zz;
+            unsigned int token = (unsigned int)z.zz;
             if (have < 32u) refill();
             const unsigned int top = __brev((unsigned int)res);
             int l = kZFastBits + 1;
@@ -721,30 +748,38 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                     }
                 }
             }
+            entry = tab.info[token];
         }
-        int zeros = tab.zeros[token];
-        const unsigned int code = tab.code[token];
+        int zeros = (int)((entry >> 8) & 0xFFu);
+        const unsigned int code = entry & 0xFFu;
         zeros = zeros < remaining ? zeros : remaining;
+        at += zeros;
         remaining -= zeros;
-        while (zeros > 0) {                                    // up to 32 / R zeros per round
-            const int m = zeros < kFieldsPerWord ? zeros : kFieldsPerWord;
-            const unsigned int fields = (R * m) >= 32 ? zero_fields : (zero_fields & ((1u << (R * m)) - 1u));
-            out_acc |= (unsigned long long)fields << out_held;
-            out_held += (unsigned int)(R * m);
-            zeros -= m;
-            push_words();
-        }
         if (code != 255u && remaining > 0) {
-            out_acc |= (unsigned long long)(code & ((1u << R) - 1u)) << out_held;
-            out_held += R;
+            // The window holds the code of level 0 (s) here: XOR turns it into the level's code.
+            const unsigned int delta = (code ^ (unsigned int)a.s) & ((1u << R) - 1u);
+            const int bit = at * R, word = bit >> 5, sh = bit & 31;
+            advance_to(word);
+            atomicXor(&ring[word - window], delta << sh);
+            if ((32 % R) != 0 && sh + R > 32) {                // the field straddles two words
+                advance_to(word + 1);
+                atomicXor(&ring[word + 1 - window], delta >> (32 - sh));
+            }
+            ++at;
             --remaining;
-            push_words();
         }
     }
-    // What is left of a ragged last tile: whole words, then fewer than 32 bits (pad bits zero).
-    flush_ring(ring_at);
-    if (out_held > 0u && out_byte < a.row_bytes)
-        store_code_bytes(crow + out_byte, out_acc, (int)((out_held + 7u) >> 3), a.row_bytes - out_byte);
+    // The rest of the tile: whole windows, then the last words, pad bits of a ragged tile zero.
+    const int tile_bits_out = tile_elems * R;
+    const int tile_words = (tile_bits_out + 31) >> 5;
+    while (window + kZRingWords < tile_words) {
+        store_window(kZRingWords);
+        window += kZRingWords;
+        fill_window();
+    }
+    const int left = tile_words - window;                      // 1..16: the window that holds the tile's last word
+    if (tile_bits_out & 31) ring[left - 1] &= (1u << (tile_bits_out & 31)) - 1u;
+    store_window(left);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -760,7 +795,7 @@ hipError_t launch_zrun_histogram(const Args &a, unsigned long long *counts, int6
     const int symbols = 2 * a.s * (127 / a.s) + 1;
     hipLaunchKernelGGL(k_zrun_zero_counts, dim3((unsigned)a.workers), dim3(256), 0, stream, counts, count_stride, symbols);
     const int64_t tiles = (a.n + kZTile - 1) / kZTile;
-    unsigned per_row = cdiv(tiles, kZGroup);
+    unsigned per_row = cdiv(tiles, kZBlockTiles);
     const unsigned want = cdiv(kZHistBlocks, a.workers);
     if (per_row > want) per_row = want;
     const dim3 grid(per_row, (unsigned)a.workers);
@@ -776,7 +811,7 @@ hipError_t launch_zrun_encode(const Args &a, const uint8_t *lengths, const unsig
                               int64_t group_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kZTile - 1) / kZTile;
-    const dim3 grid(cdiv(tiles, kZGroup), (unsigned)a.workers);
+    const dim3 grid(cdiv(tiles, kZBlockTiles), (unsigned)a.workers);
 #define CALL(RR)                                                                                                  \
     hipLaunchKernelGGL((k_zrun_tile_bits<RR>), grid, dim3(256), 0, stream, a, lengths, table_stride, tiles, tile_bits, \
                        tile_stride)
