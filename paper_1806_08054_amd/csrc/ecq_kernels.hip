@@ -799,9 +799,8 @@ constexpr int kAggStageStride = 20;    // floats between lanes in the transposit
 // LDS so the wave stores (and, for the model update, loads) whole contiguous kilobytes as
 // float4 per lane.  The ragged last run of a row goes through agg_run_guarded.
 // bucket_shift >= 0 when the bucket is a power of two.
-template <int R, int NORMS, int U>
-__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift, const float inv_p,
-                                                           const int stream_codes)
+template <int R, int NORMS, int U, bool STREAM>
+__global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const int bucket_shift, const float inv_p)
 {
     // One LDS object with the pair table first: its byte offsets are then LDS addresses, and a
     // lookup address is a single AND-OR of the shifted codes with the lane's copy offset.
@@ -856,7 +855,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         auto request = [&](Codes16<R> (&c)[U], float (&nl)[U], float (&nh)[U]) {
     #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (stream_codes) c[u].template load<true>(cptr + u * a.code_stride); else c[u].template load<false>(cptr + u * a.code_stride);
+                c[u].template load<STREAM>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, nl[u], nh[u]);
             }
             cptr += U * a.code_stride;
@@ -878,7 +877,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (int p = batches * U; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            if (stream_codes) one.template load<true>(cptr); else one.template load<false>(cptr);
+            one.template load<STREAM>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
@@ -894,7 +893,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
             float lo[V], hi[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
-                if (stream_codes) cd[u].template load<true>(cptr + u * a.code_stride); else cd[u].template load<false>(cptr + u * a.code_stride);
+                cd[u].template load<STREAM>(cptr + u * a.code_stride);
                 norms_of(srow + u * a.scale_stride, lo[u], hi[u]);
             }
 #pragma unroll
@@ -906,7 +905,7 @@ __global__ void __launch_bounds__(256) k_dequant_aggregate(const Args a, const i
         for (; p < a.workers; ++p) {
             Codes16<R> one;
             float one_lo, one_hi;
-            if (stream_codes) one.template load<true>(cptr); else one.template load<false>(cptr);
+            one.template load<STREAM>(cptr);
             norms_of(srow, one_lo, one_hi);
             agg_add16<R>(table, pair, lane_off, one, one_lo, NORMS == 2 ? one_hi : one_lo, acc);
             cptr += a.code_stride;
@@ -1293,19 +1292,23 @@ hipError_t launch_dequant_aggregate(const Args &a, hipStream_t stream)
     // Messages of up to 96 MB in all are most likely still in the 256 MB last-level cache, where
     // the encoding pass left them; larger ones are streamed past it.
     const int stream_codes = (int64_t)a.workers * a.row_bytes > ((int64_t)96 << 20);
-#define LAUNCH(RR, NN, UU) \
-    hipLaunchKernelGGL((k_dequant_aggregate<RR, NN, UU>), grid, dim3(256), 0, stream, a, bucket_shift, inv_p, \
-                       stream_codes)
-#define CALL(RR)                                      \
-    if (norms == 0) {                                 \
-        if (RR == 2 && wide) LAUNCH(RR, 0, (RR == 2 ? 8 : 4)); \
-        else LAUNCH(RR, 0, 4);                        \
-    } else if (norms == 1) {                          \
-        if (RR == 2 && wide) LAUNCH(RR, 1, (RR == 2 ? 8 : 4)); \
-        else LAUNCH(RR, 1, 4);                        \
-    } else {                                          \
-        if (RR == 2 && wide) LAUNCH(RR, 2, (RR == 2 ? 8 : 4)); \
-        else LAUNCH(RR, 2, 4);                        \
+#define LAUNCH(RR, NN, UU)                                                                                      \
+    if (stream_codes)                                                                                           \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, NN, UU, true>), grid, dim3(256), 0, stream, a, bucket_shift,  \
+                           inv_p);                                                                              \
+    else                                                                                                        \
+        hipLaunchKernelGGL((k_dequant_aggregate<RR, NN, UU, false>), grid, dim3(256), 0, stream, a, bucket_shift, \
+                           inv_p)
+#define CALL(RR)                                                 \
+    if (norms == 0) {                                            \
+        if (RR == 2 && wide) { LAUNCH(RR, 0, (RR == 2 ? 8 : 4)); } \
+        else { LAUNCH(RR, 0, 4); }                               \
+    } else if (norms == 1) {                                     \
+        if (RR == 2 && wide) { LAUNCH(RR, 1, (RR == 2 ? 8 : 4)); } \
+        else { LAUNCH(RR, 1, 4); }                               \
+    } else {                                                     \
+        if (RR == 2 && wide) { LAUNCH(RR, 2, (RR == 2 ? 8 : 4)); } \
+        else { LAUNCH(RR, 2, 4); }                               \
     }
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL

@@ -33,7 +33,7 @@ constexpr int kZSteps = kZTile / kZStep;
 constexpr int kZWaveTiles = kZBlockTiles / 4;                  // consecutive tiles per wave
 constexpr int kZWaveSteps = kZWaveTiles * kZSteps;
 constexpr int kZMaxLen = 63;                                   // longest codeword handled
-constexpr int kZFastBits = 10;                                 // decode: direct table on 10 stream bits
+constexpr int kZFastBits = 12;                                 // decode: direct table on 12 stream bits
 constexpr int kZRingWords = 16;                                // decode: words a lane collects before storing
 constexpr int kZRingStride = 20;                               // ... and the distance between lanes' rings
 // Words of LDS a wave needs for one step: 1024 elements send at most 1025 tokens (every element
@@ -519,10 +519,14 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 // ---------------------------------------------------------------------------------------------
 // Decoding a tile is a chain (a token's position is known only once the one before it has been
 // decoded), so the work per token is kept small:
-//  - `fast` maps the next 10 stream bits to the token whose codeword they begin with, together
+//  - `fast` maps the next 12 stream bits to the token whose codeword they begin with, together
 //    with what the token stands for: (length << 16) | (zeros << 8) | code, code 255 = no level;
-//    0 = the codeword is longer than 10 bits, found by the canonical first-code / count test
-//    on the next 32 stream bits (one bit at a time beyond that);
+//    0 = the codeword is longer than 12 bits.  In a canonical code the codewords, left-aligned,
+//    grow with their length, so the length of a longer codeword is 13 plus the number of
+//    lengths l >= 13 whose last left-aligned codeword lies below the next 32 stream bits: a
+//    count over 20 bounds that every lane keeps in registers (in a wave of 64 tiles some lane
+//    meets a rare, long codeword in most rounds, so this route has to be short); beyond 32 bits
+//    one bit at a time;
 //  - the output is a window of 16 words per lane in LDS that starts out as codes of level 0
 //    (a message is mostly zeros); a token moves the output position past its zeros and XORs
 //    its level's code into the window, which leaves 64 bytes at a time.
@@ -532,8 +536,11 @@ struct ZDecodeTable {
     unsigned int count[64];                  // codewords of each length
     unsigned int zero_words[8];              // the output's words when every level is 0 (they repeat
                                              // after R / gcd(R, 32) words)
+    unsigned int last[33];                   // last left-aligned 32-bit codeword of lengths <= l (wraps to ~0 when none)
+    unsigned int delta[33];                  // index into sorted[] minus the codeword, per length
     unsigned short base[64];                 // index into sorted[] of the first one
     unsigned short info[256];                // token -> (zeros << 8) | code
+    unsigned short sorted_info[256];         // info of the tokens in the order (length, token)
     unsigned char sorted[256];               // tokens in the order (length, token)
 };
 
@@ -587,6 +594,17 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
         if (rank == 0) tab.first_code[l] = cw;
         const int slot = tab.base[l] + rank;
         if (slot < 256) tab.sorted[slot] = (unsigned char)c;
+    }
+    for (int c = tid; c < 256; c += blockDim.x) tab.sorted_info[c] = tab.info[z.zz];
+    __syncthreads();
+    for (int c = tid; c < 256; c += blockDim.x) tab.sorted_info[c] = tab.info[tab.sorted[c]];
+    for (int l = tid; l <= 32; l += blockDim.x) {
+        // (first codeword of the next occupied length, left-aligned) - 1 = the last codeword of lengths <= l
+        unsigned long long bound = 0;                          // left-aligned end of the codewords of lengths <= l
+        for (int j = 1; j <= l; ++j)
+            if (tab.count[j]) bound = (tab.first_code[j] + tab.count[j]) << (32 - j);
+        tab.last[l] = (unsigned int)(bound - 1ull);
+        tab.delta[l] = (unsigned int)tab.base[l] - (unsigned int)tab.first_code[l];
     }
     // Every window whose low bits are a codeword of at most kZFastBits bits.
     for (int c = 0; c < symbols; ++c) {
@@ -702,6 +720,11 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         }
     };
     fill_window();
+    // The bounds of the lengths 13..31 and of length 32, in registers.
+    unsigned int last[32 - (kZFastBits + 1)];
+#pragma unroll
+    for (int j = 0; j < 32 - (kZFastBits + 1); ++j) last[j] = tab.last[kZFastBits + 1 + j];
+    const unsigned int last32 = tab.last[32];
 
     int at = 0;                                                // elements decoded so far
     while (remaining > 0) {
@@ -711,28 +734,21 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
             res >>= (entry >> 16);
             have -= (entry >> 16);
         } else {
-            // Longer than the table covers.  Up to 32 bits: the next 32 stream bits, first one on
-            // top, give the candidate codeword of every length by one shift; the canonical code
-            // says which length holds it.
-            unsigned int token = (unsigned int)z.zz;
+            // Longer than the table covers: its length from the bounds, then its place among the
+            // codewords of that length.
             if (have < 32u) refill();
             const unsigned int top = __brev((unsigned int)res);
             int l = kZFastBits + 1;
-            bool found = false;
-            for (; l <= 32; ++l) {
-                const unsigned long long cand = top >> (32 - l);
-                const unsigned long long idx = cand - tab.first_code[l];
-                if (tab.count[l] && cand >= tab.first_code[l] && idx < tab.count[l]) {
-                    token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
-                    res >>= l;
-                    have -= (unsigned int)l;
-                    found = true;
-                    break;
-                }
-            }
-            if (!found) {
-                // Beyond 32 bits: one bit at a time.  (A stream that is not of this code ends up
+#pragma unroll
+            for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
+            if (top <= last32) {
+                entry = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
+                res >>= l;
+                have -= (unsigned int)l;
+            } else {
+                // Beyond 32 bits: one bit at a time.  (A stream that is not of this code may end up
                 // here as well and comes out as "Z zeros" tokens.)
+                unsigned int token = (unsigned int)z.zz;
                 unsigned long long word = top;
                 res >>= 32;
                 have -= 32u;
@@ -747,8 +763,8 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                         break;
                     }
                 }
+                entry = tab.info[token];
             }
-            entry = tab.info[token];
         }
         int zeros = (int)((entry >> 8) & 0xFFu);
         const unsigned int code = entry & 0xFFu;
