@@ -29,7 +29,6 @@ constexpr int kRunTiles = 16;                                  // encoder: conse
 constexpr int kRunElems = kRunTiles * ECQ_HUFFMAN_TILE;
 constexpr int kDecodeThreads = 256;                            // decode: tiles (lanes) per block
 constexpr int kRingWords = 16;                                 // decode: words a lane collects before storing
-constexpr int kRingStride = 20;                                // ... and the distance between lanes' rings
 
 // The encoder's waves take a run in steps of 64 lanes x 16*Q elements: Q = 4 (four tiles per
 // step) while codes have at most 4 bits, fewer for wider codes, whose codewords can be longer,
@@ -835,7 +834,9 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
                                                        const int64_t stream_words, const int64_t stream_stride_words)
 {
     __shared__ DecodeTable tab;
-    __shared__ __attribute__((aligned(16))) unsigned int out_ring[kDecodeThreads * kRingStride];
+    // Word k of lane t's ring at [k][t]: whatever slots the lanes of a wave are at, they write to
+    // 64 different banks.
+    __shared__ unsigned int out_ring[kRingWords * kDecodeThreads];
     const uint32_t p = blockIdx.y;
     fill_decode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride,
                          2 * a.s + 1);
@@ -903,19 +904,16 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
     // stores inside the chain would make every later wait for a stream word also wait for them.
     unsigned long long out_acc = 0;                            // decoded r-bit codes not yet in the ring
     unsigned int out_held = 0;
-    unsigned int *__restrict__ ring = out_ring + threadIdx.x * kRingStride;
+    unsigned int *__restrict__ ring = out_ring + threadIdx.x;
     int ring_at = 0;
     auto flush_ring = [&](int count) {
         if (count == kRingWords && out_byte + 4 * kRingWords <= a.row_bytes) {
 #pragma unroll
-            for (int q = 0; q < kRingWords / 4; ++q) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(&ring[4 * q]);
-                uint32_t *dst = reinterpret_cast<uint32_t *>(crow + out_byte) + 4 * q;
-                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-            }
+            for (int k = 0; k < kRingWords; ++k)
+                reinterpret_cast<uint32_t *>(crow + out_byte)[k] = ring[k * kDecodeThreads];
         } else {
             for (int k = 0; k < count; ++k)
-                store_code_bytes(crow + out_byte + 4 * k, ring[k], 4, a.row_bytes - (out_byte + 4 * k));
+                store_code_bytes(crow + out_byte + 4 * k, ring[k * kDecodeThreads], 4, a.row_bytes - (out_byte + 4 * k));
         }
         out_byte += 4 * count;
     };
@@ -984,7 +982,7 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
         // The low word goes to the ring's next slot whether it is complete or not; the slot is
         // only given up once it is.
         const bool full = out_held >= 32u;
-        ring[ring_at] = (unsigned int)out_acc;
+        ring[ring_at * kDecodeThreads] = (unsigned int)out_acc;
         out_acc = full ? out_acc >> 32 : out_acc;
         out_held -= full ? 32u : 0u;
         ring_at += full ? 1 : 0;

@@ -734,6 +734,33 @@ __device__ __forceinline__ void fill_byte_table(f2 *tab, int s)
     __syncthreads();
 }
 
+// Byte 1 of `at` <- the low (HIGH = 0) or high (HIGH = 1) nibble of byte k of x; the other bytes
+// of `at` stay.  A partial-register write must not be read by the very next vector instruction
+// on this chip, and the compiler does not see inside the statement: the idle slot after it
+// keeps that distance whatever is scheduled next.
+template <int HIGH>
+__device__ __forceinline__ void pair_address(uint32_t &at, uint32_t x, int k)
+{
+#define ECQ_PAIR_ADDRESS(K)                                                                                      \
+    if (HIGH)                                                                                                    \
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "            \
+            "src1_sel:BYTE_" #K "\n\ts_nop 0"                                                                    \
+            : "+v"(at)                                                                                           \
+            : "v"(4u), "v"(x));                                                                                  \
+    else                                                                                                         \
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" #K " "          \
+            "src1_sel:DWORD\n\ts_nop 0"                                                                          \
+            : "+v"(at)                                                                                           \
+            : "v"(x), "v"(0x0Fu))
+    switch (k) {
+    case 0: ECQ_PAIR_ADDRESS(0); break;
+    case 1: ECQ_PAIR_ADDRESS(1); break;
+    case 2: ECQ_PAIR_ADDRESS(2); break;
+    default: ECQ_PAIR_ADDRESS(3); break;
+    }
+#undef ECQ_PAIR_ADDRESS
+}
+
 // acc += one worker's dequantised values for a lane's 16 elements (Eq. 8).
 //   r = 2: levels from the pair table; acc = fma(norm, level, acc) equals acc + norm * level
 //          because that product is exact.
@@ -747,16 +774,22 @@ __device__ __forceinline__ void agg_add16(const float *sxi, const f2 *pair, uint
     // size is an odd multiple of 8; else the same value twice).
     if constexpr (R == 2) {
         const uint32_t x = cd.w[0];
+        // Byte offset nib*256 + (lane & 31)*8 of a lookup: the lane's copy offset sits in byte 0,
+        // the nibble goes into byte 1 with one sub-dword-addressed instruction that takes byte K
+        // of the codes, masks or shifts it, and writes only that byte of the address register.
+        // Two address registers alternate between the low and the high nibbles.
+        uint32_t lo_at = lane_off, hi_at = lane_off;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float norm = j < 4 ? norm_lo : norm_hi;
-            // Byte offset nib*256 + (lane & 31)*8: the nibble moved to bits 8..11, OR-ed with the
-            // lane's copy offset (bits 3..7).
-            const uint32_t nib8 = 4 * j >= 8 ? (x >> (4 * j - 8)) : (x << (8 - 4 * j));
-            const uint32_t off = (nib8 & 0xF00u) | lane_off;
-            const f2 lv = *reinterpret_cast<const f2 *>(reinterpret_cast<const char *>(pair) + off);
-            acc[2 * j] = __builtin_fmaf(norm, lv.x, acc[2 * j]);
-            acc[2 * j + 1] = __builtin_fmaf(norm, lv.y, acc[2 * j + 1]);
+        for (int k = 0; k < 4; ++k) {
+            const float norm = k < 2 ? norm_lo : norm_hi;
+            pair_address<0>(lo_at, x, k);
+            const f2 a = *reinterpret_cast<const f2 *>(reinterpret_cast<const char *>(pair) + lo_at);
+            acc[4 * k] = __builtin_fmaf(norm, a.x, acc[4 * k]);
+            acc[4 * k + 1] = __builtin_fmaf(norm, a.y, acc[4 * k + 1]);
+            pair_address<1>(hi_at, x, k);
+            const f2 b = *reinterpret_cast<const f2 *>(reinterpret_cast<const char *>(pair) + hi_at);
+            acc[4 * k + 2] = __builtin_fmaf(norm, b.x, acc[4 * k + 2]);
+            acc[4 * k + 3] = __builtin_fmaf(norm, b.y, acc[4 * k + 3]);
         }
     } else if constexpr (R == 4) {
         // `pair` is the byte table here: g~ = norm * sxi[c] for the byte's two codes, then acc + g~.

@@ -34,8 +34,7 @@ constexpr int kZWaveTiles = kZBlockTiles / 4;                  // consecutive ti
 constexpr int kZWaveSteps = kZWaveTiles * kZSteps;
 constexpr int kZMaxLen = 63;                                   // longest codeword handled
 constexpr int kZFastBits = 12;                                 // decode: direct table on 12 stream bits
-constexpr int kZRingWords = 16;                                // decode: words a lane collects before storing
-constexpr int kZRingStride = 20;                               // ... and the distance between lanes' rings
+constexpr int kZRingWords = 16;                                // decode: words of a lane's output window
 // Words of LDS a wave needs for one step: 1024 elements send at most 1025 tokens (every element
 // at most one, plus the tile's closing token) of at most 63 bits, plus the up-to-31-bit shift
 // that aligns the buffer with the stream's words.
@@ -521,7 +520,10 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 // decoded), so the work per token is kept small:
 //  - `fast` maps the next 12 stream bits to the token whose codeword they begin with, together
 //    with what the token stands for: (length << 16) | (zeros << 8) | code, code 255 = no level;
-//    0 = the codeword is longer than 12 bits.  In a canonical code the codewords, left-aligned,
+//    0 = the codeword is longer than 12 bits.  (16-bit entries with a second lookup of what the
+//    token stands for free LDS for two more blocks per compute unit, but the second lookup
+//    lengthens every token's chain: 6-8 % slower at 8 and 16 workers, 8 % faster at 32.)  In a
+//    canonical code the codewords, left-aligned,
 //    grow with their length, so the length of a longer codeword is 13 plus the number of
 //    lengths l >= 13 whose last left-aligned codeword lies below the next 32 stream bits: a
 //    count over 20 bounds that every lane keeps in registers (in a wave of 64 tiles some lane
@@ -529,7 +531,10 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 //    one bit at a time;
 //  - the output is a window of 16 words per lane in LDS that starts out as codes of level 0
 //    (a message is mostly zeros); a token moves the output position past its zeros and XORs
-//    its level's code into the window, which leaves 64 bytes at a time.
+//    its level's code into the window.  The lanes of a wave go through their tiles window by
+//    window together, so a window leaves with one store sequence for all 64 tiles (lanes that
+//    moved theirs on their own made the wave run that sequence for a few lanes at a time,
+//    nearly once per token); a token whose level falls beyond the window is held for the next.
 struct ZDecodeTable {
     unsigned long long first_code[64];       // canonical: first codeword of each length
     unsigned int fast[1 << kZFastBits];
@@ -629,7 +634,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
 {
     constexpr int kPeriod = R == 2 || R == 4 || R == 8 ? 1 : (R == 6 ? 3 : R);   // words after which zero_words repeat
     __shared__ ZDecodeTable tab;
-    __shared__ __attribute__((aligned(16))) unsigned int out_ring[256 * kZRingStride];
+    __shared__ unsigned int out_ring[kZRingWords * 256];
     const ZrunShape z = zrun_shape(a.s);
     const uint32_t p = blockIdx.y;
     fill_zdecode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
@@ -691,111 +696,136 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         have -= skip;
     }
 
-    // The output window: words [window, window + 16) of the tile's part of the row.
-    unsigned int *__restrict__ ring = out_ring + threadIdx.x * kZRingStride;
-    int window = 0;
-    auto fill_window = [&]() {
+    // The output window: words [w0, w0 + kZRingWords) of the tile's part of the row, the same w0
+    // for every lane of the wave.  Word k of lane t at [k][t]: whatever words the lanes of a wave
+    // touch, they lie in 64 different banks.
+    unsigned int *__restrict__ ring = out_ring + threadIdx.x;
+    auto fill_window = [&](int w0) {
 #pragma unroll
-        for (int k = 0; k < kZRingWords; ++k) ring[k] = tab.zero_words[kPeriod == 1 ? 0 : (window + k) % kPeriod];
+        for (int k = 0; k < kZRingWords; ++k)
+            ring[k * 256] = tab.zero_words[kPeriod == 1 ? 0 : (w0 + k) % kPeriod];
     };
-    auto store_window = [&](int count) {                       // the window's first `count` words leave
-        if (count == kZRingWords && out_byte + 4 * kZRingWords <= a.row_bytes) {
-#pragma unroll
-            for (int q = 0; q < kZRingWords / 4; ++q) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(&ring[4 * q]);
-                uint32_t *dst = reinterpret_cast<uint32_t *>(crow + out_byte) + 4 * q;
-                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-            }
-        } else {
-            for (int k = 0; k < count; ++k)
-                store_code_bytes(crow + out_byte + 4 * k, ring[k], 4, a.row_bytes - (out_byte + 4 * k));
-        }
-        out_byte += 4 * count;
-    };
-    auto advance_to = [&](int word) {                          // make `word` part of the window
-        while (word >= window + kZRingWords) {
-            store_window(kZRingWords);
-            window += kZRingWords;
-            fill_window();
-        }
-    };
-    fill_window();
     // The bounds of the lengths 13..31 and of length 32, in registers.
     unsigned int last[32 - (kZFastBits + 1)];
 #pragma unroll
     for (int j = 0; j < 32 - (kZFastBits + 1); ++j) last[j] = tab.last[kZFastBits + 1 + j];
     const unsigned int last32 = tab.last[32];
 
-    int at = 0;                                                // elements decoded so far
-    while (remaining > 0) {
-        refill();
-        unsigned int entry = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
-        if (entry) {
-            res >>= (entry >> 16);
-            have -= (entry >> 16);
-        } else {
-            // Longer than the table covers: its length from the bounds, then its place among the
-            // codewords of that length.
-            if (have < 32u) refill();
-            const unsigned int top = __brev((unsigned int)res);
-            int l = kZFastBits + 1;
-#pragma unroll
-            for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
-            if (top <= last32) {
-                entry = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
-                res >>= l;
-                have -= (unsigned int)l;
-            } else {
-                // Beyond 32 bits: one bit at a time.  (A stream that is not of this code may end up
-                // here as well and comes out as "Z zeros" tokens.)
-                unsigned int token = (unsigned int)z.zz;
-                unsigned long long word = top;
-                res >>= 32;
-                have -= 32u;
-                for (l = 33; l <= kZMaxLen; ++l) {
-                    if (have == 0u) refill();
-                    word = (word << 1) | (res & 1ull);
-                    res >>= 1;
-                    --have;
-                    const unsigned long long idx = word - tab.first_code[l];
-                    if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
-                        token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
-                        break;
-                    }
-                }
-                entry = tab.info[token];
-            }
-        }
-        int zeros = (int)((entry >> 8) & 0xFFu);
-        const unsigned int code = entry & 0xFFu;
-        zeros = zeros < remaining ? zeros : remaining;
-        at += zeros;
-        remaining -= zeros;
-        if (code != 255u && remaining > 0) {
-            // The window holds the code of level 0 (s) here: XOR turns it into the level's code.
-            const unsigned int delta = (code ^ (unsigned int)a.s) & ((1u << R) - 1u);
-            const int bit = at * R, word = bit >> 5, sh = bit & 31;
-            advance_to(word);
-            atomicXor(&ring[word - window], delta << sh);
-            if ((32 % R) != 0 && sh + R > 32) {                // the field straddles two words
-                advance_to(word + 1);
-                atomicXor(&ring[word + 1 - window], delta >> (32 - sh));
-            }
-            ++at;
-            --remaining;
-        }
-    }
-    // The rest of the tile: whole windows, then the last words, pad bits of a ragged tile zero.
     const int tile_bits_out = tile_elems * R;
     const int tile_words = (tile_bits_out + 31) >> 5;
-    while (window + kZRingWords < tile_words) {
-        store_window(kZRingWords);
-        window += kZRingWords;
-        fill_window();
+    const bool rows_on_16 = (reinterpret_cast<uintptr_t>(crow) & 15u) == 0u;   // block-uniform
+    int at = 0;                                                // elements decoded so far
+    // What a token decoded in one window leaves for a later one: the XOR of its level's code.
+    int held_word = -1, held_word2 = -1;
+    unsigned int held_bits = 0u, held_bits2 = 0u;
+    fill_window(0);
+#pragma unroll 1
+    for (int w0 = 0; w0 < kZTile * R / 32; w0 += kZRingWords) {
+        const int w_end = w0 + kZRingWords;
+        if (held_word >= 0 && held_word < w_end) {
+            atomicXor(&ring[(held_word - w0) * 256], held_bits);
+            held_word = -1;
+        }
+        if ((32 % R) != 0 && held_word2 >= 0 && held_word2 < w_end) {
+            atomicXor(&ring[(held_word2 - w0) * 256], held_bits2);
+            held_word2 = -1;
+        }
+        // Tokens while the lane's next element lies in this window.
+        while (remaining > 0 && held_word < 0 && ((at * R) >> 5) < w_end) {
+            refill();
+            unsigned int entry = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
+            if (entry) {
+                res >>= (entry >> 16);
+                have -= (entry >> 16);
+            } else {
+                // Longer than the table covers: its length from the bounds, then its place among the
+                // codewords of that length.
+                if (have < 32u) refill();
+                const unsigned int top = __brev((unsigned int)res);
+                int l = kZFastBits + 1;
+#pragma unroll
+                for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
+                if (top <= last32) {
+                    entry = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
+                    res >>= l;
+                    have -= (unsigned int)l;
+                } else {
+                    // Beyond 32 bits: one bit at a time.  (A stream that is not of this code may end up
+                    // here as well and comes out as "Z zeros" tokens.)
+                    unsigned int token = (unsigned int)z.zz;
+                    unsigned long long word = top;
+                    res >>= 32;
+                    have -= 32u;
+                    for (l = 33; l <= kZMaxLen; ++l) {
+                        if (have == 0u) refill();
+                        word = (word << 1) | (res & 1ull);
+                        res >>= 1;
+                        --have;
+                        const unsigned long long idx = word - tab.first_code[l];
+                        if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
+                            token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
+                            break;
+                        }
+                    }
+                    entry = tab.info[token];
+                }
+            }
+            int zeros = (int)((entry >> 8) & 0xFFu);
+            const unsigned int code = entry & 0xFFu;
+            zeros = zeros < remaining ? zeros : remaining;
+            at += zeros;
+            remaining -= zeros;
+            if (code != 255u && remaining > 0) {
+                // The window holds the code of level 0 (s) here: XOR turns it into the level's code.
+                const unsigned int delta = (code ^ (unsigned int)a.s) & ((1u << R) - 1u);
+                const int bit = at * R, word = bit >> 5, sh = bit & 31;
+                if (word < w_end) {
+                    atomicXor(&ring[(word - w0) * 256], delta << sh);
+                } else {
+                    held_word = word;
+                    held_bits = delta << sh;
+                }
+                if ((32 % R) != 0 && sh + R > 32) {            // the field straddles two words
+                    if (word + 1 < w_end) {
+                        atomicXor(&ring[(word + 1 - w0) * 256], delta >> (32 - sh));
+                    } else {
+                        held_word2 = word + 1;
+                        held_bits2 = delta >> (32 - sh);
+                    }
+                }
+                ++at;
+                --remaining;
+            }
+        }
+        // The window leaves: whole, or the last words of a ragged tile with its pad bits zero.
+        const int count = tile_words - w0 < kZRingWords ? tile_words - w0 : kZRingWords;
+        if (count > 0) {
+            if (w0 + count == tile_words && (tile_bits_out & 31))
+                ring[(count - 1) * 256] &= (1u << (tile_bits_out & 31)) - 1u;
+            if (count == kZRingWords && out_byte + 4 * kZRingWords <= a.row_bytes) {
+                if (rows_on_16) {
+#pragma unroll
+                    for (int q = 0; q < kZRingWords / 4; ++q) {
+                        uint4 v;
+                        v.x = ring[(4 * q + 0) * 256];
+                        v.y = ring[(4 * q + 1) * 256];
+                        v.z = ring[(4 * q + 2) * 256];
+                        v.w = ring[(4 * q + 3) * 256];
+                        reinterpret_cast<uint4 *>(crow + out_byte)[q] = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < kZRingWords; ++k)
+                        reinterpret_cast<uint32_t *>(crow + out_byte)[k] = ring[k * 256];
+                }
+            } else {
+                for (int k = 0; k < count; ++k)
+                    store_code_bytes(crow + out_byte + 4 * k, ring[k * 256], 4, a.row_bytes - (out_byte + 4 * k));
+            }
+            out_byte += 4 * count;
+        }
+        fill_window(w_end);
     }
-    const int left = tile_words - window;                      // 1..16: the window that holds the tile's last word
-    if (tile_bits_out & 31) ring[left - 1] &= (1u << (tile_bits_out & 31)) - 1u;
-    store_window(left);
 }
 
 // ---------------------------------------------------------------------------------------------
