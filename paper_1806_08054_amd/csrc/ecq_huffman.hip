@@ -57,6 +57,7 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     __shared__ unsigned long long weight[512];
     __shared__ unsigned long long first_code[64];
     __shared__ unsigned long long leaf_key[256];               // occupied levels in the order (weight, number)
+    __shared__ unsigned long long node_key[256];               // every level's key, ~0 when it does not occur
     __shared__ unsigned int len_count[64];
     __shared__ short parent[512];
     __shared__ unsigned char len_of[256];
@@ -73,15 +74,31 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     // A node's place in the order (weight, number) as one integer: weights stay below 2^35 (a
     // row sums to at most 2^34), numbers below 2^9.
     auto key_of = [&](int node) -> unsigned long long { return (weight[node] << 9) | (unsigned long long)node; };
-    // Sort the occupied levels by counting, for every one, the occupied levels before it.
+    // Sort the occupied levels by counting, for every one, the occupied levels before it: a lane
+    // takes up to four levels at once, so every key read from LDS serves four comparisons, and the
+    // reads of several steps are in flight together (one wave: nothing else hides their latency).
+    for (int i = lane; i < 256; i += 64) node_key[i] = (i < bins && weight[i] != 0ull) ? key_of(i) : ~0ull;
+    __syncthreads();
+    const int bins_up = (bins + 7) & ~7;                       // the loops over all levels go in steps of 8 (<= 256)
     int alive = 0;
-    for (int i = lane; i < bins; i += 64) {
-        if (weight[i] == 0ull) continue;
-        ++alive;
-        const unsigned long long mine = key_of(i);
-        int rank = 0;
-        for (int j = 0; j < bins; ++j) rank += (weight[j] != 0ull && key_of(j) < mine) ? 1 : 0;
-        leaf_key[rank] = mine;
+    {
+        unsigned long long mine[4];
+        int rank[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            mine[q] = node_key[lane + 64 * q];
+            rank[q] = 0;
+            alive += mine[q] != ~0ull ? 1 : 0;
+        }
+#pragma unroll 8
+        for (int j = 0; j < bins_up; ++j) {
+            const unsigned long long other = node_key[j];      // an unoccupied level: the largest key, before nothing
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rank[q] += other < mine[q] ? 1 : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (mine[q] != ~0ull) leaf_key[rank[q]] = mine[q];
     }
     for (int d = 1; d < 64; d <<= 1) alive += __shfl_xor(alive, d, 64);
     const bool single = alive == 1;
@@ -92,25 +109,41 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     // merged nodes come into being in that very order (their weights never decrease, their
     // numbers grow), so the first of all live nodes is always the first leaf not yet taken or
     // the first merged node not yet taken: one lane walks the two queues.
+    // The walk is a chain of dependent steps, so the first two keys of each queue travel in
+    // registers and the entries behind them are requested from LDS two picks before they can be
+    // needed.  A key holds the node's weight: nothing else is read back.
     if (lane == 0) {
+        const unsigned long long none = ~0ull;
         int next_leaf = 0, next_made = 0, made = 0;
+        unsigned long long l0 = alive > 0 ? leaf_key[0] : none, l1 = alive > 1 ? leaf_key[1] : none;
+        unsigned long long m0 = none, m1 = none;
         for (int m = 0; m + 1 < alive; ++m) {
-            int pick[2];
+            unsigned long long pick[2];
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
-                const unsigned long long lk = next_leaf < alive ? leaf_key[next_leaf] : ~0ull;
-                const unsigned long long mk = next_made < made ? key_of(bins + next_made) : ~0ull;
-                if (lk < mk) {
-                    pick[k] = (int)(lk & 511ull);
+                const unsigned long long l2 = next_leaf + 2 < alive ? leaf_key[next_leaf + 2] : none;
+                const unsigned long long m2 = next_made + 2 < made ? key_of(bins + next_made + 2) : none;
+                if (l0 < m0) {
+                    pick[k] = l0;
+                    l0 = l1;
+                    l1 = l2;
                     ++next_leaf;
                 } else {
-                    pick[k] = bins + next_made;
+                    pick[k] = m0;
+                    m0 = m1;
+                    m1 = m2;
                     ++next_made;
                 }
             }
-            weight[bins + made] = weight[pick[0]] + weight[pick[1]];
-            parent[pick[0]] = (short)(bins + made);
-            parent[pick[1]] = (short)(bins + made);
+            const int node = bins + made;
+            const unsigned long long sum = (pick[0] >> 9) + (pick[1] >> 9);
+            const unsigned long long key = (sum << 9) | (unsigned long long)node;
+            weight[node] = sum;
+            parent[(int)(pick[0] & 511ull)] = (short)node;
+            parent[(int)(pick[1] & 511ull)] = (short)node;
+            // The new node is entry `made` of its queue: the first or second one not yet taken?
+            if (made == next_made) m0 = key;
+            else if (made == next_made + 1) m1 = key;
             ++made;
         }
     }
@@ -137,12 +170,28 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
         }
     }
     __syncthreads();
-    for (int c = lane; c < bins; c += 64) {
-        const int l = len_of[c];
-        unsigned int rank = 0;
-        for (int j = 0; j < c; ++j) rank += len_of[j] == l ? 1u : 0u;
-        lengths[row + c] = (uint8_t)l;
-        codewords[row + c] = l ? first_code[l] + rank : 0ull;
+    // Canonical codewords: a level's place among the levels of its length, in number order.
+    {
+        int len[4];
+        unsigned int rank[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            len[q] = len_of[lane + 64 * q];                    // 0 beyond `bins`
+            rank[q] = 0u;
+        }
+#pragma unroll 8
+        for (int j = 0; j < bins_up; ++j) {
+            const int other = len_of[j];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rank[q] += (other == len[q] && j < lane + 64 * q) ? 1u : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = lane + 64 * q;
+            if (c >= bins) continue;
+            lengths[row + c] = (uint8_t)len[q];
+            codewords[row + c] = len[q] ? first_code[len[q]] + rank[q] : 0ull;
+        }
     }
 }
 
@@ -785,7 +834,7 @@ __device__ __forceinline__ void fill_decode_table(DecodeTable &tab, const uint8_
     // Chain single-symbol lookups inside the 10-bit window.  Bits beyond the window read as
     // zeros, so a hit only counts when the whole codeword lies inside the window.
     // A thread walks four windows side by side, so that their table reads overlap.
-    constexpr int kMaxSyms = 24 / R < 10 ? 24 / R : 10;
+    constexpr int kMaxSyms = 24 / R < kFastBits ? 24 / R : kFastBits;
     constexpr int kSide = 4;
     for (int i0 = tid; i0 < (1 << kFastBits); i0 += kSide * blockDim.x) {
         unsigned int used[kSide], syms[kSide], packed[kSide];
