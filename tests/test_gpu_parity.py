@@ -437,11 +437,14 @@ def test_aggregate_worker_counts(E, P, s, bucket):
     _free_run(E, wl, 2)
 
 
-@pytest.mark.parametrize("P,s,bucket", [(13, 1, 512), (16, 1, 8192), (13, 7, 2048), (12, 5, 496)])
+@pytest.mark.parametrize("P,s,bucket", [(13, 1, 512), (16, 1, 8192), (13, 7, 2048), (12, 5, 496), (34, 3, 1000),
+                                        (18, 31, 4096)])
 def test_aggregate_many_workers_long_rows(E, P, s, bucket):
-    """Twelve or more workers on rows of more than 2^23 elements (2-, 3- and 4-bit codes):
+    """Twelve or more workers on rows of more than 2^23 elements (2-, 3-, 4- and 6-bit codes):
     per-lane and per-wave norms, worker counts that are not a multiple of the batch of four,
-    a ragged last run, and the model update fused into the aggregation."""
+    a ragged last run, and the model update fused into the aggregation.  The last two cases
+    hold more than 96 MB of codes in all, the size from which the codes are streamed past the
+    cache, at code widths the benchmark's workloads do not have."""
     N = (1 << 23) + 3 * 1024 + 500
     wl = synth.Workload("edge", P=P, N=N, bucket=bucket, s=s, alpha=1.0, beta=0.9, iters=1, kind="student_t",
                         data_seed=P + s)
