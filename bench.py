@@ -82,13 +82,27 @@ def cpu_baseline(wl, sample_n, g_sample, steps=3):
         codes = oracle.pack_rows(q, wl.s)
         oracle.aggregate(codes, scales, sample_n, wl.bucket, wl.s)
     dt = (time.perf_counter() - t0) / steps
-    rb = oracle.row_bytes(sample_n, wl.s)
-    nb = (sample_n + wl.bucket - 1) // wl.bucket
-    nbytes = P * (12 * sample_n + rb + 4 * nb) + P * (rb + 4 * nb) + 4 * sample_n
-    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+
+    def step_bytes(n):
+        rb = oracle.row_bytes(n, wl.s)
+        nb = (n + wl.bucket - 1) // wl.bucket
+        return P * (12 * n + rb + 4 * nb) + P * (rb + 4 * nb) + 4 * n
+
+    # The same on one thread, one step, on a sixteenth of the sample (whole buckets).
+    n1 = max(wl.bucket, sample_n // 16 // wl.bucket * wl.bucket)
+    n1 = min(n1, sample_n)
+    g1 = np.ascontiguousarray(g[:, :n1])
+    h1 = np.zeros_like(g1)
+    t0 = time.perf_counter()
+    q, scales, _ = oracle.batch_step(g1, h1, wl.bucket, wl.s, wl.alpha, wl.beta, 1, 0, threads=1, norm=wl.norm)
+    oracle.aggregate(oracle.pack_rows(q, wl.s), scales, n1, wl.bucket, wl.s)
+    dt1 = time.perf_counter() - t0
+    return {"value": round(step_bytes(sample_n) / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"first {sample_n} elements of each of the {P} workers, {steps} steps "
                       f"(quantise+update, pack, aggregate), {dt:.2f} s wall per step on {threads} threads",
-            "gelem_per_s": round(P * sample_n / dt / 1e9, 5)}
+            "gelem_per_s": round(P * sample_n / dt / 1e9, 5),
+            "one_thread": {"value": round(step_bytes(n1) / dt1 / 1e9, 4), "unit": "GB/s",
+                           "sample": f"first {n1} elements of each worker, one step, {dt1:.2f} s"}}
 
 
 def entropy_coding(E, torch, sh, wl, codes, timed):
