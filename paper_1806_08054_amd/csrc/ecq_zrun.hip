@@ -39,6 +39,12 @@ constexpr int kZRingWords = 16;                                // decode: words 
 // at most one, plus the tile's closing token) of at most 63 bits, plus the up-to-31-bit shift
 // that aligns the buffer with the stream's words.
 constexpr int kZBufWords = ((kZStep + 1) * kZMaxLen + 31 + 31) / 32 + 1;
+// When no codeword is longer than 24 bits a step fills at most kZKeepAt words of that buffer; the
+// rest holds the table entries of the step's tokens, at most 18 per lane (one per element, one
+// "Z zeros" completed by the zeros carried in, one closing token).
+constexpr int kZKeepAt = ((kZStep + 1) * 24 + 31 + 31) / 32 + 1;
+constexpr int kZKeepMax = 18;
+static_assert(kZKeepAt + kZKeepMax * 64 <= kZBufWords, "the kept entries fit behind the short codewords");
 
 static_assert(kZTile == 4096 && kZGroup == 64 && kZGroup % kZBlockTiles == 0, "a wave scans one group's 64 tile sizes");
 
@@ -439,8 +445,18 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
             const int64_t elem = step_first + lane * 16;
             const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
             const bool close = closes_tile(a.n, tile, elem, valid);
+            // First walk: the lane's bits; while no codeword is longer than 24 bits the tokens'
+            // table entries are kept (entry k of lane t at [k][t], behind the part of the buffer
+            // such codewords can fill), so the second walk need not find the tokens again.
+            const bool all_short = tab.all_short != 0;
             unsigned int nbits = 0;
-            lane_tokens<R>(cd, valid, run, close, z, [&](int token) { nbits += tab.len[token & 255]; });
+            int kept = 0;
+            lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
+                const unsigned int e = tab.packed[token & 255];
+                nbits += e >> 24;
+                if (all_short && kept < kZKeepMax) mine[kZKeepAt + kept * 64 + lane] = e;
+                ++kept;
+            });
             const unsigned int incl_bits = wave_inclusive_scan(nbits);
             const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63);
             const unsigned int shift = (unsigned int)(pos & 31ull);
@@ -465,12 +481,13 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
                         held -= 32u;
                     }
                 };
-                const bool all_short = tab.all_short != 0;
-                lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
-                    if (all_short) {
-                        const unsigned int e = tab.packed[token & 255];
+                if (all_short) {
+                    for (int k = 0; k < kept; ++k) {
+                        const unsigned int e = mine[kZKeepAt + k * 64 + lane];
                         put(e & 0xFFFFFFu, e >> 24);
-                    } else {
+                    }
+                } else {
+                    lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
                         unsigned int l = tab.len[token & 255];
                         unsigned long long bits = tab.rev[token & 255];
                         if (l > 32u) {
@@ -479,8 +496,8 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
                             l -= 32u;
                         }
                         put((unsigned int)bits, l);
-                    }
-                });
+                    });
+                }
                 if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
             }
             wave_lds_sync();
