@@ -536,11 +536,15 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 // Decoding a tile is a chain (a token's position is known only once the one before it has been
 // decoded), so the work per token is kept small:
 //  - `fast` maps the next 12 stream bits to the token whose codeword they begin with, together
-//    with what the token stands for: (length << 16) | (zeros << 8) | code, code 255 = no level;
-//    0 = the codeword is longer than 12 bits.  (16-bit entries with a second lookup of what the
-//    token stands for free LDS for two more blocks per compute unit, but the second lookup
-//    lengthens every token's chain: 6-8 % slower at 8 and 16 workers, 8 % faster at 32.)  In a
-//    canonical code the codewords, left-aligned,
+//    with what the token stands for: length | zeros << 4 | d << 11 in 16 bits, where d is the
+//    XOR of the level's code with the code of level 0 (0 = the token has no level); 0 = the
+//    codeword is longer than 12 bits.  Up to 4-bit codes the upper 16 bits describe, in the same
+//    form, the token that follows when its codeword also ends inside the 12 bits (0 = none): one
+//    lookup then yields two tokens; wider codes keep d in the upper half (8 bits) and get one
+//    token per lookup.  (16-bit entries with a second lookup of what the token stands for free
+//    LDS for two more blocks per compute unit, but the second lookup lengthens every token's
+//    chain: 6-8 % slower at 8 and 16 workers, 8 % faster at 32.)  In a canonical code the
+//    codewords, left-aligned,
 //    grow with their length, so the length of a longer codeword is 13 plus the number of
 //    lengths l >= 13 whose last left-aligned codeword lies below the next 32 stream bits: a
 //    count over 20 bounds that every lane keeps in registers (in a wave of 64 tiles some lane
@@ -561,7 +565,7 @@ struct ZDecodeTable {
     unsigned int last[33];                   // last left-aligned 32-bit codeword of lengths <= l (wraps to ~0 when none)
     unsigned int delta[33];                  // index into sorted[] minus the codeword, per length
     unsigned short base[64];                 // index into sorted[] of the first one
-    unsigned short info[256];                // token -> (zeros << 8) | code
+    unsigned short info[256];                // token -> (zeros << 8) | d (d: see above)
     unsigned short sorted_info[256];         // info of the tokens in the order (length, token)
     unsigned char sorted[256];               // tokens in the order (length, token)
 };
@@ -581,10 +585,10 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
     for (int c = tid; c < 256; c += blockDim.x) {
         tab.sorted[c] = (unsigned char)z.zz;
         if (c >= z.zz) {                                       // "Z zeros" (entries beyond it are never reached)
-            tab.info[c] = (unsigned short)((z.Z << 8) | 255);
+            tab.info[c] = (unsigned short)(z.Z << 8);
         } else {
-            const int rank = c % z.two_s;
-            tab.info[c] = (unsigned short)(((c / z.two_s) << 8) | (rank < z.s ? rank : rank + 1));
+            const int rank = c % z.two_s, code = rank < z.s ? rank : rank + 1;
+            tab.info[c] = (unsigned short)(((c / z.two_s) << 8) | ((code ^ z.s) & ((1 << R) - 1)));
         }
     }
     if (tid < 8) {                                             // bits [32 tid, 32 tid + 32) of the all-zero-level stream
@@ -634,10 +638,28 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
         if (!l || l > kZFastBits) continue;                    // block-uniform
         const unsigned long long cw = codewords[c] & ((1ull << l) - 1ull);
         const unsigned int rev = (unsigned int)(__brevll(cw) >> (64 - l));
-        const unsigned int entry = ((unsigned int)l << 16) | tab.info[c];
+        const unsigned int info = tab.info[c], zeros = info >> 8, d = info & 255u;
+        const unsigned int entry = (unsigned int)l | (zeros << 4) | (d << (R <= 4 ? 11 : 16));
         for (unsigned int hi = tid; hi < (1u << (kZFastBits - l)); hi += blockDim.x) tab.fast[rev | (hi << l)] = entry;
     }
     __syncthreads();
+    if constexpr (R <= 4) {
+        // The token that follows inside the window: the entry of the window shifted by the first
+        // codeword, when both lengths fit 12 bits (then it did not depend on the bits shifted in).
+        constexpr int kMine = (1 << kZFastBits) / 256;
+        unsigned int second[kMine];
+#pragma unroll
+        for (int q = 0; q < kMine; ++q) {
+            const unsigned int i = (unsigned int)tid + 256u * q;
+            const unsigned int first = tab.fast[i];
+            const unsigned int next = first ? tab.fast[i >> (first & 15u)] & 0xFFFFu : 0u;
+            second[q] = (next && (first & 15u) + (next & 15u) <= (unsigned int)kZFastBits) ? next : 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kMine; ++q) tab.fast[tid + 256 * q] |= second[q] << 16;
+        __syncthreads();
+    }
 }
 
 template <int R>
@@ -750,10 +772,13 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         // Tokens while the lane's next element lies in this window.
         while (remaining > 0 && held_word < 0 && ((at * R) >> 5) < w_end) {
             refill();
-            unsigned int entry = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
-            if (entry) {
-                res >>= (entry >> 16);
-                have -= (entry >> 16);
+            const unsigned int hit = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
+            unsigned int entry, second = 0u;                   // entry: (zeros << 8) | d
+            if (hit) {
+                res >>= (hit & 15u);
+                have -= (hit & 15u);
+                entry = ((hit << 4) & 0x7F00u) | (R <= 4 ? (hit >> 11) & 15u : (hit >> 16) & 255u);
+                if constexpr (R <= 4) second = hit >> 16;
             } else {
                 // Longer than the table covers: its length from the bounds, then its place among the
                 // codewords of that length.
@@ -788,13 +813,12 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                 }
             }
             int zeros = (int)((entry >> 8) & 0xFFu);
-            const unsigned int code = entry & 0xFFu;
+            const unsigned int delta = entry & 0xFFu;
             zeros = zeros < remaining ? zeros : remaining;
             at += zeros;
             remaining -= zeros;
-            if (code != 255u && remaining > 0) {
+            if (delta != 0u && remaining > 0) {
                 // The window holds the code of level 0 (s) here: XOR turns it into the level's code.
-                const unsigned int delta = (code ^ (unsigned int)a.s) & ((1u << R) - 1u);
                 const int bit = at * R, word = bit >> 5, sh = bit & 31;
                 if (word < w_end) {
                     atomicXor(&ring[(word - w0) * 256], delta << sh);
@@ -812,6 +836,26 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                 }
                 ++at;
                 --remaining;
+            }
+            if constexpr (R <= 4) {
+                // The second token of the lookup, taken only when it lies wholly inside the tile
+                // and the window (else its codeword stays in the stream for the next lookup).
+                if (second != 0u && held_word < 0) {
+                    const int zeros2 = (int)((second >> 4) & 127u);
+                    const unsigned int delta2 = (second >> 11) & 15u;
+                    const int level_at = at + zeros2, covers = zeros2 + (delta2 != 0u ? 1 : 0);
+                    if (covers <= remaining && ((level_at * R + (R - 1)) >> 5) < w_end) {
+                        res >>= (second & 15u);
+                        have -= (second & 15u);
+                        if (delta2 != 0u) {
+                            const int bit = level_at * R, word = bit >> 5, sh = bit & 31;
+                            atomicXor(&ring[(word - w0) * 256], delta2 << sh);
+                            if ((32 % R) != 0 && sh + R > 32) atomicXor(&ring[(word + 1 - w0) * 256], delta2 >> (32 - sh));
+                        }
+                        at += covers;
+                        remaining -= covers;
+                    }
+                }
             }
         }
         // The window leaves: whole, or the last words of a ragged tile with its pad bits zero.
