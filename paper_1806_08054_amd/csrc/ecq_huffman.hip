@@ -955,22 +955,42 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
     unsigned int out_held = 0;
     unsigned int *__restrict__ ring = out_ring + threadIdx.x;
     int ring_at = 0;
+    const bool rows_on_16 = (reinterpret_cast<uintptr_t>(crow) & 15u) == 0u;   // block-uniform
     auto flush_ring = [&](int count) {
         if (count == kRingWords && out_byte + 4 * kRingWords <= a.row_bytes) {
+            if (rows_on_16) {                                  // (a tile starts on a multiple of 128 bytes of its row)
 #pragma unroll
-            for (int k = 0; k < kRingWords; ++k)
-                reinterpret_cast<uint32_t *>(crow + out_byte)[k] = ring[k * kDecodeThreads];
+                for (int q = 0; q < kRingWords / 4; ++q) {
+                    uint4 v;
+                    v.x = ring[(4 * q + 0) * kDecodeThreads];
+                    v.y = ring[(4 * q + 1) * kDecodeThreads];
+                    v.z = ring[(4 * q + 2) * kDecodeThreads];
+                    v.w = ring[(4 * q + 3) * kDecodeThreads];
+                    reinterpret_cast<uint4 *>(crow + out_byte)[q] = v;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < kRingWords; ++k)
+                    reinterpret_cast<uint32_t *>(crow + out_byte)[k] = ring[k * kDecodeThreads];
+            }
         } else {
             for (int k = 0; k < count; ++k)
                 store_code_bytes(crow + out_byte + 4 * k, ring[k * kDecodeThreads], 4, a.row_bytes - (out_byte + 4 * k));
         }
         out_byte += 4 * count;
     };
-    while (remaining > 0) {
+    // The lanes of a wave fill their rings side by side (a tile gives every lane the same number
+    // of words) and empty them together: one store sequence per 64 bytes of every tile.  (Each
+    // lane emptying its own ring when full made the wave run that sequence for one or two lanes
+    // in most rounds.)  A lookup adds at most 24 bits to fewer than 32 held ones, so at most one
+    // word per lookup: a lane stops when its ring is full and keeps the rest in `out_acc`.
+#pragma unroll 1
+    for (int piece = 0; piece < (kTile * R / 32) / kRingWords; ++piece) {
+    while (remaining > 0 && ring_at < kRingWords) {
       refill();                                                // have >= 33 here: enough for three lookups
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
-        if (remaining <= 0 || have < (unsigned int)kFastBits) break;   // (a long codeword may have used more)
+        if (remaining <= 0 || have < (unsigned int)kFastBits || ring_at >= kRingWords) break;   // (a long codeword may have used more)
         const unsigned int m = tab.multi[(unsigned int)res & ((1u << kFastBits) - 1u)];
         const unsigned int syms = m >> 28;
         if (syms != 0u && (int)syms <= remaining) {
@@ -1035,11 +1055,12 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
         out_acc = full ? out_acc >> 32 : out_acc;
         out_held -= full ? 32u : 0u;
         ring_at += full ? 1 : 0;
-        if (ring_at == kRingWords) {                            // 64 bytes of codes: send them off together
-            flush_ring(kRingWords);
-            ring_at = 0;
-        }
       }
+    }
+    if (ring_at == kRingWords) {                                // 64 bytes of codes of every tile of the wave
+        flush_ring(kRingWords);
+        ring_at = 0;
+    }
     }
     // What is left of a ragged last tile: whole words, then fewer than 32 bits (pad bits zero).
     flush_ring(ring_at);
