@@ -880,7 +880,8 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
                                                        const unsigned long long *__restrict__ tile_offsets,
                                                        const int64_t offset_stride,
                                                        const uint32_t *__restrict__ streams,
-                                                       const int64_t stream_words, const int64_t stream_stride_words)
+                                                       const int64_t stream_words, const int64_t stream_stride_words,
+                                                       const int lanes)
 {
     __shared__ DecodeTable tab;
     // Word k of lane t's ring at [k][t]: whatever slots the lanes of a wave are at, they write to
@@ -889,8 +890,11 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
     const uint32_t p = blockIdx.y;
     fill_decode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride,
                          2 * a.s + 1);
-    const int64_t tile = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tile >= tiles) return;                                 // after the last barrier
+    // A wave takes `lanes` tiles, one per lane of its first `lanes` lanes: decoding is a chain of
+    // dependent instructions, so while the message has too few tiles to fill the chip with
+    // whole waves, more waves with idle lanes finish sooner.
+    const int64_t tile = ((int64_t)blockIdx.x * (kDecodeThreads / 64) + (threadIdx.x >> 6)) * lanes + (threadIdx.x & 63);
+    if ((int)(threadIdx.x & 63) >= lanes || tile >= tiles) return;   // after the last barrier
     const int64_t elem0 = tile * kTile;
     int remaining = (int)((a.n - elem0) < kTile ? (a.n - elem0) : (int64_t)kTile);
     const uint32_t *__restrict__ in = streams + (int64_t)p * stream_stride_words;
@@ -1110,10 +1114,16 @@ hipError_t launch_huffman_decode(const Args &a, const uint8_t *lengths, const un
                                  const unsigned long long *tile_offsets, int64_t offset_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kTile - 1) / kTile;
-    const dim3 grid(cdiv(tiles, kDecodeThreads), (unsigned)a.workers);
+    // Tiles per wave: 64 when that still gives the chip all the waves it can hold at once (six
+    // blocks per compute unit), else as few as spreads the tiles over that many waves (8 at least).
+    const int64_t held = (int64_t)256 * 6 * (kDecodeThreads / 64);
+    int64_t lanes = (tiles * a.workers + held - 1) / held;
+    lanes = (lanes + 7) / 8 * 8;
+    lanes = lanes < 8 ? 8 : (lanes > 64 ? 64 : lanes);
+    const dim3 grid(cdiv(cdiv(tiles, lanes), kDecodeThreads / 64), (unsigned)a.workers);
 #define CALL(RR)                                                                                               \
     hipLaunchKernelGGL((k_huffman_decode<RR>), grid, dim3(kDecodeThreads), 0, stream, a, lengths, codewords, table_stride,   \
-                       tiles, tile_offsets, offset_stride, streams, stream_stride_words, stream_stride_words)
+                       tiles, tile_offsets, offset_stride, streams, stream_stride_words, stream_stride_words, (int)lanes)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();

@@ -568,6 +568,7 @@ struct ZDecodeTable {
     unsigned short info[256];                // token -> (zeros << 8) | d (d: see above)
     unsigned short sorted_info[256];         // info of the tokens in the order (length, token)
     unsigned char sorted[256];               // tokens in the order (length, token)
+    unsigned char len[256];                  // codeword length of every token (0: does not occur)
 };
 
 template <int R>
@@ -576,12 +577,15 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
                                                    const ZrunShape &z)
 {
     const int tid = threadIdx.x, symbols = z.zz + 1;
-    auto len_of = [&](int c) -> int { return c < symbols ? (lengths[c] > kZMaxLen ? kZMaxLen : lengths[c]) : 0; };
+    // The lengths go to LDS first: the loops below read them many times, and a read from global
+    // memory inside a loop that every thread of the block walks costs its full latency each time.
+    for (int c = tid; c < 256; c += blockDim.x)
+        tab.len[c] = (unsigned char)(c < symbols ? (lengths[c] > kZMaxLen ? kZMaxLen : lengths[c]) : 0);
+    auto len_of = [&](int c) -> int { return tab.len[c & 255]; };
     for (int l = tid; l < 64; l += blockDim.x) {
         tab.count[l] = 0;
         tab.first_code[l] = 0ull;
     }
-    for (int i = tid; i < (1 << kZFastBits); i += blockDim.x) tab.fast[i] = 0u;
     for (int c = tid; c < 256; c += blockDim.x) {
         tab.sorted[c] = (unsigned char)z.zz;
         if (c >= z.zz) {                                       // "Z zeros" (entries beyond it are never reached)
@@ -632,15 +636,25 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
         tab.last[l] = (unsigned int)(bound - 1ull);
         tab.delta[l] = (unsigned int)tab.base[l] - (unsigned int)tab.first_code[l];
     }
-    // Every window whose low bits are a codeword of at most kZFastBits bits.
-    for (int c = 0; c < symbols; ++c) {
-        const int l = len_of(c);
-        if (!l || l > kZFastBits) continue;                    // block-uniform
-        const unsigned long long cw = codewords[c] & ((1ull << l) - 1ull);
-        const unsigned int rev = (unsigned int)(__brevll(cw) >> (64 - l));
-        const unsigned int info = tab.info[c], zeros = info >> 8, d = info & 255u;
-        const unsigned int entry = (unsigned int)l | (zeros << 4) | (d << (R <= 4 ? 11 : 16));
-        for (unsigned int hi = tid; hi < (1u << (kZFastBits - l)); hi += blockDim.x) tab.fast[rev | (hi << l)] = entry;
+    __syncthreads();
+    // Every window of kZFastBits stream bits that begins with a codeword of at most that length: in
+    // a canonical code the left-aligned codewords grow with their length, so the length is one
+    // plus the number of lengths whose last codeword lies below the window (its unknown bits
+    // taken as zeros: exact up to kZFastBits bits), and the token follows from the codeword's
+    // distance to the first one of its length.  One thread per entry, no walk over the tokens.
+    int shortest = 1;                                          // (lengths below it have no last codeword)
+    while (shortest <= kZFastBits && tab.count[shortest] == 0u) ++shortest;
+    for (unsigned int i = tid; i < (1u << kZFastBits); i += blockDim.x) {
+        const unsigned int top = __brev(i);                    // first stream bit on top
+        int l = 1;
+#pragma unroll
+        for (int j = 1; j <= kZFastBits; ++j) l += (j < shortest || top > tab.last[j]) ? 1 : 0;
+        unsigned int entry = 0u;
+        if (l <= kZFastBits) {
+            const unsigned int info = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
+            entry = (unsigned int)l | ((info >> 8) << 4) | ((info & 255u) << (R <= 4 ? 11 : 16));
+        }
+        tab.fast[i] = entry;
     }
     __syncthreads();
     if constexpr (R <= 4) {
@@ -669,7 +683,8 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                                                     const uint32_t *__restrict__ tile_bits, const int64_t tile_stride,
                                                     const unsigned long long *__restrict__ group_offsets,
                                                     const int64_t group_stride, const uint32_t *__restrict__ streams,
-                                                    const int64_t stream_words, const int64_t stream_stride_words)
+                                                    const int64_t stream_words, const int64_t stream_stride_words,
+                                                    const int lanes_shift)
 {
     constexpr int kPeriod = R == 2 || R == 4 || R == 8 ? 1 : (R == 6 ? 3 : R);   // words after which zero_words repeat
     __shared__ ZDecodeTable tab;
@@ -679,13 +694,23 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     fill_zdecode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t group = (int64_t)blockIdx.x * 4 + wave;
+    // A wave takes 64 >> lanes_shift tiles of a group, one per lane of its first lanes: decoding
+    // is a chain of dependent instructions, so while the message has too few tiles to fill the
+    // chip with whole waves, more waves with idle lanes finish sooner (and a wave waits for the
+    // slowest of fewer tiles at every window).
+    const int64_t part = (int64_t)blockIdx.x * 4 + wave;       // index of the wave's part of a group
+    const int64_t group = part >> lanes_shift;
     if (group * kZGroup >= tiles) return;                      // wave-uniform, after the last barrier
-    const int64_t tile = group * kZGroup + lane;
-    const unsigned int my_bits = tile < tiles ? tile_bits[(int64_t)p * tile_stride + tile] : 0u;
-    const unsigned int incl = wave_inclusive_scan(my_bits);
-    const unsigned long long start = group_offsets[(int64_t)p * group_stride + group] + (incl - my_bits);
-    if (tile >= tiles) return;
+    const int lanes = kZGroup >> lanes_shift;
+    const int first = (int)(part & ((1 << lanes_shift) - 1)) * lanes;   // its first tile inside the group
+    // All 64 lanes add up the group's tile sizes; lane i then takes the start of tile first + i.
+    const int64_t scan_tile = group * kZGroup + lane;
+    const unsigned int scan_bits = scan_tile < tiles ? tile_bits[(int64_t)p * tile_stride + scan_tile] : 0u;
+    const unsigned int before = wave_inclusive_scan(scan_bits) - scan_bits;
+    const unsigned int mine_before = (unsigned int)__shfl((int)before, (first + lane) & 63, 64);
+    const int64_t tile = group * kZGroup + first + lane;
+    const unsigned long long start = group_offsets[(int64_t)p * group_stride + group] + mine_before;
+    if (lane >= lanes || tile >= tiles) return;
     const int64_t elem0 = tile * kZTile;
     const int tile_elems = (int)((a.n - elem0) < kZTile ? (a.n - elem0) : (int64_t)kZTile);
     int remaining = tile_elems;
@@ -941,11 +966,16 @@ hipError_t launch_zrun_decode(const Args &a, const uint8_t *lengths, const unsig
                               int64_t group_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kZTile - 1) / kZTile;
-    const dim3 grid(cdiv(cdiv(tiles, kZGroup), 4), (unsigned)a.workers);
+    // Tiles per wave: 64, halved while twice the waves are still no more than the chip holds at
+    // once (four blocks per compute unit), down to 8.
+    const int64_t held = (int64_t)256 * 4 * 4;
+    int lanes_shift = 0;
+    while (lanes_shift < 3 && cdiv(tiles, kZGroup >> (lanes_shift + 1)) * a.workers <= held) ++lanes_shift;
+    const dim3 grid(cdiv(cdiv(tiles, kZGroup) << lanes_shift, 4), (unsigned)a.workers);
 #define CALL(RR)                                                                                                    \
     hipLaunchKernelGGL((k_zrun_decode<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride, tiles, \
                        tile_bits, tile_stride, group_offsets, group_stride, streams, stream_stride_words,           \
-                       stream_stride_words)
+                       stream_stride_words, lanes_shift)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();

@@ -267,3 +267,51 @@ def test_zrun_full_size(E, name, rows):
         bound = oracle.entropy_bound_bits(oracle.level_histogram(q, s))
         print(f"{name}: worker {p}: {bits / N:.4f} bits per element, bound {bound / N:.4f}, "
               f"fixed length {E.code_bits(s)}", flush=True)
+
+
+@pytest.mark.parametrize("P,tiles,s", [(1, 300, 1), (2, 20_000, 4), (2, 40_000, 1), (3, 50_000, 2)])
+def test_zrun_decoder_tiles_per_wave(E, P, tiles, s):
+    """The decoder gives a wave 8, 16, 32 or 64 tiles depending on how many tiles the whole
+    message has (the four cases, in that order), the per-level decoder between 8 and 64: every
+    setting decodes the message it was given, through groups of 64 tiles that several waves
+    share and a ragged last tile.  Levels come straight from the seeded generator; the encoder
+    that feeds the decoder is compared with the oracle elsewhere, here on row 0."""
+    N = tiles * 4096 - 1234
+    rng = np.random.default_rng([P, tiles, s])
+    q = _levels(rng, P, N, s, 0.08)
+    q[:, N // 3: N // 3 + 3 * 64 * 4096] = 0                    # three whole groups of zeros
+    st = GpuState(E, P, N, 512, s)
+    codes_ref = oracle.pack_rows(q, s)
+    st.codes[:, : st.rb] = _dev(codes_ref)
+    zb = ZrunBuffers(E, P, N, s)
+    E.ecq_zrun_histogram(st.sh, st.codes, zb.counts, zb.table_stride)
+    E.ecq_zrun_build(P, s, zb.counts, zb.table_stride, zb.lengths, zb.codewords)
+    E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                      zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+    back = torch.full_like(st.codes, 0xEE)
+    E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                      zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, back)
+    torch.cuda.synchronize()
+    ref_counts = oracle.zrun_histogram(q[0], s)
+    ref_len = oracle.huffman_lengths(ref_counts)
+    ref_cw = oracle.huffman_codes(ref_len)
+    ref_stream, ref_bits, ref_groups, bits = oracle.zrun_encode(q[0], s, ref_len, ref_cw)
+    assert np.array_equal(zb.tile_bits[0, : zb.tiles].cpu().numpy().view(np.uint32), ref_bits)
+    assert np.array_equal(zb.streams[0, : (bits + 7) // 8].cpu().numpy(), ref_stream[: (bits + 7) // 8])
+    assert torch.equal(back[:, : st.rb].cpu(), torch.from_numpy(codes_ref)), "decode(encode(message)) differs"
+    assert bool((back[:, st.rb:] == 0xEE).all())
+    # the per-level coder on the same message
+    bins = 2 * s + 1
+    hcounts = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    hlen = torch.zeros(P, bins, dtype=torch.uint8, device="cuda")
+    hwords = torch.zeros(P, bins, dtype=torch.int64, device="cuda")
+    htiles = E.huffman_num_tiles(N)
+    offs = torch.zeros(P, htiles + 1, dtype=torch.int64, device="cuda")
+    hstreams = torch.zeros(P, st.sh.code_stride, dtype=torch.uint8, device="cuda")
+    E.ecq_level_histogram(st.sh, st.codes, hcounts, bins)
+    E.ecq_huffman_build(P, s, hcounts, bins, hlen, hwords)
+    E.ecq_huffman_encode(st.sh, st.codes, hlen, hwords, bins, hstreams, st.sh.code_stride, offs, htiles + 1)
+    back.fill_(0xEE)
+    E.ecq_huffman_decode(st.sh, hstreams, st.sh.code_stride, offs, htiles + 1, hlen, hwords, bins, back)
+    torch.cuda.synchronize()
+    assert torch.equal(back[:, : st.rb].cpu(), torch.from_numpy(codes_ref)), "per-level decode(encode(message)) differs"
