@@ -106,6 +106,43 @@ def test_entry_points_reject_bad_arguments_before_any_launch(E):
     assert lib.ecq_quantize_update_ex(C.byref(sh), fake, fake, 1.0, 1.0, 1, 0, fake, fake, C.byref(tu), None) == -8
 
 
+def test_header_is_plain_c_and_the_library_links_from_c(E, tmp_path):
+    """include/ecq.h compiles as C99 and as C++ without warnings, and a C program linked against
+    the library gets the documented answers from its host-side helpers."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(ROOT, "include")
+    src = os.path.join(ROOT, "tests", "abi_check.c")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, src],
+                   check=True)
+    gxx = shutil.which("g++")
+    if gxx:
+        subprocess.run([gxx, "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc,
+                        os.path.join(inc, "ecq.h")], check=True)
+    libdir = os.path.dirname(E.library_path())
+    exe = str(tmp_path / "abi_check")
+    subprocess.run([gcc, "-std=c99", "-I", inc, src, "-o", exe, "-L", libdir, "-lecq", "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split("\n")
+    n, r = 25557032, 2
+    tiles = (n + 4095) // 4096
+    assert out[:10] == [
+        "code_bits 2 4 8",
+        f"row_bytes 0 {(n * r + 7) // 8}",
+        f"num_buckets 0 {(n + 511) // 512}",
+        "check_shape 0",
+        "check_shape_bad_bucket 1",
+        "zrun_symbols 0 31 249",
+        f"zrun_num_tiles 0 {tiles} {(tiles + 63) // 64}",
+        f"zrun_stream_bytes 0 {((n * 2 + tiles * 2 * 127 + 7) // 8 + 3) // 4 * 4}",
+        "null_pointer 1",
+        "status_string text",
+    ], out
+
+
 def test_no_cpu_fallback_in_the_product():
     """The package never imports the oracle (or anything else that could stand in for the
     kernels)."""
