@@ -205,6 +205,67 @@ __device__ __forceinline__ bool closes_tile(int64_t n, int64_t tile, int64_t ele
 }
 
 // ---------------------------------------------------------------------------------------------
+// A whole tile per wave step: lane l owns the 64 consecutive elements [64 l, 64 l + 64) of the
+// tile, as four runs of 16.  The two counting passes (token histogram, tile sizes) only need
+// sums over a tile's tokens, so they take a tile in one step: one scan over the wave per tile
+// instead of one per 1024 elements.
+// ---------------------------------------------------------------------------------------------
+template <int R>
+struct TileCodes {
+    Codes16<R> q[4];
+    int valid;                                                 // how many of the lane's 64 elements exist
+};
+
+template <int R>
+__device__ __forceinline__ void load_tile_codes(const uint8_t *__restrict__ crow, int64_t row_bytes, int64_t n,
+                                                int64_t elem, TileCodes<R> &t)
+{
+    int valid = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) valid += load_step_codes<R>(crow, row_bytes, n, elem + 16 * k, t.q[k]);
+    t.valid = valid;
+}
+
+// Tokens of the lane's 64 elements in stream order; `tile_elems` = elements of the tile (4096, or
+// fewer for the last tile of a row).  Every lane of the wave must call it.
+template <int R, class Emit>
+__device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int tile_elems, const ZrunShape &z,
+                                            Emit &&emit)
+{
+    constexpr int kStride = NonZero<R>::kStride;
+    // The lane's last non-zero element (position inside the tile), or -1.
+    int last = -1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int valid_k = t.valid - 16 * k;
+        valid_k = valid_k < 0 ? 0 : (valid_k > 16 ? 16 : valid_k);
+        uint32_t mask = NonZero<R>::mask(t.q[k], z.s);
+        if (valid_k < 16) mask &= (1u << (valid_k * kStride)) - 1u;
+        if (mask) last = lane * 64 + 16 * k + (31 - __builtin_clz(mask)) / kStride;
+    }
+    // Inclusive maximum scan over the wave (lanes without a source take -1), then one lane down.
+    int incl = last;
+    auto step_max = [&](int other) { incl = other > incl ? other : incl; };
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x111, 0xF, 0xF, false));   // row_shr:1
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x112, 0xF, 0xF, false));   // row_shr:2
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x114, 0xF, 0xF, false));   // row_shr:4
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x118, 0xF, 0xF, false));   // row_shr:8
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x142, 0xA, 0xF, false));   // row_bcast:15
+    step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x143, 0xC, 0xF, false));   // row_bcast:31
+    const int before = __builtin_amdgcn_update_dpp(-1, incl, 0x138, 0xF, 0xF, false);   // wave_shr:1
+    const int zeros = lane * 64 - before - 1;                  // (before = -1: the tile starts the run)
+    int run = zeros - (int)(((unsigned int)zeros * z.magic) >> 20) * z.Z;   // zeros < 4096: exact
+    const bool closes = t.valid > 0 && lane * 64 + t.valid == tile_elems;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int valid_k = t.valid - 16 * k;
+        valid_k = valid_k < 0 ? 0 : (valid_k > 16 ? 16 : valid_k);
+        const bool close_k = closes && valid_k > 0 && t.valid - 16 * k <= 16;
+        run = lane_tokens<R>(t.q[k], valid_k, run, close_k, z, emit);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Token counts of every worker row.  A block walks units of 16 tiles of one row (a wave 4
 // consecutive tiles of each), counts into one LDS histogram per wave and adds its totals to the
 // row's counters once: long-lived blocks, because all blocks of a row end in the same global
@@ -230,23 +291,17 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
         const int64_t first = unit * kZBlockTiles + wave * kZWaveTiles;
         if (first >= tiles) break;                             // wave-uniform
-        // The wave's steps one after the other, the next step's codes requested a step ahead.
-        Codes16<R> cd, cd_next;
-        int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
-        int since = 0;
+        // The wave's tiles one after the other, the next tile's codes requested a tile ahead.
+        TileCodes<R> cd, cd_next;
+        load_tile_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 64, cd_next);
 #pragma unroll 1
-        for (int i = 0; i < kZWaveSteps; ++i) {
-            const int64_t tile = first + (i / kZSteps);
-            const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
-            const int step_valid = step_elements(a.n, step_first);
-            if (step_valid == 0 || tile >= tiles) break;       // wave-uniform
+        for (int i = 0; i < kZWaveTiles; ++i) {
+            const int64_t tile = first + i;
+            if (tile >= tiles) break;                          // wave-uniform
             cd = cd_next;
-            valid = valid_next;
-            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
-            if ((i % kZSteps) == 0) since = 0;
-            const int64_t elem = step_first + lane * 16;
-            const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
-            lane_tokens<R>(cd, valid, run, closes_tile(a.n, tile, elem, valid), z,
+            load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, cd_next);
+            const int64_t rest = a.n - tile * kZTile;
+            tile_tokens<R>(cd, lane, rest < kZTile ? (int)rest : kZTile, z,
                            [&](int token) { atomicAdd(&mine[token & 255], 1u); });
         }
     }
@@ -260,7 +315,7 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
 
 // ---------------------------------------------------------------------------------------------
 // Encoder, pass 1: the number of stream bits of every tile.  One block per 16 tiles, a wave 4
-// consecutive tiles, the next step's codes requested a step ahead.
+// consecutive tiles, a tile per step.
 // ---------------------------------------------------------------------------------------------
 template <int R>
 __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint8_t *__restrict__ lengths,
@@ -280,30 +335,21 @@ __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint
     const uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     const int64_t first = (int64_t)blockIdx.x * kZBlockTiles + wave * kZWaveTiles;
     if (first >= tiles) return;                                // wave-uniform; no barrier follows
-    Codes16<R> cd, cd_next;
-    int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
-    int since = 0;
-    unsigned int bits = 0;
+    // The wave's tiles one after the other, the next tile's codes requested a tile ahead.
+    TileCodes<R> cd, cd_next;
+    load_tile_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 64, cd_next);
 #pragma unroll 1
-    for (int i = 0; i < kZWaveSteps; ++i) {
-        const int64_t tile = first + (i / kZSteps);
-        const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
-        const int step_valid = step_elements(a.n, step_first);
-        if (tile < tiles && step_valid > 0) {                  // wave-uniform
-            cd = cd_next;
-            valid = valid_next;
-            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
-            if ((i % kZSteps) == 0) since = 0;
-            const int64_t elem = step_first + lane * 16;
-            const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
-            lane_tokens<R>(cd, valid, run, closes_tile(a.n, tile, elem, valid), z,
-                           [&](int token) { bits += len[token & 255]; });
-        }
-        if ((i % kZSteps) == kZSteps - 1 && tile < tiles) {    // the tile's last step: its size
-            const unsigned int incl = wave_inclusive_scan(bits);   // a tile has fewer than 2^32 bits
-            if (lane == 63) tile_bits[(int64_t)p * tile_stride + tile] = incl;
-            bits = 0;
-        }
+    for (int i = 0; i < kZWaveTiles; ++i) {
+        const int64_t tile = first + i;
+        if (tile >= tiles) break;                              // wave-uniform
+        cd = cd_next;
+        load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, cd_next);
+        const int64_t rest = a.n - tile * kZTile;
+        unsigned int bits = 0;
+        tile_tokens<R>(cd, lane, rest < kZTile ? (int)rest : kZTile, z,
+                       [&](int token) { bits += len[token & 255]; });
+        const unsigned int incl = wave_inclusive_scan(bits);   // a tile has fewer than 2^32 bits
+        if (lane == 63) tile_bits[(int64_t)p * tile_stride + tile] = incl;
     }
 }
 
