@@ -39,12 +39,14 @@ constexpr int kZRingWords = 16;                                // decode: words 
 // at most one, plus the tile's closing token) of at most 63 bits, plus the up-to-31-bit shift
 // that aligns the buffer with the stream's words.
 constexpr int kZBufWords = ((kZStep + 1) * kZMaxLen + 31 + 31) / 32 + 1;
-// When no codeword is longer than 24 bits a step fills at most kZKeepAt words of that buffer; the
-// rest holds the table entries of the step's tokens, at most 18 per lane (one per element, one
-// "Z zeros" completed by the zeros carried in, one closing token).
+// When no codeword is longer than 24 bits a step of 1024 elements fills at most kZKeepAt words of
+// that buffer; the rest holds the table entries of the step's tokens, at most 18 per lane (one
+// per element, one "Z zeros" completed by the zeros carried in, one closing token).
 constexpr int kZKeepAt = ((kZStep + 1) * 24 + 31 + 31) / 32 + 1;
 constexpr int kZKeepMax = 18;
 static_assert(kZKeepAt + kZKeepMax * 64 <= kZBufWords, "the kept entries fit behind the short codewords");
+// A tile of at most this many bits is written in one piece (see k_zrun_write).
+constexpr unsigned int kZSparseTileBits = 2048;
 
 static_assert(kZTile == 4096 && kZGroup == 64 && kZGroup % kZBlockTiles == 0, "a wave scans one group's 64 tile sizes");
 
@@ -226,11 +228,10 @@ __device__ __forceinline__ void load_tile_codes(const uint8_t *__restrict__ crow
     t.valid = valid;
 }
 
-// Tokens of the lane's 64 elements in stream order; `tile_elems` = elements of the tile (4096, or
-// fewer for the last tile of a row).  Every lane of the wave must call it.
-template <int R, class Emit>
-__device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int tile_elems, const ZrunShape &z,
-                                            Emit &&emit)
+// The zeros pending before the lane's first element (already below Z).  Every lane of the wave
+// must call it.
+template <int R>
+__device__ __forceinline__ int tile_run_in(const TileCodes<R> &t, int lane, const ZrunShape &z)
 {
     constexpr int kStride = NonZero<R>::kStride;
     // The lane's last non-zero element (position inside the tile), or -1.
@@ -254,7 +255,15 @@ __device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int
     step_max(__builtin_amdgcn_update_dpp(-1, incl, 0x143, 0xC, 0xF, false));   // row_bcast:31
     const int before = __builtin_amdgcn_update_dpp(-1, incl, 0x138, 0xF, 0xF, false);   // wave_shr:1
     const int zeros = lane * 64 - before - 1;                  // (before = -1: the tile starts the run)
-    int run = zeros - (int)(((unsigned int)zeros * z.magic) >> 20) * z.Z;   // zeros < 4096: exact
+    return zeros - (int)(((unsigned int)zeros * z.magic) >> 20) * z.Z;   // zeros < 4096: exact
+}
+
+// Tokens of the lane's 64 elements in stream order, given the run pending before them;
+// `tile_elems` = elements of the tile (4096, or fewer for the last tile of a row).
+template <int R, class Emit>
+__device__ __forceinline__ void tile_walk(const TileCodes<R> &t, int lane, int tile_elems, int run, const ZrunShape &z,
+                                          Emit &&emit)
+{
     const bool closes = t.valid > 0 && lane * 64 + t.valid == tile_elems;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -263,6 +272,13 @@ __device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int
         const bool close_k = closes && valid_k > 0 && t.valid - 16 * k <= 16;
         run = lane_tokens<R>(t.q[k], valid_k, run, close_k, z, emit);
     }
+}
+
+template <int R, class Emit>
+__device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int tile_elems, const ZrunShape &z,
+                                            Emit &&emit)
+{
+    tile_walk<R>(t, lane, tile_elems, tile_run_in<R>(t, lane, z), z, emit);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -460,6 +476,8 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     const int64_t my_tile = group * kZGroup + lane;
     const unsigned int my_bits = my_tile < tiles ? tile_bits[(int64_t)p * tile_stride + my_tile] : 0u;
     const unsigned long long group_start = group_offsets[(int64_t)p * group_stride + group];
+    // (the first step's codes are requested before the table is built; a wave that goes by whole
+    // tiles does not use them)
     Codes16<R> cd, cd_next;
     int valid, valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 16, cd_next);
     fill_zencode_table(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z.zz + 1);
@@ -471,108 +489,152 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     for (int j = lane; j < kZBufWords; j += 64) mine[j] = 0u;
     wave_lds_sync();
 
-    unsigned long long pos = range_start;                      // bit offset of the current step
-    unsigned int carry = 0;                                    // partial last word of the step before
+    unsigned long long pos = range_start;                      // bit offset of the current piece
+    unsigned int carry = 0;                                    // partial last word of the piece before
     int64_t last_tile = first + kZWaveTiles - 1;
     if (last_tile > tiles - 1) last_tile = tiles - 1;
+    const bool all_short = tab.all_short != 0;
+    // A piece (a step of 1024 elements, or a whole tile): every lane has `nbits` bits for it; a
+    // wave prefix sum places them, `walk(put)` appends the lane's codewords with put(bits,
+    // length) into the wave's LDS buffer, which is aligned with the 32-bit words of the stream.
+    // Words wholly inside the wave's range then leave with plain stores and their buffer word is
+    // cleared for the next piece.  The last word of a piece, when partial, is carried into the
+    // first word of the next; only the two ends of the wave's range use atomic ORs.
+    auto write_piece = [&](unsigned int nbits, auto &&walk, bool final_piece) {
+        const unsigned int incl_bits = wave_inclusive_scan(nbits);
+        const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63);
+        const unsigned int shift = (unsigned int)(pos & 31ull);
+        const unsigned long long word0 = pos >> 5;
+        const unsigned long long end = pos + total;
+        const unsigned int span = (total + shift + 31u) >> 5;
+        const int words = (int)(span < (unsigned int)kZBufWords ? span : (unsigned int)kZBufWords);
+        {
+            const unsigned int at = shift + (incl_bits - nbits);
+            int w = (int)(at >> 5);
+            unsigned long long acc = 0;
+            unsigned int held = at & 31u;                      // bits of acc below the next free one
+            auto put = [&](unsigned int piece, unsigned int l) {   // l <= 32, held < 32
+                acc |= (unsigned long long)piece << held;
+                held += l;
+                if (held >= 32u) {
+                    if (w < words) atomicOr(&mine[w], (unsigned int)acc);
+                    ++w;
+                    acc >>= 32;
+                    held -= 32u;
+                }
+            };
+            walk(put);
+            if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+        }
+        wave_lds_sync();
+        const bool has_tail = (end & 31ull) != 0ull;
+        if (words > 0) {
+            unsigned int tail = mine[words - 1];               // same address for all lanes
+            if (words == 1) tail |= carry;
+            for (int j = lane; j < words; j += 64) {
+                unsigned int value = mine[j];
+                mine[j] = 0u;
+                if (j == 0) value |= carry;
+                const unsigned long long gw = word0 + (unsigned long long)j;
+                if (gw >= (unsigned long long)stream_words) continue;
+                const bool lower_ok = gw * 32ull >= range_start;
+                const bool upper_ok = (gw + 1ull) * 32ull <= end;
+                if (lower_ok && upper_ok) out[gw] = value;
+                else if (!upper_ok && !final_piece) continue;  // carried below
+                else if (value) atomicOr(&out[gw], value);
+            }
+            carry = has_tail && !final_piece ? tail : 0u;
+        }
+        wave_lds_sync();                                       // the buffer is clear again for the next piece
+        pos = end;
+    };
+    // One token's codeword, in at most two parts of at most 32 bits.
+    auto put_token = [&](auto &put, int token) {
+        if (all_short) {
+            const unsigned int e = tab.packed[token & 255];
+            put(e & 0xFFFFFFu, e >> 24);
+        } else {
+            unsigned int l = tab.len[token & 255];
+            unsigned long long bits = tab.rev[token & 255];
+            if (l > 32u) {
+                put((unsigned int)bits, 32u);
+                bits >>= 32;
+                l -= 32u;
+            }
+            put((unsigned int)bits, l);
+        }
+    };
+
+    // Sparse tiles (at most half a bit per element) go a whole tile at a time, 64 consecutive
+    // elements per lane: with few tokens the cost of a piece is its scans and its bookkeeping,
+    // and a tile pays them once instead of four times (-13 % at 0.3 bits per element).  Denser
+    // tiles go in steps of 1024 elements, whose bits fit the buffer whatever the code is, and
+    // whose tokens' table entries can be kept between the two walks.
+    // (Ternary codes only: wider codes spend their time finding the non-zero levels of every
+    // element, which a whole tile does not make cheaper.)
+    bool whole_tiles = R == 2;
+    for (int i = 0; i < kZWaveTiles; ++i) {
+        const unsigned int bits_i =
+            (unsigned int)__builtin_amdgcn_readlane((int)my_bits, (int)((first - group * kZGroup + i) & 63));
+        whole_tiles = whole_tiles && bits_i <= kZSparseTileBits;
+    }
+    if (whole_tiles) {
+        TileCodes<R> tc, tc_next;
+        load_tile_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 64, tc_next);
+#pragma unroll 1
+        for (int i = 0; i < kZWaveTiles; ++i) {
+            const int64_t tile = first + i;
+            if (tile > last_tile) break;                       // wave-uniform
+            tc = tc_next;
+            load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, tc_next);
+            const int64_t rest = a.n - tile * kZTile;
+            const int tile_elems = rest < kZTile ? (int)rest : kZTile;
+            const int run = tile_run_in<R>(tc, lane, z);
+            unsigned int nbits = 0;
+            tile_walk<R>(tc, lane, tile_elems, run, z, [&](int token) { nbits += tab.packed[token & 255] >> 24; });
+            write_piece(nbits, [&](auto &put) {
+                tile_walk<R>(tc, lane, tile_elems, run, z, [&](int token) { put_token(put, token); });
+            }, tile == last_tile);
+        }
+        return;
+    }
     int since = 0;
 #pragma unroll 1
     for (int i = 0; i < kZWaveSteps; ++i) {
-        {
-            const int64_t tile = first + (i / kZSteps);
-            const int step = i % kZSteps;
-            const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
-            const int step_valid = step_elements(a.n, step_first);
-            if (tile > last_tile || step_valid == 0) break;    // wave-uniform
-            cd = cd_next;
-            valid = valid_next;
-            valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
-            if (step == 0) since = 0;
-            const int64_t elem = step_first + lane * 16;
-            const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
-            const bool close = closes_tile(a.n, tile, elem, valid);
-            // First walk: the lane's bits; while no codeword is longer than 24 bits the tokens'
-            // table entries are kept (entry k of lane t at [k][t], behind the part of the buffer
-            // such codewords can fill), so the second walk need not find the tokens again.
-            const bool all_short = tab.all_short != 0;
-            unsigned int nbits = 0;
-            int kept = 0;
-            lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
-                const unsigned int e = tab.packed[token & 255];
-                nbits += e >> 24;
-                if (all_short && kept < kZKeepMax) mine[kZKeepAt + kept * 64 + lane] = e;
-                ++kept;
-            });
-            const unsigned int incl_bits = wave_inclusive_scan(nbits);
-            const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63);
-            const unsigned int shift = (unsigned int)(pos & 31ull);
-            const unsigned long long word0 = pos >> 5;
-            const unsigned long long end = pos + total;
-            const unsigned int span = (total + shift + 31u) >> 5;
-            const int words = (int)(span < (unsigned int)kZBufWords ? span : (unsigned int)kZBufWords);
-
-            // The lane's codewords, from buffer bit shift + (bits of the lanes before it).
-            {
-                const unsigned int at = shift + (incl_bits - nbits);
-                int w = (int)(at >> 5);
-                unsigned long long acc = 0;
-                unsigned int held = at & 31u;                  // bits of acc below the next free one
-                auto put = [&](unsigned int piece, unsigned int l) {   // l <= 32, held < 32
-                    acc |= (unsigned long long)piece << held;
-                    held += l;
-                    if (held >= 32u) {
-                        if (w < words) atomicOr(&mine[w], (unsigned int)acc);
-                        ++w;
-                        acc >>= 32;
-                        held -= 32u;
-                    }
-                };
-                if (all_short) {
-                    for (int k = 0; k < kept; ++k) {
-                        const unsigned int e = mine[kZKeepAt + k * 64 + lane];
-                        put(e & 0xFFFFFFu, e >> 24);
-                    }
-                } else {
-                    lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
-                        unsigned int l = tab.len[token & 255];
-                        unsigned long long bits = tab.rev[token & 255];
-                        if (l > 32u) {
-                            put((unsigned int)bits, 32u);
-                            bits >>= 32;
-                            l -= 32u;
-                        }
-                        put((unsigned int)bits, l);
-                    });
+        const int64_t tile = first + (i / kZSteps);
+        const int step = i % kZSteps;
+        const int64_t step_first = first * kZTile + (int64_t)i * kZStep;
+        const int step_valid = step_elements(a.n, step_first);
+        if (tile > last_tile || step_valid == 0) break;        // wave-uniform
+        cd = cd_next;
+        valid = valid_next;
+        valid_next = load_step_codes<R>(crow, a.row_bytes, a.n, step_first + kZStep + lane * 16, cd_next);
+        if (step == 0) since = 0;
+        const int64_t elem = step_first + lane * 16;
+        const int run = lane_run_in<R>(cd, valid, lane, step_valid, since, z);
+        const bool close = closes_tile(a.n, tile, elem, valid);
+        // First walk: the lane's bits; while no codeword is longer than 24 bits the tokens'
+        // table entries are kept (entry k of lane t at [k][t], behind the part of the buffer
+        // such codewords can fill), so the second walk need not find the tokens again.
+        unsigned int nbits = 0;
+        int kept = 0;
+        lane_tokens<R>(cd, valid, run, close, z, [&](int token) {
+            const unsigned int e = tab.packed[token & 255];
+            nbits += e >> 24;
+            if (all_short && kept < kZKeepMax) mine[kZKeepAt + kept * 64 + lane] = e;
+            ++kept;
+        });
+        const bool final_step = tile == last_tile && (step == kZSteps - 1 || step_first + kZStep >= a.n);
+        write_piece(nbits, [&](auto &put) {
+            if (all_short) {
+                for (int k = 0; k < kept; ++k) {
+                    const unsigned int e = mine[kZKeepAt + k * 64 + lane];
+                    put(e & 0xFFFFFFu, e >> 24);
                 }
-                if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
+            } else {
+                lane_tokens<R>(cd, valid, run, close, z, [&](int token) { put_token(put, token); });
             }
-            wave_lds_sync();
-
-            // Words wholly inside the wave's range leave with plain stores and their buffer word
-            // is cleared for the next step.  The last word of a step, when partial, is carried
-            // into the first word of the next step; only the two ends of the range use atomic ORs.
-            const bool final_step = tile == last_tile && (step == kZSteps - 1 || step_first + kZStep >= a.n);
-            const bool has_tail = (end & 31ull) != 0ull;
-            if (words > 0) {
-                unsigned int tail = mine[words - 1];           // same address for all lanes
-                if (words == 1) tail |= carry;
-                for (int j = lane; j < words; j += 64) {
-                    unsigned int value = mine[j];
-                    mine[j] = 0u;
-                    if (j == 0) value |= carry;
-                    const unsigned long long gw = word0 + (unsigned long long)j;
-                    if (gw >= (unsigned long long)stream_words) continue;
-                    const bool lower_ok = gw * 32ull >= range_start;
-                    const bool upper_ok = (gw + 1ull) * 32ull <= end;
-                    if (lower_ok && upper_ok) out[gw] = value;
-                    else if (!upper_ok && !final_step) continue;   // carried below
-                    else if (value) atomicOr(&out[gw], value);
-                }
-                carry = has_tail && !final_step ? tail : 0u;
-            }
-            wave_lds_sync();                                   // the buffer is clear again for the next step
-            pos = end;
-        }
+        }, final_step);
     }
 }
 

@@ -146,6 +146,56 @@ def test_zrun_long_codewords(E):
     _roundtrip(E, q, s)
 
 
+def test_zrun_long_codewords_in_sparse_tiles(E):
+    """Codewords of up to 47 bits, from a prefix code given to the coder instead of its own
+    Huffman code (lengths 1, 2, ..., 39 by falling token count, 47 for the rest: Kraft's sum stays
+    below 1), on a message whose first part is dense and whose second part has runs of 111 to 126
+    zeros: the encoder writes sparse tiles a whole tile at a time and dense ones in steps, and
+    in both appends codewords longer than 32 bits in two parts; the decoder walks the canonical
+    code beyond its table and beyond 32 bits.  Sizes, offsets and stream against the oracle's
+    encoder with the same code, then decode(encode(message)) = message."""
+    s = 1
+    fib = [1, 1]
+    while len(fib) < 30:
+        fib.append(fib[-1] + fib[-2])
+    rng = np.random.default_rng(11)
+    runs_of = [126 - k if k < 16 else 29 - k for k in range(30)]      # zeros before the level of token k
+    dense = np.repeat([runs_of[k] for k in range(16, 30)], [fib[k] for k in range(16, 30)])
+    sparse = np.repeat([runs_of[k] for k in range(16)], [40 * fib[k] for k in range(16)])
+    rng.shuffle(dense)
+    rng.shuffle(sparse)
+    reps = np.concatenate([dense, sparse]).astype(np.int64)
+    N = int((reps + 1).sum())
+    q = np.zeros((1, N), np.int8)
+    q[0, np.cumsum(reps + 1) - 1] = 1
+    counts = oracle.zrun_histogram(q[0], s)
+    order = np.argsort(-counts.astype(np.int64), kind="stable")
+    lengths = np.zeros(len(counts), np.uint8)
+    lengths[order] = [min(rank + 1, 39) if rank < 39 else 47 for rank in range(len(counts))]
+    codewords = oracle.huffman_codes(lengths)
+    assert sum(2.0 ** -int(l) for l in lengths) <= 1.0
+    ref_stream, ref_bits, ref_groups, bits = oracle.zrun_encode(q[0], s, lengths, codewords)
+    assert int(ref_bits.min()) <= 2048 < int(ref_bits.max())          # sparse tiles and dense ones
+    st = GpuState(E, 1, N, 512, s)
+    codes_ref = oracle.pack_rows(q, s)
+    st.codes[:, : st.rb] = _dev(codes_ref)
+    zb = ZrunBuffers(E, 1, N, s)
+    zb.lengths[0, : zb.symbols] = _dev(lengths)
+    zb.codewords[0, : zb.symbols] = _dev(codewords.view(np.int64))
+    E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                      zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+    back = torch.full_like(st.codes, 0xEE)
+    E.ecq_zrun_decode(st.sh, zb.streams, zb.stream_stride, zb.tile_bits, zb.tile_stride, zb.group_offsets,
+                      zb.group_stride, zb.lengths, zb.codewords, zb.table_stride, back)
+    torch.cuda.synchronize()
+    assert (bits + 7) // 8 <= zb.stream_stride
+    assert np.array_equal(zb.tile_bits[0, : zb.tiles].cpu().numpy().view(np.uint32), ref_bits)
+    assert np.array_equal(zb.group_offsets[0, : zb.groups + 1].cpu().numpy().view(np.uint64), ref_groups)
+    nbytes = (bits + 7) // 8
+    assert np.array_equal(zb.streams[0, :nbytes].cpu().numpy(), ref_stream[:nbytes]), "stream differs"
+    assert torch.equal(back[:, : st.rb].cpu(), torch.from_numpy(codes_ref)), "decode(encode(message)) differs"
+
+
 def test_zrun_decodes_an_oracle_stream(E):
     """The library's decoder on a stream, index and tables written by the oracle."""
     s, P, N = 3, 2, 64 * 4096 + 3000
