@@ -76,6 +76,26 @@ struct NonZero {
         if constexpr (R == 2) {
             // s = 1: codes 0 and 2 are the levels -1 and +1, code 1 is level 0, code 3 is off the grid.
             return ~cd.w[0] & 0x55555555u;
+        } else if constexpr (R == 4) {
+            // Eight codes per word, tested side by side: a nibble differs from s iff its XOR with s
+            // is not zero (bit 3 of ((y & 7) + 7) | y); it exceeds 2s iff adding 15 - 2s carries
+            // out of it (low and high nibbles of the bytes apart, so no carry crosses).  The
+            // eight flags of a word are then gathered into eight neighbouring bits.
+            const uint32_t every = 0x11111111u * (uint32_t)s, room = 0x01010101u * (uint32_t)(15 - 2 * s);
+            uint32_t m = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t x = cd.w[i], y = x ^ every;
+                const uint32_t differs = ((((y & 0x77777777u) + 0x77777777u) | y) >> 3) & 0x11111111u;
+                const uint32_t low_over = (((x & 0x0F0F0F0Fu) + room) >> 4) & 0x01010101u;
+                const uint32_t high_over = ((x >> 4) & 0x0F0F0F0Fu) + room;      // flag at bit 4 of each byte
+                uint32_t f = differs & ~(low_over | (high_over & 0x10101010u));   // flag of element e at bit 4e
+                f = (f | (f >> 3)) & 0x03030303u;
+                f = (f | (f >> 6)) & 0x000F000Fu;
+                f = (f | (f >> 12)) & 0xFFu;
+                m |= f << (8 * i);
+            }
+            return m;
         } else {
             uint32_t m = 0;
 #pragma unroll
@@ -94,6 +114,8 @@ __device__ __forceinline__ int code_at(const Codes16<R> &cd, int pos)
 {
     if constexpr (R == 2) {
         return (int)((cd.w[0] >> (2 * pos)) & 3u);
+    } else if constexpr (R == 4) {
+        return (int)(((pos < 8 ? cd.w[0] : cd.w[1]) >> (4 * (pos & 7))) & 15u);
     } else {
         const int bit = R * pos, i = bit >> 5, sh = bit & 31;
         uint32_t lo = 0, hi = 0;

@@ -365,3 +365,47 @@ def test_zrun_decoder_tiles_per_wave(E, P, tiles, s):
     E.ecq_huffman_decode(st.sh, hstreams, st.sh.code_stride, offs, htiles + 1, hlen, hwords, bins, back)
     torch.cuda.synchronize()
     assert torch.equal(back[:, : st.rb].cpu(), torch.from_numpy(codes_ref)), "per-level decode(encode(message)) differs"
+
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 7, 20])
+def test_zrun_codes_beyond_the_grid_count_as_level_zero(E, s):
+    """r-bit patterns above 2s (no message of this library holds one) are tokenised as level 0:
+    a message with such codes planted in it gives the token counts, tile sizes and stream of
+    the same message with the code of level 0 in their place.  (The oracle works on levels and
+    cannot hold such a code; the reference here is the library on the cleaned message, whose
+    products are compared with the oracle's by the other tests.)"""
+    r = E.code_bits(s)
+    if 2 * s + 1 == (1 << r):
+        pytest.skip("every r-bit pattern is a level")
+    rng = np.random.default_rng(s)
+    P, N = 2, 3 * 64 * 4096 + 1000
+    q = _levels(rng, P, N, s, 0.2)
+    clean = oracle.pack_rows(q, s)
+    # plant codes beyond the grid in one element out of 50
+    codes = np.zeros((P, N), np.int64) + (q.astype(np.int64) + s)
+    planted = rng.random((P, N)) < 0.02
+    codes_bad = np.where(planted, rng.integers(2 * s + 1, 1 << r, (P, N)), codes)
+    codes_clean = np.where(planted, s, codes)
+    def pack(c):
+        out = np.zeros((P, clean.shape[1]), np.uint8)
+        for p in range(P):
+            bits = ((c[p][:, None] >> np.arange(r)) & 1).astype(np.uint8).reshape(-1)
+            packed = np.packbits(bits, bitorder="little")
+            out[p, : len(packed)] = packed
+        return out
+    assert np.array_equal(pack(codes), clean)                   # the packer above is the oracle's layout
+    results = []
+    for message in (pack(codes_bad), pack(codes_clean)):
+        st = GpuState(E, P, N, 512, s)
+        st.codes[:, : st.rb] = _dev(message)
+        zb = ZrunBuffers(E, P, N, s)
+        E.ecq_zrun_histogram(st.sh, st.codes, zb.counts, zb.table_stride)
+        E.ecq_zrun_build(P, s, zb.counts, zb.table_stride, zb.lengths, zb.codewords)
+        E.ecq_zrun_encode(st.sh, st.codes, zb.lengths, zb.codewords, zb.table_stride, zb.streams, zb.stream_stride,
+                          zb.tile_bits, zb.tile_stride, zb.group_offsets, zb.group_stride)
+        torch.cuda.synchronize()
+        total = int(zb.group_offsets[0, zb.groups].item())
+        results.append((zb.counts[:, : zb.symbols].cpu().numpy(), zb.tile_bits[:, : zb.tiles].cpu().numpy(),
+                        zb.streams[0, : (total + 7) // 8].cpu().numpy()))
+    for got, ref in zip(results[0], results[1]):
+        assert np.array_equal(got, ref)
