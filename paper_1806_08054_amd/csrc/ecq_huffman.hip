@@ -929,7 +929,15 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
     int in_batch = 4;
     auto take = [&]() -> unsigned int {
         if (in_batch == 0) {
-            batch = batch_ahead;
+            // The batch in flight becomes the current one through moves that cannot sink below the
+            // new loads (the loads' address passes through them), so that its registers are free to
+            // receive those loads.  Left to the compiler the old values stay live across the loads,
+            // the new ones land in other registers and are copied into place at once, which waits
+            // for them to arrive: a memory round trip in most rounds of a wave, since its lanes run
+            // out of words at different times.
+            asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8"
+                         : "=v"(batch.x), "=v"(batch.y), "=v"(batch.z), "=v"(batch.w), "+v"(next_word)
+                         : "v"(batch_ahead.x), "v"(batch_ahead.y), "v"(batch_ahead.z), "v"(batch_ahead.w));
             batch_ahead = fetch4();
             in_batch = 4;
         }

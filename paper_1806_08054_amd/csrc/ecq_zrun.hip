@@ -1241,9 +1241,11 @@ hipError_t launch_zrun_decode(const Args &a, const uint8_t *lengths, const unsig
                               int64_t group_stride, hipStream_t stream)
 {
     const int64_t tiles = (a.n + kZTile - 1) / kZTile;
-    // Tiles per wave: 64, halved while twice the waves are still no more than the chip holds at
-    // once (four blocks per compute unit), down to 8.
-    const int64_t held = (int64_t)256 * 4 * 4;
+    // Tiles per wave: 64, halved while that still gives every SIMD at most two waves, down to 8:
+    // decoding is bound by the instructions a SIMD issues, and a wave costs the same whether 8 or
+    // 64 of its lanes decode; only a message too small to give every SIMD work gains from more
+    // waves (each a shorter wait for the slowest of its tiles).
+    const int64_t held = (int64_t)256 * 4 * 2;
     int lanes_shift = 0;
     while (lanes_shift < 3 && cdiv(tiles, kZGroup >> (lanes_shift + 1)) * a.workers <= held) ++lanes_shift;
     const dim3 grid(cdiv(cdiv(tiles, kZGroup) << lanes_shift, 4), (unsigned)a.workers);

@@ -319,7 +319,7 @@ def test_zrun_full_size(E, name, rows):
               f"fixed length {E.code_bits(s)}", flush=True)
 
 
-@pytest.mark.parametrize("P,tiles,s", [(1, 300, 1), (2, 20_000, 4), (2, 40_000, 1), (3, 50_000, 2)])
+@pytest.mark.parametrize("P,tiles,s", [(1, 300, 1), (2, 10_000, 4), (2, 20_000, 1), (3, 50_000, 2)])
 def test_zrun_decoder_tiles_per_wave(E, P, tiles, s):
     """The decoder gives a wave 8, 16, 32 or 64 tiles depending on how many tiles the whole
     message has (the four cases, in that order), the per-level decoder between 8 and 64: every
