@@ -818,7 +818,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
 {
     constexpr int kPeriod = R == 2 || R == 4 || R == 8 ? 1 : (R == 6 ? 3 : R);   // words after which zero_words repeat
     __shared__ ZDecodeTable tab;
-    __shared__ unsigned int out_ring[kZRingWords * 256];
+    __shared__ unsigned int out_ring[(kZRingWords + 1) * 256];
     const ZrunShape z = zrun_shape(a.s);
     const uint32_t p = blockIdx.y;
     fill_zdecode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
@@ -843,7 +843,6 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     if (lane >= lanes || tile >= tiles) return;
     const int64_t elem0 = tile * kZTile;
     const int tile_elems = (int)((a.n - elem0) < kZTile ? (a.n - elem0) : (int64_t)kZTile);
-    int remaining = tile_elems;
     const uint32_t *__restrict__ in = streams + (int64_t)p * stream_stride_words;
     uint8_t *__restrict__ crow = a.codes + (int64_t)p * a.code_stride;
     int64_t out_byte = (elem0 >> 3) * R;                       // a multiple of 512*R: 4-byte aligned in the row
@@ -900,12 +899,34 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
 
     // The output window: words [w0, w0 + kZRingWords) of the tile's part of the row, the same w0
     // for every lane of the wave.  Word k of lane t at [k][t]: whatever words the lanes of a wave
-    // touch, they lie in 64 different banks.
+    // touch, they lie in 64 different banks.  When codes can straddle two words the window has
+    // one more word, the first of the next window: an element belongs to the window in which it
+    // begins, and what it leaves in that extra word moves on to the next window's word 0.
+    constexpr bool kStraddle = (32 % R) != 0;
     unsigned int *__restrict__ ring = out_ring + threadIdx.x;
-    auto fill_window = [&](int w0) {
+    auto start_window = [&](int w0) {                          // w0 is the same for the whole wave
+        if constexpr (kStraddle) {
+            ring[0] = w0 > 0 ? ring[kZRingWords * 256] : tab.zero_words[0];
 #pragma unroll
-        for (int k = 0; k < kZRingWords; ++k)
-            ring[k * 256] = tab.zero_words[kPeriod == 1 ? 0 : (w0 + k) % kPeriod];
+            for (int k = 1; k <= kZRingWords; ++k) ring[k * 256] = tab.zero_words[(w0 + k) % kPeriod];
+        } else {
+#pragma unroll
+            for (int k = 0; k < kZRingWords; ++k)
+                ring[k * 256] = tab.zero_words[kPeriod == 1 ? 0 : (w0 + k) % kPeriod];
+        }
+    };
+    // XORs d into element e's field (d == 0: no change).  Only the row within the window is
+    // formed from e, so an element outside the window (always with d == 0) touches some row of
+    // the lane's own.
+    auto put = [&](unsigned int e, unsigned int d) {
+        const unsigned int bit = e * R, row = (bit >> 5) & (unsigned int)(kZRingWords - 1);
+        if constexpr (kStraddle) {
+            const unsigned long long v = (unsigned long long)d << (bit & 31u);
+            atomicXor(&ring[row * 256], (unsigned int)v);
+            atomicXor(&ring[(row + 1) * 256], (unsigned int)(v >> 32));
+        } else {
+            atomicXor(&ring[row * 256], d << (bit & 31u));
+        }
     };
     // The bounds of the lengths 13..31 and of length 32, in registers.
     unsigned int last[32 - (kZFastBits + 1)];
@@ -945,247 +966,116 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
             out_byte += 4 * count;
         }
     };
-    if constexpr (R == 2 || R == 4) {
-        // Codes of 2 and 4 bits (an element never straddles two words).  The steps of a token are
-        // written without branches: the lanes of a wave are at different tokens, so a branch that one
-        // lane takes costs all of them, and decoding is bound by the number of instructions issued.
-        //  - the next 32 stream bits are bits [bp, bp + 32) of nxt:cur, bp < 32; a lookup consumes at
-        //    most 12 bits (32 for a long codeword), then the pair moves on by a word where due;
-        //  - a token whose level lies beyond the window is not taken: it stays in the stream and is
-        //    looked up again in the next window (runs are shorter than a window, so it fits there);
-        //  - the second token of an entry is taken when its zeros and one more element fit the
-        //    window and the tile;
-        //  - words that get no level are XORed with 0.
-        constexpr int kPerWord = 32 / R;
-        unsigned int cur = batch.x, nxt = batch.y, bp = (unsigned int)(start & 31ull);
-        batch.x = batch.z;
-        batch.y = batch.w;
-        in_batch = 2;
-        auto advance = [&]() {
-            const bool step = bp >= 32u;
-            cur = step ? nxt : cur;
-            nxt = step ? batch.x : nxt;
-            batch.x = step ? batch.y : batch.x;
-            batch.y = step ? batch.z : batch.y;
-            batch.z = step ? batch.w : batch.z;
-            in_batch -= step ? 1 : 0;
-            bp &= 31u;
-            if (in_batch == 0) next_batch();
-        };
-        unsigned int at = 0;                                       // elements decoded so far
-        int held_word = -1;                                        // only codewords beyond 32 bits leave a level behind
-        unsigned int held_bits = 0u;
-        fill_window(0);
-    #pragma unroll 1
-        for (int w0 = 0; w0 < kZTile * R / 32; w0 += kZRingWords) {
-            const int w_end = w0 + kZRingWords;
-            const unsigned int limit = (unsigned int)(w_end * kPerWord < tile_elems ? w_end * kPerWord : tile_elems);
-            if (held_word >= 0 && held_word < w_end) {
-                atomicXor(&ring[(held_word - w0) * 256], held_bits);
-                held_word = -1;
-            }
-            bool blocked = false;
-            while (at < limit && !blocked) {
-                const unsigned int bits = __builtin_amdgcn_alignbit(nxt, cur, bp);
-                const unsigned int hit = tab.fast[bits & ((1u << kZFastBits) - 1u)];
-                unsigned int len1 = hit & 15u, zeros1 = (hit >> 4) & 127u, d1 = (hit >> 11) & 15u;
-                const unsigned int second = hit >> 16;
-                if (hit == 0u) {
-                    // Longer than the table covers: its length from the bounds, then its place among the
-                    // codewords of that length.
-                    const unsigned int top = __brev(bits);
-                    int l = kZFastBits + 1;
-    #pragma unroll
-                    for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
-                    if (top <= last32) {
-                        const unsigned int info = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
-                        len1 = (unsigned int)l;
-                        zeros1 = info >> 8;
-                        d1 = info & 255u;
-                    } else {
-                        // Beyond 32 bits: one bit at a time, the token applied here.  (A stream that is not of
-                        // this code may end up here as well and comes out as "Z zeros" tokens.)
-                        unsigned int token = (unsigned int)z.zz;
-                        unsigned long long word = top;
-                        bp += 32u;
-                        advance();
-                        for (l = 33; l <= kZMaxLen; ++l) {
-                            word = (word << 1) | (unsigned long long)((cur >> bp) & 1u);
-                            ++bp;
-                            advance();
-                            const unsigned long long idx = word - tab.first_code[l];
-                            if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
-                                token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
-                                break;
-                            }
-                        }
-                        const unsigned int info = tab.info[token];
-                        const unsigned int room = (unsigned int)tile_elems - at;   // > 0 inside this loop
-                        at += (info >> 8) < room ? (info >> 8) : room;
-                        if ((info & 255u) != 0u && at < (unsigned int)tile_elems) {
-                            const int bit = (int)at * R, level_word = bit >> 5;
-                            if (level_word < w_end) {
-                                atomicXor(&ring[(level_word - w0) * 256], (info & 255u) << (bit & 31));
-                            } else {
-                                held_word = level_word;
-                                held_bits = (info & 255u) << (bit & 31);
-                            }
-                            ++at;
-                        }
-                        continue;
-                    }
-                }
-                // (A token that closes a tile has its level beyond the tile's end: it is never taken, and
-                // nothing follows it.  An entry without a second token has zeros there: taking it changes
-                // nothing.  After a blocked token the test of the second one fails by itself.)
-                const unsigned int end1 = at + zeros1;             // where the token's level goes
-                const bool put1 = d1 != 0u && end1 < limit;
-                blocked = d1 != 0u && end1 >= limit;
-                atomicXor(&ring[((end1 / kPerWord) & (kZRingWords - 1)) * 256], put1 ? d1 << ((end1 * R) & 31u) : 0u);
-                const unsigned int at1 = end1 + (put1 ? 1u : 0u);
-                const unsigned int zeros2 = (second >> 4) & 127u, d2 = (second >> 11) & 15u;
-                const unsigned int end2 = at1 + zeros2;
-                const bool take2 = end2 < limit;
-                atomicXor(&ring[((end2 / kPerWord) & (kZRingWords - 1)) * 256], take2 ? d2 << ((end2 * R) & 31u) : 0u);
-                const unsigned int at2 = end2 + (d2 != 0u ? 1u : 0u);
-                at = blocked ? at : (take2 ? at2 : at1);
-                bp += (blocked ? 0u : len1) + (take2 ? second & 15u : 0u);
-                advance();
-            }
-            leave_window(w0);
-            fill_window(w_end);
+    // The steps of a token are written without branches: the lanes of a wave are at different
+    // tokens, so a branch that one lane takes costs all of them, and decoding is bound by the
+    // number of instructions issued.
+    //  - the next 32 stream bits are bits [bp, bp + 32) of nxt:cur, bp < 32; a lookup consumes at
+    //    most 12 bits (32 for a long codeword), then the pair moves on by a word where due;
+    //  - a token whose level begins beyond the window is not taken: it stays in the stream and is
+    //    looked up again in the next window (runs are shorter than a window, so it fits there);
+    //  - the second token of an entry is taken when its zeros and one more element fit the
+    //    window and the tile;
+    //  - words that get no level are XORed with 0.
+    unsigned int cur = batch.x, nxt = batch.y, bp = (unsigned int)(start & 31ull);
+    batch.x = batch.z;
+    batch.y = batch.w;
+    in_batch = 2;
+    auto advance = [&]() {
+        const bool step = bp >= 32u;
+        cur = step ? nxt : cur;
+        nxt = step ? batch.x : nxt;
+        batch.x = step ? batch.y : batch.x;
+        batch.y = step ? batch.z : batch.y;
+        batch.z = step ? batch.w : batch.z;
+        in_batch -= step ? 1 : 0;
+        bp &= 31u;
+        if (in_batch == 0) next_batch();
+    };
+    unsigned int at = 0;                                       // elements decoded so far
+    int held_word = -1;                                        // only codewords beyond 32 bits leave a level behind
+    unsigned long long held_bits = 0ull;
+    start_window(0);
+#pragma unroll 1
+    for (int w0 = 0; w0 < kZTile * R / 32; w0 += kZRingWords) {
+        const int w_end = w0 + kZRingWords;
+        const int begin_here = (w_end * 32 + R - 1) / R;     // elements that begin before the window's end
+        const unsigned int limit = (unsigned int)(begin_here < tile_elems ? begin_here : tile_elems);
+        if (held_word >= 0 && held_word < w_end) {
+            atomicXor(&ring[(held_word - w0) * 256], (unsigned int)held_bits);
+            if constexpr (kStraddle) atomicXor(&ring[(held_word - w0 + 1) * 256], (unsigned int)(held_bits >> 32));
+            held_word = -1;
         }
-    } else {
-        // Bit reservoir: `have` valid bits, the next stream bit is bit 0.
-        auto take = [&]() -> unsigned int {
-            if (in_batch == 0) next_batch();
-            const unsigned int wv = batch.x;
-            batch.x = batch.y; batch.y = batch.z; batch.z = batch.w;
-            --in_batch;
-            return wv;
-        };
-        unsigned long long res = take();
-        unsigned int have = 32u;
-        auto refill = [&]() {
-            if (have <= 32u) {
-                res |= (unsigned long long)take() << have;
-                have += 32u;
-            }
-        };
-        {
-            const unsigned int skip = (unsigned int)(start & 31ull);
-            res >>= skip;
-            have -= skip;
-        }
-
-        int at = 0;                                                // elements decoded so far
-        // What a token decoded in one window leaves for a later one: the XOR of its level's code.
-        int held_word = -1, held_word2 = -1;
-        unsigned int held_bits = 0u, held_bits2 = 0u;
-        fill_window(0);
-    #pragma unroll 1
-        for (int w0 = 0; w0 < kZTile * R / 32; w0 += kZRingWords) {
-            const int w_end = w0 + kZRingWords;
-            if (held_word >= 0 && held_word < w_end) {
-                atomicXor(&ring[(held_word - w0) * 256], held_bits);
-                held_word = -1;
-            }
-            if ((32 % R) != 0 && held_word2 >= 0 && held_word2 < w_end) {
-                atomicXor(&ring[(held_word2 - w0) * 256], held_bits2);
-                held_word2 = -1;
-            }
-            // Tokens while the lane's next element lies in this window.
-            while (remaining > 0 && held_word < 0 && ((at * R) >> 5) < w_end) {
-                refill();
-                const unsigned int hit = tab.fast[(unsigned int)res & ((1u << kZFastBits) - 1u)];
-                unsigned int entry, second = 0u;                   // entry: (zeros << 8) | d
-                if (hit) {
-                    res >>= (hit & 15u);
-                    have -= (hit & 15u);
-                    entry = ((hit << 4) & 0x7F00u) | (R <= 4 ? (hit >> 11) & 15u : (hit >> 16) & 255u);
-                    if constexpr (R <= 4) second = hit >> 16;
+        bool blocked = false;
+        while (at < limit && !blocked) {
+            const unsigned int bits = __builtin_amdgcn_alignbit(nxt, cur, bp);
+            const unsigned int hit = tab.fast[bits & ((1u << kZFastBits) - 1u)];
+            unsigned int len1 = hit & 15u, zeros1 = (hit >> 4) & 127u;
+            unsigned int d1 = R <= 4 ? (hit >> 11) & 15u : (hit >> 16) & 255u;
+            const unsigned int second = R <= 4 ? hit >> 16 : 0u;
+            if (hit == 0u) {
+                // Longer than the table covers: its length from the bounds, then its place among the
+                // codewords of that length.
+                const unsigned int top = __brev(bits);
+                int l = kZFastBits + 1;
+#pragma unroll
+                for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
+                if (top <= last32) {
+                    const unsigned int info = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
+                    len1 = (unsigned int)l;
+                    zeros1 = info >> 8;
+                    d1 = info & 255u;
                 } else {
-                    // Longer than the table covers: its length from the bounds, then its place among the
-                    // codewords of that length.
-                    if (have < 32u) refill();
-                    const unsigned int top = __brev((unsigned int)res);
-                    int l = kZFastBits + 1;
-    #pragma unroll
-                    for (int j = 0; j < 32 - (kZFastBits + 1); ++j) l += top > last[j] ? 1 : 0;
-                    if (top <= last32) {
-                        entry = tab.sorted_info[((top >> (32 - l)) + tab.delta[l]) & 255u];
-                        res >>= l;
-                        have -= (unsigned int)l;
-                    } else {
-                        // Beyond 32 bits: one bit at a time.  (A stream that is not of this code may end up
-                        // here as well and comes out as "Z zeros" tokens.)
-                        unsigned int token = (unsigned int)z.zz;
-                        unsigned long long word = top;
-                        res >>= 32;
-                        have -= 32u;
-                        for (l = 33; l <= kZMaxLen; ++l) {
-                            if (have == 0u) refill();
-                            word = (word << 1) | (res & 1ull);
-                            res >>= 1;
-                            --have;
-                            const unsigned long long idx = word - tab.first_code[l];
-                            if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
-                                token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
-                                break;
-                            }
+                    // Beyond 32 bits: one bit at a time, the token applied here.  (A stream that is not of
+                    // this code may end up here as well and comes out as "Z zeros" tokens.)
+                    unsigned int token = (unsigned int)z.zz;
+                    unsigned long long word = top;
+                    bp += 32u;
+                    advance();
+                    for (l = 33; l <= kZMaxLen; ++l) {
+                        word = (word << 1) | (unsigned long long)((cur >> bp) & 1u);
+                        ++bp;
+                        advance();
+                        const unsigned long long idx = word - tab.first_code[l];
+                        if (tab.count[l] && word >= tab.first_code[l] && idx < tab.count[l]) {
+                            token = tab.sorted[(tab.base[l] + (unsigned int)idx) & 255u];
+                            break;
                         }
-                        entry = tab.info[token];
                     }
-                }
-                int zeros = (int)((entry >> 8) & 0xFFu);
-                const unsigned int delta = entry & 0xFFu;
-                zeros = zeros < remaining ? zeros : remaining;
-                at += zeros;
-                remaining -= zeros;
-                if (delta != 0u && remaining > 0) {
-                    // The window holds the code of level 0 (s) here: XOR turns it into the level's code.
-                    const int bit = at * R, word = bit >> 5, sh = bit & 31;
-                    if (word < w_end) {
-                        atomicXor(&ring[(word - w0) * 256], delta << sh);
-                    } else {
-                        held_word = word;
-                        held_bits = delta << sh;
-                    }
-                    if ((32 % R) != 0 && sh + R > 32) {            // the field straddles two words
-                        if (word + 1 < w_end) {
-                            atomicXor(&ring[(word + 1 - w0) * 256], delta >> (32 - sh));
+                    const unsigned int info = tab.info[token];
+                    const unsigned int room = (unsigned int)tile_elems - at;   // > 0 inside this loop
+                    at += (info >> 8) < room ? (info >> 8) : room;
+                    if ((info & 255u) != 0u && at < (unsigned int)tile_elems) {
+                        const int bit = (int)at * R, level_word = bit >> 5;
+                        if (level_word < w_end) {
+                            put(at, info & 255u);
                         } else {
-                            held_word2 = word + 1;
-                            held_bits2 = delta >> (32 - sh);
+                            held_word = level_word;
+                            held_bits = (unsigned long long)(info & 255u) << (bit & 31);
                         }
+                        ++at;
                     }
-                    ++at;
-                    --remaining;
-                }
-                if constexpr (R <= 4) {
-                    // The second token of the lookup, taken only when it lies wholly inside the tile
-                    // and the window (else its codeword stays in the stream for the next lookup).
-                    if (second != 0u && held_word < 0) {
-                        const int zeros2 = (int)((second >> 4) & 127u);
-                        const unsigned int delta2 = (second >> 11) & 15u;
-                        const int level_at = at + zeros2, covers = zeros2 + (delta2 != 0u ? 1 : 0);
-                        if (covers <= remaining && ((level_at * R + (R - 1)) >> 5) < w_end) {
-                            res >>= (second & 15u);
-                            have -= (second & 15u);
-                            if (delta2 != 0u) {
-                                const int bit = level_at * R, word = bit >> 5, sh = bit & 31;
-                                atomicXor(&ring[(word - w0) * 256], delta2 << sh);
-                                if ((32 % R) != 0 && sh + R > 32) atomicXor(&ring[(word + 1 - w0) * 256], delta2 >> (32 - sh));
-                            }
-                            at += covers;
-                            remaining -= covers;
-                        }
-                    }
+                    continue;
                 }
             }
-            leave_window(w0);
-            fill_window(w_end);
+            // (A token that closes a tile has its level beyond the tile's end: it is never taken, and
+            // nothing follows it.  An entry without a second token has zeros there: taking it changes
+            // nothing.  After a blocked token the test of the second one fails by itself.)
+            const unsigned int end1 = at + zeros1;             // where the token's level goes
+            const bool put1 = d1 != 0u && end1 < limit;
+            blocked = d1 != 0u && end1 >= limit;
+            put(end1, put1 ? d1 : 0u);
+            const unsigned int at1 = end1 + (put1 ? 1u : 0u);
+            const unsigned int zeros2 = (second >> 4) & 127u, d2 = (second >> 11) & 15u;
+            const unsigned int end2 = at1 + zeros2;
+            const bool take2 = end2 < limit;
+            put(end2, take2 ? d2 : 0u);
+            const unsigned int at2 = end2 + (d2 != 0u ? 1u : 0u);
+            at = blocked ? at : (take2 ? at2 : at1);
+            bp += (blocked ? 0u : len1) + (take2 ? second & 15u : 0u);
+            advance();
         }
+        leave_window(w0);
+        start_window(w_end);
     }
 }
 
