@@ -936,7 +936,7 @@ __global__ void __launch_bounds__(kDecodeThreads) k_huffman_decode(const Args a,
             // for them to arrive: a memory round trip in most rounds of a wave, since its lanes run
             // out of words at different times.
             asm volatile("v_mov_b32 %0, %5\n\tv_mov_b32 %1, %6\n\tv_mov_b32 %2, %7\n\tv_mov_b32 %3, %8"
-                         : "=v"(batch.x), "=v"(batch.y), "=v"(batch.z), "=v"(batch.w), "+v"(next_word)
+                         : "=&v"(batch.x), "=&v"(batch.y), "=&v"(batch.z), "=&v"(batch.w), "+v"(next_word)
                          : "v"(batch_ahead.x), "v"(batch_ahead.y), "v"(batch_ahead.z), "v"(batch_ahead.w));
             batch_ahead = fetch4();
             in_batch = 4;
