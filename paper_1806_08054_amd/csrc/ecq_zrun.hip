@@ -244,6 +244,13 @@ template <int R>
 __device__ __forceinline__ void load_tile_codes(const uint8_t *__restrict__ crow, int64_t row_bytes, int64_t n,
                                                 int64_t elem, TileCodes<R> &t)
 {
+    if (n - elem >= 64) {                                      // every lane of a tile inside the row
+        const uint8_t *at = crow + ((elem * R) >> 3);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) t.q[k].load(at + 2 * R * k);
+        t.valid = 64;
+        return;
+    }
     int valid = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) valid += load_step_codes<R>(crow, row_bytes, n, elem + 16 * k, t.q[k]);
