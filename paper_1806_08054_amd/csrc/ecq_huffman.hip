@@ -54,9 +54,10 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
                                                      uint8_t *__restrict__ lengths,
                                                      unsigned long long *__restrict__ codewords)
 {
-    __shared__ unsigned long long weight[512];
+    __shared__ unsigned long long weight[256];                 // of the levels
     __shared__ unsigned long long first_code[64];
-    __shared__ unsigned long long leaf_key[256];               // occupied levels in the order (weight, number)
+    __shared__ unsigned long long leaf_key[256 + 4];           // occupied levels in the order (weight, number), then ~0
+    __shared__ unsigned long long made_key[256 + 4];           // merged nodes in the order they are made, then ~0
     __shared__ unsigned long long node_key[256];               // every level's key, ~0 when it does not occur
     __shared__ unsigned int len_count[64];
     __shared__ short parent[512];
@@ -65,7 +66,7 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     const int lane = threadIdx.x;
     const int64_t row = (int64_t)blockIdx.x * table_stride;
     for (int i = lane; i < 512; i += 64) {
-        weight[i] = i < bins ? counts[row + i] : 0ull;
+        if (i < 256) weight[i] = i < bins ? counts[row + i] : 0ull;
         parent[i] = -1;
     }
     len_count[lane] = 0u;
@@ -102,6 +103,10 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     }
     for (int d = 1; d < 64; d <<= 1) alive += __shfl_xor(alive, d, 64);
     const bool single = alive == 1;
+    for (int i = lane; i < 256 + 4; i += 64) {                  // (ranks stay below `alive`: no entry is written twice)
+        if (i >= alive) leaf_key[i] = ~0ull;
+        made_key[i] = ~0ull;
+    }
     __syncthreads();
 
     // The two nodes that come first in the order (weight, number) are merged into a node with
@@ -109,56 +114,79 @@ __global__ void __launch_bounds__(64) k_huffman_build(const unsigned long long *
     // merged nodes come into being in that very order (their weights never decrease, their
     // numbers grow), so the first of all live nodes is always the first leaf not yet taken or
     // the first merged node not yet taken: one lane walks the two queues.
-    // The walk is a chain of dependent steps, so the first two keys of each queue travel in
-    // registers and the entries behind them are requested from LDS two picks before they can be
-    // needed.  A key holds the node's weight: nothing else is read back.
+    // The walk is a chain of dependent steps of one lane, so it is written without branches and
+    // without waits: the first two keys of each queue travel in registers, the third is requested
+    // from LDS a pick before it can be needed (both queues, whichever moves), and a node made
+    // while such a request is in flight is put in its place from registers.  A key holds the
+    // node's weight: nothing else is read back.
     if (lane == 0) {
-        const unsigned long long none = ~0ull;
         int next_leaf = 0, next_made = 0, made = 0;
-        unsigned long long l0 = alive > 0 ? leaf_key[0] : none, l1 = alive > 1 ? leaf_key[1] : none;
-        unsigned long long m0 = none, m1 = none;
+        unsigned long long l0 = leaf_key[0], l1 = leaf_key[1], l2 = leaf_key[2];
+        unsigned long long m0 = ~0ull, m1 = ~0ull, m2 = ~0ull;
+        bool m2_new = false;                                   // the third merged node was made after its request:
+        unsigned long long m2_key = ~0ull;                     // this is its key
         for (int m = 0; m + 1 < alive; ++m) {
             unsigned long long pick[2];
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
-                const unsigned long long l2 = next_leaf + 2 < alive ? leaf_key[next_leaf + 2] : none;
-                const unsigned long long m2 = next_made + 2 < made ? key_of(bins + next_made + 2) : none;
-                if (l0 < m0) {
-                    pick[k] = l0;
-                    l0 = l1;
-                    l1 = l2;
-                    ++next_leaf;
-                } else {
-                    pick[k] = m0;
-                    m0 = m1;
-                    m1 = m2;
-                    ++next_made;
-                }
+                const unsigned long long third = m2_new ? m2_key : m2;
+                const bool leaf = l0 < m0;
+                pick[k] = leaf ? l0 : m0;
+                l0 = leaf ? l1 : l0;
+                l1 = leaf ? l2 : l1;
+                m0 = leaf ? m0 : m1;
+                m1 = leaf ? m1 : third;
+                next_leaf += leaf ? 1 : 0;
+                next_made += leaf ? 0 : 1;
+                l2 = leaf_key[next_leaf + 2];
+                m2 = made_key[next_made + 2];                  // (requested after the last node was stored)
+                m2_new = false;
             }
             const int node = bins + made;
             const unsigned long long sum = (pick[0] >> 9) + (pick[1] >> 9);
             const unsigned long long key = (sum << 9) | (unsigned long long)node;
-            weight[node] = sum;
+            made_key[made] = key;
             parent[(int)(pick[0] & 511ull)] = (short)node;
             parent[(int)(pick[1] & 511ull)] = (short)node;
-            // The new node is entry `made` of its queue: the first or second one not yet taken?
-            if (made == next_made) m0 = key;
-            else if (made == next_made + 1) m1 = key;
+            // The new node is entry `made` of its queue: one of the three that travel in registers?
+            const int ahead = made - next_made;
+            m0 = ahead == 0 ? key : m0;
+            m1 = ahead == 1 ? key : m1;
+            m2_new = ahead == 2;
+            m2_key = key;
             ++made;
         }
     }
     __syncthreads();
 
-    for (int c = lane; c < 256; c += 64) {
-        int depth = 0;
-        if (c < bins && weight[c] > 0) {
-            if (single) depth = 1;
-            else
-                for (int i = c; parent[i] >= 0; i = parent[i]) ++depth;
+    // A level's codeword length is its depth in the tree.  A lane climbs from its four levels side
+    // by side, so that the four chains of LDS reads overlap.
+    {
+        int at[4], depth[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = lane + 64 * q;
+            const bool occurs = c < bins && weight[c] > 0;
+            at[q] = occurs && !single ? c : -1;
+            depth[q] = occurs && single ? 1 : 0;
         }
-        depth = depth > kMaxLen ? kMaxLen : depth;             // cannot happen for counts that sum to <= 2^34
-        len_of[c] = (unsigned char)depth;
-        if (depth) atomicAdd(&len_count[depth], 1u);
+        for (;;) {
+            bool climbing = false;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int up = at[q] >= 0 ? parent[at[q]] : -1;
+                depth[q] += up >= 0 ? 1 : 0;
+                at[q] = up;
+                climbing = climbing || up >= 0;
+            }
+            if (!climbing) break;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int d = depth[q] > kMaxLen ? kMaxLen : depth[q];   // cannot happen for counts that sum to <= 2^34
+            len_of[lane + 64 * q] = (unsigned char)d;
+            if (d) atomicAdd(&len_count[d], 1u);
+        }
     }
     __syncthreads();
     if (lane == 0) {
