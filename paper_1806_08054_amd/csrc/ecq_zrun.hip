@@ -45,8 +45,10 @@ constexpr int kZBufWords = ((kZStep + 1) * kZMaxLen + 31 + 31) / 32 + 1;
 constexpr int kZKeepAt = ((kZStep + 1) * 24 + 31 + 31) / 32 + 1;
 constexpr int kZKeepMax = 18;
 static_assert(kZKeepAt + kZKeepMax * 64 <= kZBufWords, "the kept entries fit behind the short codewords");
-// A tile of at most this many bits is written in one piece (see k_zrun_write).
-constexpr unsigned int kZSparseTileBits = 2048;
+// A tile of at most this many bits is written in one piece (see k_zrun_write); the list of its
+// non-zero levels then sits in the wave's buffer behind the words such a tile can fill.
+constexpr unsigned int kZSparseTileBits = 4096;
+constexpr int kZListAt = (kZSparseTileBits + 31 + 31) / 32 + 2;
 
 static_assert(kZTile == 4096 && kZGroup == 64 && kZGroup % kZBlockTiles == 0, "a wave scans one group's 64 tile sizes");
 
@@ -311,6 +313,82 @@ __device__ __forceinline__ void tile_tokens(const TileCodes<R> &t, int lane, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// A sparse tile by way of a position list.  The walks above cost a wave as many rounds as its
+// busiest lane has non-zero levels, each round the whole token arithmetic for a few lanes.  A
+// tile with few non-zero levels is cheaper in two parts: every lane notes where its non-zero
+// levels are (a short loop body), at the places a wave prefix sum of the lanes' counts assigns,
+// so that the list is in position order; then the wave takes the list 64 entries at a time, a
+// token per lane: the zeros before a level are the distance to the entry before it.
+//   list[0] = 0 (stands for position -1), list[i + 1] = (position + 1) | index << 13 for the
+//   i-th non-zero level (index: its place among the 2s non-zero levels), list[T + 1] = the
+//   tile's element count + 1 (the closing entry: the zeros after the last level).
+// ---------------------------------------------------------------------------------------------
+constexpr int kZListMax = 1024;                                // non-zero levels of a tile the list holds
+constexpr int kZListWords = kZListMax + 2;
+static_assert(kZListAt + kZListWords <= kZBufWords, "the list fits the encoder's buffer behind a sparse tile's words");
+
+// Returns the number of non-zero levels T (wave-uniform), or -1 when the list cannot hold them
+// (then nothing was written).  Every lane of the wave must call it.
+template <int R>
+__device__ __forceinline__ int tile_list_build(const TileCodes<R> &t, int lane, int tile_elems, const ZrunShape &z,
+                                               unsigned int *__restrict__ list)
+{
+    constexpr int kStride = NonZero<R>::kStride;
+    uint32_t mask[4];
+    unsigned int count = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int valid_k = t.valid - 16 * k;
+        valid_k = valid_k < 0 ? 0 : (valid_k > 16 ? 16 : valid_k);
+        mask[k] = NonZero<R>::mask(t.q[k], z.s);
+        if (valid_k < 16) mask[k] &= (1u << (valid_k * kStride)) - 1u;
+        count += (unsigned int)__builtin_popcount(mask[k]);
+    }
+    const unsigned int incl = wave_inclusive_scan(count);
+    const int total = __builtin_amdgcn_readlane((int)incl, 63);
+    if (total > kZListMax) return -1;
+    unsigned int at = incl - count + 1u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t m = mask[k];
+        while (m) {
+            const int pos = __builtin_ctz(m) / kStride;
+            m &= m - 1u;
+            const int c = code_at<R>(t.q[k], pos);
+            list[at++] = (unsigned int)(lane * 64 + 16 * k + pos + 1) | ((unsigned int)(c < z.s ? c : c - 1) << 13);
+        }
+    }
+    if (lane == 0) {
+        list[0] = 0u;
+        list[total + 1] = (unsigned int)tile_elems + 1u;
+    }
+    wave_lds_sync();
+    return total;
+}
+
+// The tile's tokens, 64 list entries at a time: emit(have, closing, token, zs) once per round in
+// every lane; `have`: the lane has an entry; it stands for `zs` tokens "Z zeros" followed, unless
+// `closing`, by `token`.
+template <class Emit>
+__device__ __forceinline__ void tile_list_tokens(const unsigned int *__restrict__ list, int total, int lane,
+                                                 const ZrunShape &z, Emit &&emit)
+{
+    for (int j0 = 0; j0 <= total; j0 += 64) {
+        const int j = j0 + lane;
+        const bool have = j <= total;
+        const int at = have ? j : total;
+        const unsigned int cur = list[at + 1], prev = list[at];
+        const unsigned int gap = (cur & 0x1FFFu) - (prev & 0x1FFFu) - 1u;
+        // gap <= 4096: exact; the product needs 33 bits when Z = 1
+        unsigned int zs = (unsigned int)(((unsigned long long)gap * z.magic) >> 20);
+        const unsigned int rest = gap - zs * (unsigned int)z.Z;
+        const bool closing = j == total;
+        zs += closing && rest > 0u ? 1u : 0u;
+        emit(have, closing, (int)(rest * (unsigned int)z.two_s + (cur >> 13)), zs);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Token counts of every worker row.  A block walks units of 16 tiles of one row (a wave 4
 // consecutive tiles of each), counts into one LDS histogram per wave and adds its totals to the
 // row's counters once: long-lived blocks, because all blocks of a row end in the same global
@@ -324,6 +402,7 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
                                                        const int64_t count_stride)
 {
     __shared__ unsigned int hist[4][256];
+    __shared__ unsigned int lists[4][kZListWords];
     for (int c = threadIdx.x; c < 4 * 256; c += blockDim.x) (&hist[0][0])[c] = 0u;
     __syncthreads();
     const ZrunShape z = zrun_shape(a.s);
@@ -346,8 +425,16 @@ __global__ void __launch_bounds__(256) k_zrun_histogram(const Args a, const int6
             cd = cd_next;
             load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, cd_next);
             const int64_t rest = a.n - tile * kZTile;
-            tile_tokens<R>(cd, lane, rest < kZTile ? (int)rest : kZTile, z,
-                           [&](int token) { atomicAdd(&mine[token & 255], 1u); });
+            const int tile_elems = rest < kZTile ? (int)rest : kZTile;
+            const int levels = tile_list_build<R>(cd, lane, tile_elems, z, lists[wave]);
+            if (levels >= 0) {
+                tile_list_tokens(lists[wave], levels, lane, z, [&](bool have, bool closing, int token, unsigned int zs) {
+                    if (have && !closing) atomicAdd(&mine[token & 255], 1u);
+                    if (have && zs) atomicAdd(&mine[z.zz], zs);
+                });
+            } else {
+                tile_tokens<R>(cd, lane, tile_elems, z, [&](int token) { atomicAdd(&mine[token & 255], 1u); });
+            }
         }
     }
     __syncthreads();
@@ -368,6 +455,7 @@ __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint
                                                        uint32_t *__restrict__ tile_bits, const int64_t tile_stride)
 {
     __shared__ unsigned char len[256];
+    __shared__ unsigned int lists[4][kZListWords];
     const ZrunShape z = zrun_shape(a.s);
     const uint32_t p = blockIdx.y;
     for (int c = threadIdx.x; c < 256; c += blockDim.x) {
@@ -390,9 +478,17 @@ __global__ void __launch_bounds__(256) k_zrun_tile_bits(const Args a, const uint
         cd = cd_next;
         load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, cd_next);
         const int64_t rest = a.n - tile * kZTile;
+        const int tile_elems = rest < kZTile ? (int)rest : kZTile;
         unsigned int bits = 0;
-        tile_tokens<R>(cd, lane, rest < kZTile ? (int)rest : kZTile, z,
-                       [&](int token) { bits += len[token & 255]; });
+        const int levels = tile_list_build<R>(cd, lane, tile_elems, z, lists[wave]);
+        if (levels >= 0) {
+            const unsigned int len_zeros = len[z.zz];
+            tile_list_tokens(lists[wave], levels, lane, z, [&](bool have, bool closing, int token, unsigned int zs) {
+                bits += have ? zs * len_zeros + (closing ? 0u : (unsigned int)len[token & 255]) : 0u;
+            });
+        } else {
+            tile_tokens<R>(cd, lane, tile_elems, z, [&](int token) { bits += len[token & 255]; });
+        }
         const unsigned int incl = wave_inclusive_scan(bits);   // a tile has fewer than 2^32 bits
         if (lane == 63) tile_bits[(int64_t)p * tile_stride + tile] = incl;
     }
@@ -529,32 +625,38 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     // Words wholly inside the wave's range then leave with plain stores and their buffer word is
     // cleared for the next piece.  The last word of a piece, when partial, is carried into the
     // first word of the next; only the two ends of the wave's range use atomic ORs.
-    auto write_piece = [&](unsigned int nbits, auto &&walk, bool final_piece) {
-        const unsigned int incl_bits = wave_inclusive_scan(nbits);
-        const unsigned int total = (unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63);
-        const unsigned int shift = (unsigned int)(pos & 31ull);
-        const unsigned long long word0 = pos >> 5;
-        const unsigned long long end = pos + total;
-        const unsigned int span = (total + shift + 31u) >> 5;
-        const int words = (int)(span < (unsigned int)kZBufWords ? span : (unsigned int)kZBufWords);
-        {
-            const unsigned int at = shift + (incl_bits - nbits);
-            int w = (int)(at >> 5);
-            unsigned long long acc = 0;
-            unsigned int held = at & 31u;                      // bits of acc below the next free one
-            auto put = [&](unsigned int piece, unsigned int l) {   // l <= 32, held < 32
-                acc |= (unsigned long long)piece << held;
-                held += l;
-                if (held >= 32u) {
-                    if (w < words) atomicOr(&mine[w], (unsigned int)acc);
-                    ++w;
-                    acc >>= 32;
-                    held -= 32u;
-                }
-            };
-            walk(put);
-            if (held > 0u && acc != 0ull && w < words) atomicOr(&mine[w], (unsigned int)acc);
-        }
+    // (write_piece in three parts, so that a piece can also be placed token by token.)
+    unsigned int piece_shift = 0;
+    unsigned long long piece_word0 = 0, piece_end = 0;
+    int piece_words = 0;
+    auto begin_piece = [&](unsigned int total) {
+        piece_shift = (unsigned int)(pos & 31ull);
+        piece_word0 = pos >> 5;
+        piece_end = pos + total;
+        const unsigned int span = (total + piece_shift + 31u) >> 5;
+        piece_words = (int)(span < (unsigned int)kZBufWords ? span : (unsigned int)kZBufWords);
+    };
+    // Appends a lane's bits from bit `at` of the buffer on: put(bits, length) with length <= 32.
+    auto place = [&](unsigned int at, auto &&walk) {
+        int w = (int)(at >> 5);
+        unsigned long long acc = 0;
+        unsigned int held = at & 31u;                          // bits of acc below the next free one
+        auto put = [&](unsigned int piece, unsigned int l) {   // l <= 32, held < 32
+            acc |= (unsigned long long)piece << held;
+            held += l;
+            if (held >= 32u) {
+                if (w < piece_words) atomicOr(&mine[w], (unsigned int)acc);
+                ++w;
+                acc >>= 32;
+                held -= 32u;
+            }
+        };
+        walk(put);
+        if (held > 0u && acc != 0ull && w < piece_words) atomicOr(&mine[w], (unsigned int)acc);
+    };
+    auto end_piece = [&](bool final_piece) {
+        const int words = piece_words;
+        const unsigned long long word0 = piece_word0, end = piece_end;
         wave_lds_sync();
         const bool has_tail = (end & 31ull) != 0ull;
         if (words > 0) {
@@ -577,6 +679,12 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
         wave_lds_sync();                                       // the buffer is clear again for the next piece
         pos = end;
     };
+    auto write_piece = [&](unsigned int nbits, auto &&walk, bool final_piece) {
+        const unsigned int incl_bits = wave_inclusive_scan(nbits);
+        begin_piece((unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63));
+        place(piece_shift + (incl_bits - nbits), walk);
+        end_piece(final_piece);
+    };
     // One token's codeword, in at most two parts of at most 32 bits.
     auto put_token = [&](auto &put, int token) {
         if (all_short) {
@@ -594,14 +702,14 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
         }
     };
 
-    // Sparse tiles (at most half a bit per element) go a whole tile at a time, 64 consecutive
+    // Sparse tiles (at most one bit per element) go a whole tile at a time, 64 consecutive
     // elements per lane: with few tokens the cost of a piece is its scans and its bookkeeping,
-    // and a tile pays them once instead of four times (-13 % at 0.3 bits per element).  Denser
-    // tiles go in steps of 1024 elements, whose bits fit the buffer whatever the code is, and
-    // whose tokens' table entries can be kept between the two walks.
-    // (Ternary codes only: wider codes spend their time finding the non-zero levels of every
-    // element, which a whole tile does not make cheaper.)
-    bool whole_tiles = R == 2;
+    // and a tile pays them once instead of four times; and the tokens are placed from the list
+    // of the tile's non-zero levels, a token per lane, instead of by two walks that cost the wave
+    // as many rounds as its busiest lane has levels.  Denser tiles go in steps of 1024 elements,
+    // whose bits fit the buffer whatever the code is, and whose tokens' table entries can be kept
+    // between the two walks.
+    bool whole_tiles = true;
     for (int i = 0; i < kZWaveTiles; ++i) {
         const unsigned int bits_i =
             (unsigned int)__builtin_amdgcn_readlane((int)my_bits, (int)((first - group * kZGroup + i) & 63));
@@ -618,6 +726,31 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
             load_tile_codes<R>(crow, a.row_bytes, a.n, (tile + 1) * kZTile + lane * 64, tc_next);
             const int64_t rest = a.n - tile * kZTile;
             const int tile_elems = rest < kZTile ? (int)rest : kZTile;
+            unsigned int *__restrict__ list = mine + kZListAt;
+            const int levels = tile_list_build<R>(tc, lane, tile_elems, z, list);
+            if (levels >= 0) {
+                // By the position list: the tile's size is known from pass 1, a wave prefix sum
+                // per 64 entries places every lane's token (with the "Z zeros" before it).
+                const unsigned int tile_total = (unsigned int)__builtin_amdgcn_readlane(
+                    (int)my_bits, (int)((first - group * kZGroup + i) & 63));
+                begin_piece(tile_total);
+                unsigned int placed = piece_shift;
+                const unsigned int len_zeros = tab.len[z.zz];
+                tile_list_tokens(list, levels, lane, z, [&](bool have, bool closing, int token, unsigned int zs) {
+                    const unsigned int own = closing ? 0u : (unsigned int)tab.len[token & 255];
+                    const unsigned int nbits = have ? zs * len_zeros + own : 0u;
+                    const unsigned int incl_bits = wave_inclusive_scan(nbits);
+                    place(placed + (incl_bits - nbits), [&](auto &put) {
+                        if (have) {
+                            for (unsigned int k = 0; k < zs; ++k) put_token(put, z.zz);
+                            if (!closing) put_token(put, token);
+                        }
+                    });
+                    placed += (unsigned int)__builtin_amdgcn_readlane((int)incl_bits, 63);
+                });
+                end_piece(tile == last_tile);
+                continue;
+            }
             const int run = tile_run_in<R>(tc, lane, z);
             unsigned int nbits = 0;
             tile_walk<R>(tc, lane, tile_elems, run, z, [&](int token) { nbits += tab.packed[token & 255] >> 24; });
