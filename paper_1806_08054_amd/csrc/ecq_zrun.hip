@@ -611,7 +611,16 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     const unsigned int excl_tile = incl - my_bits;
     const unsigned long long range_start =
         group_start + (unsigned int)__builtin_amdgcn_readlane((int)excl_tile, (int)(first - group * kZGroup));
-    for (int j = lane; j < kZBufWords; j += 64) mine[j] = 0u;
+    // Sparse tiles (at most one bit per element) go a whole tile at a time; see below.
+    bool whole_tiles = true;
+    for (int i = 0; i < kZWaveTiles; ++i) {
+        const unsigned int bits_i =
+            (unsigned int)__builtin_amdgcn_readlane((int)my_bits, (int)((first - group * kZGroup + i) & 63));
+        whole_tiles = whole_tiles && bits_i <= kZSparseTileBits;
+    }
+    // The buffer's words that codewords are ORed into start out as zeros (and are cleared again
+    // as they leave): all of them, or only the few a sparse tile can fill.
+    for (int j = lane; j < (whole_tiles ? kZListAt : kZBufWords); j += 64) mine[j] = 0u;
     wave_lds_sync();
 
     unsigned long long pos = range_start;                      // bit offset of the current piece
@@ -709,12 +718,6 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
     // as many rounds as its busiest lane has levels.  Denser tiles go in steps of 1024 elements,
     // whose bits fit the buffer whatever the code is, and whose tokens' table entries can be kept
     // between the two walks.
-    bool whole_tiles = true;
-    for (int i = 0; i < kZWaveTiles; ++i) {
-        const unsigned int bits_i =
-            (unsigned int)__builtin_amdgcn_readlane((int)my_bits, (int)((first - group * kZGroup + i) & 63));
-        whole_tiles = whole_tiles && bits_i <= kZSparseTileBits;
-    }
     if (whole_tiles) {
         TileCodes<R> tc, tc_next;
         load_tile_codes<R>(crow, a.row_bytes, a.n, first * kZTile + lane * 64, tc_next);
