@@ -409,3 +409,28 @@ def test_zrun_codes_beyond_the_grid_count_as_level_zero(E, s):
                         zb.streams[0, : (total + 7) // 8].cpu().numpy()))
     for got, ref in zip(results[0], results[1]):
         assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("s", [1, 2, 4, 9])
+def test_zrun_tiles_around_the_encoder_route_limits(E, s):
+    """The encoder takes a tile by a list of its non-zero levels while it has at most 1024 of
+    them, and a wave writes whole tiles while each of its four tiles has at most 4096 stream
+    bits: tiles with exactly 0, 1, 1023, 1024, 1025 and 4096 non-zero levels, side by side in
+    one wave and on their own, with the levels spread evenly, bunched at the tile's start and at
+    its end, and a ragged last tile."""
+    rng = np.random.default_rng(100 + s)
+    counts = [1024, 1025, 1023, 0, 4096, 1, 1024, 1024, 1024, 1024, 0, 0, 0, 0, 1023, 1025, 2048, 600, 1024, 300]
+    N = len(counts) * 4096 - 777
+    q = np.zeros((2, N), np.int8)
+    for p in range(2):
+        for t, c in enumerate(counts):
+            lo, hi = t * 4096, min((t + 1) * 4096, N)
+            c = min(c, hi - lo)
+            if p == 0:
+                where = rng.choice(hi - lo, c, replace=False)               # spread
+            elif t % 2 == 0:
+                where = np.arange(c)                                        # bunched at the start
+            else:
+                where = (hi - lo) - 1 - np.arange(c)                        # bunched at the end
+            q[p, lo + where] = rng.integers(1, s + 1, c) * rng.choice([-1, 1], c)
+    _roundtrip(E, q, s)
