@@ -34,7 +34,7 @@ constexpr int kZWaveTiles = kZBlockTiles / 4;                  // consecutive ti
 constexpr int kZWaveSteps = kZWaveTiles * kZSteps;
 constexpr int kZMaxLen = 63;                                   // longest codeword handled
 constexpr int kZFastBits = 12;                                 // decode: direct table on 12 stream bits
-constexpr int kZRingWords = 16;                                // decode: words of a lane's output window
+// decode: a lane's output window has 16 or 32 words (template parameter of k_zrun_decode)
 // Words of LDS a wave needs for one step: 1024 elements send at most 1025 tokens (every element
 // at most one, plus the tile's closing token) of at most 63 bits, plus the up-to-31-bit shift
 // that aligns the buffer with the stream's words.
@@ -823,7 +823,7 @@ __global__ void __launch_bounds__(256) k_zrun_write(const Args a, const uint8_t 
 //    count over 20 bounds that every lane keeps in registers (in a wave of 64 tiles some lane
 //    meets a rare, long codeword in most rounds, so this route has to be short); beyond 32 bits
 //    one bit at a time;
-//  - the output is a window of 16 words per lane in LDS that starts out as codes of level 0
+//  - the output is a window of W = 16 or 32 words per lane in LDS that starts out as codes of level 0
 //    (a message is mostly zeros); a token moves the output position past its zeros and XORs
 //    its level's code into the window.  The lanes of a wave go through their tiles window by
 //    window together, so a window leaves with one store sequence for all 64 tiles (lanes that
@@ -949,7 +949,7 @@ __device__ __forceinline__ void fill_zdecode_table(ZDecodeTable &tab, const uint
     }
 }
 
-template <int R>
+template <int R, int W>
 __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t *__restrict__ lengths,
                                                     const unsigned long long *__restrict__ codewords,
                                                     const int64_t table_stride, const int64_t tiles,
@@ -961,7 +961,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
 {
     constexpr int kPeriod = R == 2 || R == 4 || R == 8 ? 1 : (R == 6 ? 3 : R);   // words after which zero_words repeat
     __shared__ ZDecodeTable tab;
-    __shared__ unsigned int out_ring[(kZRingWords + 1) * 256];
+    __shared__ unsigned int out_ring[(W + 1) * 256];
     const ZrunShape z = zrun_shape(a.s);
     const uint32_t p = blockIdx.y;
     fill_zdecode_table<R>(tab, lengths + (int64_t)p * table_stride, codewords + (int64_t)p * table_stride, z);
@@ -1040,7 +1040,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
         in_batch = 4;
     };
 
-    // The output window: words [w0, w0 + kZRingWords) of the tile's part of the row, the same w0
+    // The output window: words [w0, w0 + W) of the tile's part of the row, the same w0
     // for every lane of the wave.  Word k of lane t at [k][t]: whatever words the lanes of a wave
     // touch, they lie in 64 different banks.  When codes can straddle two words the window has
     // one more word, the first of the next window: an element belongs to the window in which it
@@ -1049,12 +1049,12 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     unsigned int *__restrict__ ring = out_ring + threadIdx.x;
     auto start_window = [&](int w0) {                          // w0 is the same for the whole wave
         if constexpr (kStraddle) {
-            ring[0] = w0 > 0 ? ring[kZRingWords * 256] : tab.zero_words[0];
+            ring[0] = w0 > 0 ? ring[W * 256] : tab.zero_words[0];
 #pragma unroll
-            for (int k = 1; k <= kZRingWords; ++k) ring[k * 256] = tab.zero_words[(w0 + k) % kPeriod];
+            for (int k = 1; k <= W; ++k) ring[k * 256] = tab.zero_words[(w0 + k) % kPeriod];
         } else {
 #pragma unroll
-            for (int k = 0; k < kZRingWords; ++k)
+            for (int k = 0; k < W; ++k)
                 ring[k * 256] = tab.zero_words[kPeriod == 1 ? 0 : (w0 + k) % kPeriod];
         }
     };
@@ -1062,7 +1062,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     // formed from e, so an element outside the window (always with d == 0) touches some row of
     // the lane's own.
     auto put = [&](unsigned int e, unsigned int d) {
-        const unsigned int bit = e * R, row = (bit >> 5) & (unsigned int)(kZRingWords - 1);
+        const unsigned int bit = e * R, row = (bit >> 5) & (unsigned int)(W - 1);
         if constexpr (kStraddle) {
             const unsigned long long v = (unsigned long long)d << (bit & 31u);
             atomicXor(&ring[row * 256], (unsigned int)v);
@@ -1082,14 +1082,14 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     const bool rows_on_16 = (reinterpret_cast<uintptr_t>(crow) & 15u) == 0u;   // block-uniform
     auto leave_window = [&](const int w0) {
         // The window leaves: whole, or the last words of a ragged tile with its pad bits zero.
-        const int count = tile_words - w0 < kZRingWords ? tile_words - w0 : kZRingWords;
+        const int count = tile_words - w0 < W ? tile_words - w0 : W;
         if (count > 0) {
             if (w0 + count == tile_words && (tile_bits_out & 31))
                 ring[(count - 1) * 256] &= (1u << (tile_bits_out & 31)) - 1u;
-            if (count == kZRingWords && out_byte + 4 * kZRingWords <= a.row_bytes) {
+            if (count == W && out_byte + 4 * W <= a.row_bytes) {
                 if (rows_on_16) {
 #pragma unroll
-                    for (int q = 0; q < kZRingWords / 4; ++q) {
+                    for (int q = 0; q < W / 4; ++q) {
                         uint4 v;
                         v.x = ring[(4 * q + 0) * 256];
                         v.y = ring[(4 * q + 1) * 256];
@@ -1099,7 +1099,7 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
                     }
                 } else {
 #pragma unroll
-                    for (int k = 0; k < kZRingWords; ++k)
+                    for (int k = 0; k < W; ++k)
                         reinterpret_cast<uint32_t *>(crow + out_byte)[k] = ring[k * 256];
                 }
             } else {
@@ -1139,8 +1139,8 @@ __global__ void __launch_bounds__(256) k_zrun_decode(const Args a, const uint8_t
     unsigned long long held_bits = 0ull;
     start_window(0);
 #pragma unroll 1
-    for (int w0 = 0; w0 < kZTile * R / 32; w0 += kZRingWords) {
-        const int w_end = w0 + kZRingWords;
+    for (int w0 = 0; w0 < kZTile * R / 32; w0 += W) {
+        const int w_end = w0 + W;
         const int begin_here = (w_end * 32 + R - 1) / R;     // elements that begin before the window's end
         const unsigned int limit = (unsigned int)(begin_here < tile_elems ? begin_here : tile_elems);
         if (held_word >= 0 && held_word < w_end) {
@@ -1281,11 +1281,23 @@ hipError_t launch_zrun_decode(const Args &a, const uint8_t *lengths, const unsig
     const int64_t held = (int64_t)256 * 4 * 2;
     int lanes_shift = 0;
     while (lanes_shift < 3 && cdiv(tiles, kZGroup >> (lanes_shift + 1)) * a.workers <= held) ++lanes_shift;
-    const dim3 grid(cdiv(cdiv(tiles, kZGroup) << lanes_shift, 4), (unsigned)a.workers);
-#define CALL(RR)                                                                                                    \
-    hipLaunchKernelGGL((k_zrun_decode<RR>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride, tiles, \
-                       tile_bits, tile_stride, group_offsets, group_stride, streams, stream_stride_words,           \
-                       stream_stride_words, lanes_shift)
+    const unsigned row_blocks = cdiv(cdiv(tiles, kZGroup) << lanes_shift, 4);
+    const dim3 grid(row_blocks, (unsigned)a.workers);
+    // Windows of 32 words: half as many store sequences, each a wait for the stores before it
+    // (a wave's loads and stores share one counter), but 52 KB of LDS instead of 36: three blocks
+    // per compute unit instead of four.  A message that the chip holds at once with four blocks
+    // per unit but not with three keeps the windows of 16 words.
+    const int64_t blocks = (int64_t)row_blocks * a.workers;
+    const bool narrow = blocks > 256 * 3 && blocks <= 256 * 4;
+#define CALL(RR)                                                                                                       \
+    if (narrow)                                                                                                        \
+        hipLaunchKernelGGL((k_zrun_decode<RR, 16>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride,  \
+                           tiles, tile_bits, tile_stride, group_offsets, group_stride, streams, stream_stride_words, \
+                           stream_stride_words, lanes_shift);                                                        \
+    else                                                                                                               \
+        hipLaunchKernelGGL((k_zrun_decode<RR, 32>), grid, dim3(256), 0, stream, a, lengths, codewords, table_stride,  \
+                           tiles, tile_bits, tile_stride, group_offsets, group_stride, streams, stream_stride_words, \
+                           stream_stride_words, lanes_shift)
     ECQ_DISPATCH_R(a.r, CALL)
 #undef CALL
     return hipGetLastError();

@@ -319,10 +319,11 @@ def test_zrun_full_size(E, name, rows):
               f"fixed length {E.code_bits(s)}", flush=True)
 
 
-@pytest.mark.parametrize("P,tiles,s", [(1, 300, 1), (2, 10_000, 4), (2, 20_000, 1), (3, 50_000, 2)])
+@pytest.mark.parametrize("P,tiles,s", [(1, 300, 1), (2, 10_000, 4), (2, 20_000, 1), (3, 50_000, 2), (2, 100_000, 1)])
 def test_zrun_decoder_tiles_per_wave(E, P, tiles, s):
     """The decoder gives a wave 8, 16, 32 or 64 tiles depending on how many tiles the whole
-    message has (the four cases, in that order), the per-level decoder between 8 and 64: every
+    message has (the first four cases, in that order; the last one is a message of the size at
+    which it takes output windows of 16 words instead of 32), the per-level decoder between 8 and 64: every
     setting decodes the message it was given, through groups of 64 tiles that several waves
     share and a ragged last tile.  Levels come straight from the seeded generator; the encoder
     that feeds the decoder is compared with the oracle elsewhere, here on row 0."""
